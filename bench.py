@@ -1,0 +1,164 @@
+"""Benchmark: full backpropagation passes per second on one MI355X.
+
+A step is one pass of the whole hot path -- forward (x),(z),(a), then the leapfrogged backward pass
+(bp1)-(bp4) with k workers -- over one seeded synthetic input that is already resident in HBM.
+Prints ONE JSON line.  The roofline object prices the backward pass against the HBM peak (B = 1) or
+the MFMA peak (minibatch); the cpu_baseline object is the CPU oracle timed on this machine's cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+
+def algorithmic_work(spec):
+    """Per backward pass.  B = 1: bytes the method must move, 4 N^2 per matrix read or written:
+    M-1 chain reads of w^{l+1} plus M writes of nabla_w^l (vectors are O(N), ignored).
+    Minibatch: 2 N^2 B flops for each of the M-1 chain and M gradient contractions."""
+    M = spec.L - 1
+    if spec.B == 1:
+        es = 4 if spec.dtype == "f32" else 2
+        return {"bound": "hbm", "bwd": (es * (M - 1) + 4 * M) * spec.N * spec.N,
+                "fwd": es * M * spec.N * spec.N, "unit": "GB/s", "peak": HBM_PEAK_GBS, "scale": 1e9}
+    f = 2.0 * spec.N * spec.N * spec.B
+    return {"bound": "mfma", "bwd": f * (2 * M - 1), "fwd": f * M, "unit": "TFLOP/s",
+            "peak": MFMA_PEAK_TFLOPS[spec.dtype], "scale": 1e12}
+
+
+def cpu_baseline(net, budget_s=12.0):
+    """The oracle as it stands, timed on the host: whole passes for the small nets; for nets whose
+    pass takes minutes, two full layers (forward + chain + gradient) scaled to the whole net."""
+    import numpy as np
+    from oracle import backprop as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    s = net.spec
+    M = s.L - 1
+    flops_pass = 6.0 * s.N * s.N * s.B * M
+    if flops_pass < 5e10:
+        w = {l: net.w(l) for l in range(2, s.L + 1)}
+        b = {l: net.b(l) for l in range(2, s.L + 1)}
+        x, y = net.x(), net.y()
+        O.full_pass(w, b, x, y, s.L)
+        n, t0 = 0, time.perf_counter()
+        while True:
+            O.full_pass(w, b, x, y, s.L)
+            n += 1
+            dt = time.perf_counter() - t0
+            if dt > budget_s or n >= 200:
+                break
+        return {"value": n / dt, "unit": "passes/s", "cores": cores, "kind": "oracle",
+                "sample": f"{n} full forward+backward passes of the same net"}
+    # two layers at full width, scaled by M / 2
+    sub_L = 3
+    w = {l: net.w(l) for l in (2, 3)}
+    b = {l: net.b(l) for l in (2, 3)}
+    x, y = net.x(), net.y()
+    t0 = time.perf_counter()
+    O.full_pass(w, b, x, y, sub_L)
+    dt = time.perf_counter() - t0
+    return {"value": 1.0 / (dt * M / 2.0), "unit": "passes/s", "cores": cores, "kind": "oracle",
+            "sample": f"extrapolated from 2 of {M} layers at full N, B (one pass of a 3-layer net, x{M / 2:.1f})"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--k", type=int, default=0, help="workers (0 = the configuration's largest k)")
+    ap.add_argument("--sched", default="auto", choices=["auto", "streams", "persistent"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1801_04928_amd as P
+    from lf_inputs import config_net
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    net = config_net(args.config, cache=args.config in ("cfg1", "cfg2"))
+    s = net.spec
+    k = args.k or max(s.ks)
+    steps = args.steps if args.config in ("cfg1", "cfg2") else min(args.steps, 20)
+    warmup = args.warmup if args.config in ("cfg1", "cfg2") else min(args.warmup, 3)
+
+    g = P.LeapfrogNet(s.L, s.N, s.B, s.dtype)
+    g.load(net)
+    g.set_schedule({"auto": P.LF_SCHED_AUTO, "streams": P.LF_SCHED_STREAMS,
+                    "persistent": P.LF_SCHED_PERSISTENT}[args.sched])
+    torch.cuda.synchronize()
+
+    for _ in range(warmup):
+        g.forward()
+        g.backward(k)
+    torch.cuda.synchronize()
+
+    # Timed region: exactly `steps` passes.  Events on the stream the passes are enqueued on
+    # (torch's current stream, handed to the library) bracket each backward pass.
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
+           torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ev[i][0].record()
+        g.forward()
+        ev[i][1].record()
+        g.backward(k)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall = t1 - t0
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+
+    work = algorithmic_work(s)
+    achieved = work["bwd"] / (bwd_ms * 1e-3) / work["scale"]
+    out = {
+        "metric": "full backprop passes/sec at 1 GPU",
+        "value": steps / wall,
+        "unit": "passes/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": wall / steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": s.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{s.name}: sigmoid MLP L={s.L} N={s.N} B={s.B} {s.dtype}, k={k}, seed {s.seed}",
+                   "k": k, "schedule": args.sched, "weight_matrices": s.L - 1},
+        "fwd_ms": fwd_ms,
+        "bwd_ms": bwd_ms,
+        "roofline": {"bound": work["bound"], "kernel": "backward pass (bp1)-(bp4)", "achieved": achieved,
+                     "peak": work["peak"], "unit": work["unit"], "frac": achieved / work["peak"],
+                     "traffic": None,
+                     "fwd_achieved": work["fwd"] / (fwd_ms * 1e-3) / work["scale"]},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(net)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,134 @@
+/* lf.h -- C ABI of the leapfrogging backpropagation library for one MI355X (gfx950).
+ *
+ * One full backpropagation pass through an L-layer, width-N, fully connected
+ * sigmoid network, in the paper's notation (section 2): layers are numbered
+ * 1..L, a^1 = x^1, weights w^l (N x N) and biases b^l (N) exist for l = 2..L.
+ * The serial chain -- forward z^l = w^l a^{l-1} + b^l, a^l = sigma(z^l), and
+ * backward delta^l = ((w^{l+1})^T delta^{l+1}) (.) sigma'(z^l) -- is computed
+ * once; the gradient terms nabla_b^l = delta^l and nabla_w^l = delta^l (a^{l-1})^T
+ * are taken off that chain and computed by k interleaved workers, worker
+ * (L - l) mod k owning layer l (section 3, Algorithm 1).
+ *
+ * Conventions
+ *   - Every `l` at this boundary is the paper's layer index, 2 <= l <= L.
+ *     Arrays of per-layer pointers have L-1 entries; entry i belongs to layer i+2.
+ *   - Matrices are row-major: w^l[j][k] = w[j*N + k] is the weight into neuron j
+ *     of layer l from neuron k of layer l-1 (the index order of eq. (bp4)).
+ *   - A minibatch of B samples is sample-major: x[b*N + n].  B = 1 is the paper's
+ *     single-sample case.  With B > 1 the cost and both gradients are summed
+ *     (not averaged) over the samples.
+ *   - Storage type `dt` applies to w^l, x^1, y and the stored activations a^l.
+ *     b^l, delta^l, nabla_b^l and nabla_w^l are always fp32.  All accumulation
+ *     is fp32.  bfloat16 values are produced with round-to-nearest-even.
+ *   - All data pointers are DEVICE pointers, 16-byte aligned, BORROWED: the
+ *     caller owns every buffer (weights, inputs, workspace, gradient buffers)
+ *     and keeps it alive while the handle uses it.  Arrays of pointers
+ *     (`const void* const*`) are HOST arrays, read during the call only.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     lf_forward and lf_backward_leapfrog only enqueue work and return; the work
+ *     is ordered on that stream: anything enqueued on it afterwards sees the
+ *     finished results (the "join" of Algorithm 1).
+ *   - Every function returns an lf_status; nothing throws, nothing aborts.
+ *     After a non-OK status lf_last_error() describes it.  A handle is not
+ *     thread-safe; different handles are independent.
+ *   - Shape limits: N a multiple of 4 (fp32) or 8 (bf16) so rows stay 16-byte
+ *     aligned; 2 <= L <= 4096; 1 <= B; 1 <= k <= L-1.
+ */
+#ifndef LF_H
+#define LF_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LF_OK = 0,
+    LF_EINVAL = 1,        /* bad argument: shape, k, null or misaligned pointer, small workspace */
+    LF_ESTATE = 2,        /* call out of order: parameters/buffers not set, backward before forward */
+    LF_ENOMEM = 3,        /* host allocation failed */
+    LF_EHIP = 4,          /* a HIP call failed (no device, launch error, ...) */
+    LF_EUNSUPPORTED = 5   /* valid request this build cannot serve */
+} lf_status;
+
+typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
+
+/* Cost function C.  The paper leaves C open ("let C be the cost function");
+ * quadratic: C = 1/2 sum_b ||a^L_b - y_b||^2, hence nabla_a^L C = a^L - y. */
+typedef enum { LF_COST_QUADRATIC = 0 } lf_cost;
+
+/* How the k workers of section 3 are realised on the one GPU. */
+typedef enum {
+    LF_SCHED_AUTO = 0,        /* the library picks (persistent where supported) */
+    LF_SCHED_STREAMS = 1,     /* chain on the caller's stream, k worker streams fed by per-layer events */
+    LF_SCHED_PERSISTENT = 2   /* one persistent kernel, k workgroup partitions fed by per-layer ready flags */
+} lf_sched;
+
+typedef struct lf_net lf_net;   /* opaque handle */
+
+/* Bytes of device workspace a net of this shape needs (activations a^2..a^L,
+ * errors delta^2..delta^L, reduction partials, ready flags).  0 if the shape is
+ * invalid. */
+size_t lf_workspace_bytes(int L, int N, int B, lf_dtype dt);
+
+/* Create a handle.  `workspace` is caller-owned device memory of at least
+ * lf_workspace_bytes() bytes, 256-byte aligned; its contents need not be
+ * initialised.  Pure host work: touches no device.  LF_EINVAL on a bad shape,
+ * null/misaligned/small workspace. */
+lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost,
+                    void* workspace, size_t workspace_bytes);
+
+/* Register w^l and b^l, l = 2..L (section 2).  w[i]: N*N elements of type dt;
+ * b[i]: N floats.  The pointers are kept; the data may change between passes. */
+lf_status lf_set_params(lf_net* net, const void* const* w, const void* const* b);
+
+/* Register where nabla_w^l (N*N floats) and nabla_b^l (N floats) are written,
+ * l = 2..L.  Each pass overwrites them (never accumulates). */
+lf_status lf_set_grad_buffers(lf_net* net, float* const* nabla_w, float* const* nabla_b);
+
+/* Select the worker realisation for later lf_backward_leapfrog calls.
+ * LF_EUNSUPPORTED if the shape/type has no such path. */
+lf_status lf_set_schedule(lf_net* net, lf_sched sched);
+
+/* Forward pass, eqs. (x), (z), (a): a^1 = x^1; for l = 2..L
+ * z^l = w^l a^{l-1} + b^l, a^l = sigma(z^l).  x1: [B][N] of type dt, aliased as
+ * a^1 (it must stay valid and unchanged until the backward pass has finished).
+ * z^l is not stored (sigma' is formed from a^l). */
+lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream);
+
+/* Backward pass with k interleaved workers (section 3, Algorithm 1).
+ * Eq. (bp1) delta^L = (a^L - y) (.) sigma'(z^L); eq. (bp2) down the chain, once;
+ * eqs. (bp3), (bp4) for layer l by worker (L - l) mod k as soon as delta^l is
+ * ready.  k = 1 is the sequential pass (gradients in line with the chain).
+ * The gradients do not depend on k, bit for bit.  y: [B][N] of type dt.
+ * LF_ESTATE unless lf_forward has run since the last lf_set_params;
+ * LF_EINVAL unless 1 <= k <= L-1. */
+lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stream);
+
+/* Device pointers to nabla_w^l and nabla_b^l of the last backward pass (the
+ * registered buffers).  Valid to read once the stream of that pass has reached
+ * the end of it.  LF_ESTATE if no backward pass has been enqueued. */
+lf_status lf_grads(lf_net* net, int l, const float** nabla_w, const float** nabla_b);
+
+/* Device pointers to the stored a^l ([B][N], type dt; l = 1..L, l = 1 is x^1) and
+ * delta^l ([B][N] fp32; l = 2..L, NULL for l = 1).  For tests of the identity
+ * nabla_w^l[j][k] = a^{l-1}_k delta^l_j (eq. (bp4)).  Either out pointer may be NULL. */
+lf_status lf_activations(lf_net* net, int l, const void** a_l, const float** delta_l);
+
+/* Worker that owns layer l's gradients with k workers: (L - l) mod k, the thread
+ * rule of Algorithm 1 extended to the top k layers.  -1 on invalid arguments.
+ * Pure host function. */
+int lf_schedule_worker(int L, int k, int l);
+
+/* Description of the last failure on this handle (or of the last failed
+ * lf_create when net is NULL).  Owned by the library; never NULL. */
+const char* lf_last_error(const lf_net* net);
+
+/* Release the handle (streams, events; never the caller's buffers).  NULL is fine. */
+void lf_destroy(lf_net* net);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LF_H */

@@ -1,0 +1,370 @@
+// Minibatch (B > 1) kernels: the three per-layer contractions of the pass as LDS-tiled MFMA GEMMs.
+//
+//   forward (z),(a):  A_out[b][j] = sigma( sum_k A_in[b][k]  W[j][k]  + bias[j] )
+//   chain   (bp2):    D_l[b][k]   = ( sum_j D_next[b][j] W_next[j][k] ) * A_l[b][k] (1 - A_l[b][k])
+//   grads   (bp4):    nabla_w[j][k] = sum_b D[b][j] A_prev[b][k]        (bp3): nabla_b[j] = sum_b D[b][j]
+//
+// All three are  C[m][n] = sum_q P(m,q) Q(n,q)  with operands that are either contiguous along the
+// contraction index q ("QC": element (i,q) at p[i*ld + q]) or along their own index ("IC": element
+// (i,q) at p[q*ld + i]).  forward: P = A_in (QC), Q = W (QC).  chain: P = D_next (QC), Q = W_next (IC).
+// grads: P = D (IC), Q = A_prev (IC).  Accumulation is fp32 in the MFMA accumulators, in an order fixed
+// by (N, B) alone, so results do not depend on k or on the launch.
+#include "lf_internal.h"
+
+namespace lf {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int BM = 128, BN = 128;          // output tile of a workgroup; 2 x 2 waves of 64 x 64
+
+__host__ __device__ constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+enum Epilogue { EPI_RAW = 0, EPI_SIGMOID = 1, EPI_SIGMA_PRIME = 2, EPI_GRAD = 3 };
+
+template <typename T> struct Tile;
+template <> struct Tile<float> {
+    static constexpr int BK = 32;
+    static constexpr int LDA = BM + 4;     // LDS is [q][i]: a lane reads one float per MFMA, lanes along i
+    static constexpr int ELEMS = BK * LDA;
+};
+template <> struct Tile<__bf16> {
+    static constexpr int BK = 64;
+    static constexpr int LDA = BK + 8;     // LDS is [i][q]: a lane reads 8 consecutive q (16 bytes)
+    static constexpr int ELEMS = BM * LDA;
+};
+
+struct GemmArgs {
+    const void* P;  int ldp;               // rows of P index m
+    const void* Q;  int ldq;               // rows of Q index n
+    int M, Nn, K;                          // C is M x Nn, contraction length K
+    int k_tiles_per_split;                 // split-K: blockIdx.z handles this many BK tiles
+    float* raw;                            // EPI_RAW: [splits][M][Nn] fp32
+    const float* bias;                     // EPI_SIGMOID: [Nn]
+    const void* act;                       // EPI_SIGMA_PRIME: A_l [M][Nn], type T
+    void* out;                             // EPI_SIGMOID: T [M][Nn]; EPI_SIGMA_PRIME / EPI_GRAD: float [M][Nn]
+    void* out_bf;                          // EPI_SIGMA_PRIME with bf16: bfloat16 copy of out (or null)
+};
+
+// ---- global -> register staging ---------------------------------------------------------------
+// Each thread stages 4 x 16 bytes per operand and tile.
+template <typename T, bool IC> struct Stage;
+
+template <> struct Stage<float, false> {   // [i][q], float4 along q; 8 threads cover 32 q of one row
+    v4f r[4];
+    __device__ void load(const float* p, int ld, int i0, int q0, int I, int Kq) {
+        const int t = threadIdx.x, qv = (t & 7) * 4;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = (t >> 3) + 32 * u;
+            const bool ok = (i0 + i < I) && (q0 + qv < Kq);
+            r[u] = ok ? *reinterpret_cast<const v4f*>(p + (size_t)(i0 + i) * ld + q0 + qv)
+                      : v4f{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    __device__ void store(float* s) const {
+        const int t = threadIdx.x, qv = (t & 7) * 4;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = (t >> 3) + 32 * u;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) s[(qv + c) * Tile<float>::LDA + i] = r[u][c];
+        }
+    }
+};
+template <> struct Stage<float, true> {    // [q][i], float4 along i; 32 threads cover 128 i of one q
+    v4f r[4];
+    __device__ void load(const float* p, int ld, int i0, int q0, int I, int Kq) {
+        const int t = threadIdx.x, iv = (t & 31) * 4;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = (t >> 5) + 8 * u;
+            const bool ok = (q0 + q < Kq) && (i0 + iv < I);
+            r[u] = ok ? *reinterpret_cast<const v4f*>(p + (size_t)(q0 + q) * ld + i0 + iv)
+                      : v4f{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    __device__ void store(float* s) const {
+        const int t = threadIdx.x, iv = (t & 31) * 4;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = (t >> 5) + 8 * u;
+            *reinterpret_cast<v4f*>(s + q * Tile<float>::LDA + iv) = r[u];
+        }
+    }
+};
+template <> struct Stage<__bf16, false> {  // [i][q], 8 bf16 along q; 8 threads cover 64 q of one row
+    v8bf r[4];
+    __device__ void load(const __bf16* p, int ld, int i0, int q0, int I, int Kq) {
+        const int t = threadIdx.x, qv = (t & 7) * 8;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = (t >> 3) + 32 * u;
+            const bool ok = (i0 + i < I) && (q0 + qv < Kq);
+            if (ok) r[u] = *reinterpret_cast<const v8bf*>(p + (size_t)(i0 + i) * ld + q0 + qv);
+            else
+#pragma unroll
+                for (int c = 0; c < 8; ++c) r[u][c] = (__bf16)0.0f;
+        }
+    }
+    __device__ void store(__bf16* s) const {
+        const int t = threadIdx.x, qv = (t & 7) * 8;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = (t >> 3) + 32 * u;
+            *reinterpret_cast<v8bf*>(s + i * Tile<__bf16>::LDA + qv) = r[u];
+        }
+    }
+};
+template <> struct Stage<__bf16, true> {   // [q][i], 8 bf16 along i; 16 threads cover 128 i of one q
+    v8bf r[4];
+    __device__ void load(const __bf16* p, int ld, int i0, int q0, int I, int Kq) {
+        const int t = threadIdx.x, iv = (t & 15) * 8;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = (t >> 4) * 4 + u;            // a thread holds 4 consecutive q of its 8 i
+            const bool ok = (q0 + q < Kq) && (i0 + iv < I);
+            if (ok) r[u] = *reinterpret_cast<const v8bf*>(p + (size_t)(q0 + q) * ld + i0 + iv);
+            else
+#pragma unroll
+                for (int c = 0; c < 8; ++c) r[u][c] = (__bf16)0.0f;
+        }
+    }
+    __device__ void store(__bf16* s) const {   // transposes 4 q x 8 i into 8 stores of 4 q
+        const int t = threadIdx.x, iv = (t & 15) * 8, q = (t >> 4) * 4;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const v4bf x = {r[0][c], r[1][c], r[2][c], r[3][c]};
+            *reinterpret_cast<v4bf*>(s + (iv + c) * Tile<__bf16>::LDA + q) = x;
+        }
+    }
+};
+
+// ---- the kernel -------------------------------------------------------------------------------
+template <typename T, bool P_IC, bool Q_IC, int EPI>
+__global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g) {
+    using TL = Tile<T>;
+    __shared__ __attribute__((aligned(16))) T s_p[TL::ELEMS];
+    __shared__ __attribute__((aligned(16))) T s_q[TL::ELEMS];
+
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int r32 = lane & 31, half = lane >> 5;
+
+    const int kt_total = ceil_div(g.K, TL::BK);
+    const int kt_begin = blockIdx.z * g.k_tiles_per_split;
+    const int kt_end = min(kt_total, kt_begin + g.k_tiles_per_split);
+
+    v16f acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    Stage<T, P_IC> sp;
+    Stage<T, Q_IC> sq;
+    const T* P = static_cast<const T*>(g.P);
+    const T* Q = static_cast<const T*>(g.Q);
+    if (kt_begin < kt_end) {
+        sp.load(P, g.ldp, m0, kt_begin * TL::BK, g.M, g.K);
+        sq.load(Q, g.ldq, n0, kt_begin * TL::BK, g.Nn, g.K);
+    }
+    for (int kt = kt_begin; kt < kt_end; ++kt) {
+        sp.store(s_p);
+        sq.store(s_q);
+        __syncthreads();
+        if (kt + 1 < kt_end) {
+            sp.load(P, g.ldp, m0, (kt + 1) * TL::BK, g.M, g.K);
+            sq.load(Q, g.ldq, n0, (kt + 1) * TL::BK, g.Nn, g.K);
+        }
+        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int kk = 0; kk < TL::BK; kk += 2) {
+                float a[2], b[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) a[i] = s_p[(kk + half) * TL::LDA + wm + i * 32 + r32];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) b[j] = s_q[(kk + half) * TL::LDA + wn + j * 32 + r32];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < TL::BK; kk += 16) {
+                v8bf a[2], b[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    a[i] = *reinterpret_cast<const v8bf*>(&s_p[(wm + i * 32 + r32) * TL::LDA + kk + half * 8]);
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    b[j] = *reinterpret_cast<const v8bf*>(&s_q[(wn + j * 32 + r32) * TL::LDA + kk + half * 8]);
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+
+    // Accumulator element e of lane (r32, half) in tile (i, j) is
+    // C[m0 + wm + 32 i + 8 (e/4) + 4 half + e%4][n0 + wn + 32 j + r32].
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn + j * 32 + r32;
+            if (n >= g.Nn) continue;
+            float bias = 0.0f;
+            if constexpr (EPI == EPI_SIGMOID) bias = g.bias[n];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m0 + wm + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+                if (m >= g.M) continue;
+                const size_t o = (size_t)m * g.Nn + n;
+                const float v = acc[i][j][e];
+                if constexpr (EPI == EPI_RAW) {
+                    g.raw[(size_t)blockIdx.z * g.M * g.Nn + o] = v;
+                } else if constexpr (EPI == EPI_SIGMOID) {
+                    static_cast<T*>(g.out)[o] = (T)sigmoidf(v + bias);
+                } else if constexpr (EPI == EPI_SIGMA_PRIME) {
+                    const float a = (float)static_cast<const T*>(g.act)[o];
+                    const float d = v * (a * (1.0f - a));
+                    static_cast<float*>(g.out)[o] = d;
+                    if constexpr (sizeof(T) == 2) static_cast<__bf16*>(g.out_bf)[o] = (__bf16)d;
+                } else {
+                    __builtin_nontemporal_store(v, static_cast<float*>(g.out) + o);
+                }
+            }
+        }
+}
+
+// Split-K second stage: sum the raw partials in split order, then the layer's epilogue.
+template <typename T, int EPI>
+__global__ __launch_bounds__(kThreads) void k_split_finish(const float* __restrict__ raw, int splits,
+                                                           size_t count, int Nn,
+                                                           const float* __restrict__ bias,
+                                                           const T* __restrict__ act, void* out,
+                                                           __bf16* out_bf) {
+    const size_t o = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (o >= count) return;
+    float v = 0.0f;
+    for (int z = 0; z < splits; ++z) v += raw[(size_t)z * count + o];
+    if constexpr (EPI == EPI_SIGMOID) {
+        static_cast<T*>(out)[o] = (T)sigmoidf(v + bias[o % Nn]);
+    } else {
+        const float a = (float)act[o];
+        const float d = v * (a * (1.0f - a));
+        static_cast<float*>(out)[o] = d;
+        if constexpr (sizeof(T) == 2) out_bf[o] = (__bf16)d;
+    }
+}
+
+// eq. (bp3) for a minibatch: nabla_b[j] = sum_b D[b][j], b ascending.
+__global__ __launch_bounds__(kThreads) void k_bias_grad(const float* __restrict__ D,
+                                                        float* __restrict__ nabla_b, int N, int B) {
+    const int j = blockIdx.x * kThreads + threadIdx.x;
+    if (j >= N) return;
+    float s = 0.0f;
+    for (int b = 0; b < B; ++b) s += D[(size_t)b * N + j];
+    nabla_b[j] = s;
+}
+
+template <typename T, bool P_IC, bool Q_IC, int EPI>
+hipError_t run(GemmArgs g, int splits, hipStream_t s) {
+    const dim3 grid(ceil_div(g.Nn, BN), ceil_div(g.M, BM), splits);
+    k_gemm<T, P_IC, Q_IC, EPI><<<grid, kThreads, 0, s>>>(g);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Number of K splits used for the two chain-side GEMMs (output B x N is small, so a single pass over
+// K would leave most compute units idle).  Depends on the shape alone.
+int chain_splits(int N, int B, bool bf16) {
+    const int tiles = ceil_div(N, BN) * ceil_div(B, BM);
+    const int kt = ceil_div(N, bf16 ? Tile<__bf16>::BK : Tile<float>::BK);
+    int s = 1;
+    while (tiles * s < 192 && s < 16 && kt / (s * 2) >= 4) s *= 2;
+    return s;
+}
+
+size_t split_workspace_floats(int N, int B, bool bf16) {
+    const int s = chain_splits(N, B, bf16);
+    return s > 1 ? (size_t)s * B * N : 0;
+}
+
+template <typename T>
+static hipError_t fwd_impl(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
+                           int N, int B, hipStream_t s) {
+    constexpr bool bf = sizeof(T) == 2;
+    const int splits = chain_splits(N, B, bf);
+    GemmArgs g{};
+    g.P = A_in; g.ldp = N; g.Q = W; g.ldq = N; g.M = B; g.Nn = N; g.K = N;
+    g.k_tiles_per_split = ceil_div(ceil_div(N, Tile<T>::BK), splits);
+    g.bias = bias; g.out = A_out; g.raw = raw;
+    if (splits == 1) return run<T, false, false, EPI_SIGMOID>(g, 1, s);
+    hipError_t e = run<T, false, false, EPI_RAW>(g, splits, s);
+    if (e != hipSuccess) return e;
+    const size_t count = (size_t)B * N;
+    k_split_finish<T, EPI_SIGMOID><<<(unsigned)((count + kThreads - 1) / kThreads), kThreads, 0, s>>>(
+        raw, splits, count, N, bias, nullptr, A_out, nullptr);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t chain_impl(const void* W_next, const void* D_next_op, const void* A_l, float* D_l,
+                             void* D_l_bf, float* raw, int N, int B, hipStream_t s) {
+    constexpr bool bf = sizeof(T) == 2;
+    const int splits = chain_splits(N, B, bf);
+    GemmArgs g{};
+    g.P = D_next_op; g.ldp = N; g.Q = W_next; g.ldq = N; g.M = B; g.Nn = N; g.K = N;
+    g.k_tiles_per_split = ceil_div(ceil_div(N, Tile<T>::BK), splits);
+    g.act = A_l; g.out = D_l; g.out_bf = D_l_bf; g.raw = raw;
+    if (splits == 1) return run<T, false, true, EPI_SIGMA_PRIME>(g, 1, s);
+    hipError_t e = run<T, false, true, EPI_RAW>(g, splits, s);
+    if (e != hipSuccess) return e;
+    const size_t count = (size_t)B * N;
+    k_split_finish<T, EPI_SIGMA_PRIME><<<(unsigned)((count + kThreads - 1) / kThreads), kThreads, 0, s>>>(
+        raw, splits, count, N, nullptr, static_cast<const T*>(A_l), D_l, static_cast<__bf16*>(D_l_bf));
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_gemm(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
+                           int N, int B, bool bf16, hipStream_t s) {
+    return bf16 ? fwd_impl<__bf16>(W, bias, A_in, A_out, raw, N, B, s)
+                : fwd_impl<float>(W, bias, A_in, A_out, raw, N, B, s);
+}
+
+hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void* D_next_bf,
+                             const void* A_l, float* D_l, void* D_l_bf, float* raw, int N, int B,
+                             bool bf16, hipStream_t s) {
+    return bf16 ? chain_impl<__bf16>(W_next, D_next_bf, A_l, D_l, D_l_bf, raw, N, B, s)
+                : chain_impl<float>(W_next, D_next, A_l, D_l, nullptr, raw, N, B, s);
+}
+
+hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
+                            float* nabla_b, int N, int B, bool bf16, hipStream_t s) {
+    k_bias_grad<<<ceil_div(N, kThreads), kThreads, 0, s>>>(D, nabla_b, N, B);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    GemmArgs g{};
+    g.ldp = N; g.Q = A_prev; g.ldq = N; g.M = N; g.Nn = N; g.K = B;
+    g.out = nabla_w;
+    if (bf16) {
+        g.P = D_bf;
+        g.k_tiles_per_split = ceil_div(B, Tile<__bf16>::BK);
+        return run<__bf16, true, true, EPI_GRAD>(g, 1, s);
+    }
+    g.P = D;
+    g.k_tiles_per_split = ceil_div(B, Tile<float>::BK);
+    return run<float, true, true, EPI_GRAD>(g, 1, s);
+}
+
+}  // namespace lf

@@ -1,0 +1,340 @@
+// C ABI of the library (see include/lf.h): handle, argument and state checks, workspace layout, and
+// the stream realisation of the leapfrog schedule of section 3 / Algorithm 1:
+//   - the delta chain (bp1),(bp2) runs once, on the caller's stream;
+//   - after delta^l is enqueued an event is recorded; worker (L-l) mod k, a stream of its own, waits
+//     for that event and computes (bp3),(bp4) of layer l;
+//   - at the end the caller's stream waits for every worker (the join).
+// With k = 1 the gradient kernels are enqueued in line on the caller's stream (sequential pass).
+#include "../../include/lf.h"
+#include "lf_internal.h"
+
+#include <new>
+#include <string>
+#include <vector>
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kMaxL = 4096;
+constexpr int kMaxWorkerStreams = 32;   // workers beyond this share streams (worker j -> stream j mod 32)
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+std::string g_create_error = "no error";
+
+struct Layout {
+    size_t a_off, a_stride;          // a^2..a^L
+    size_t d_off, d_stride;          // delta^2..delta^L (fp32)
+    size_t dbf_off, dbf_stride;      // bfloat16 copies of delta (bf16 nets only)
+    size_t partial_off, partial_bytes;
+    size_t raw_off, raw_bytes;
+    size_t total;
+};
+
+bool valid_shape(int L, int N, int B, lf_dtype dt) {
+    if (L < 2 || L > kMaxL || N < 1 || B < 1) return false;
+    if (dt != LF_F32 && dt != LF_BF16) return false;
+    if (N % (dt == LF_BF16 ? 8 : 4) != 0) return false;
+    if ((size_t)N * (size_t)B > ((size_t)1 << 40)) return false;
+    return true;
+}
+
+bool single_sample_path(int N, int B, lf_dtype dt) { return B == 1 && dt == LF_F32 && N <= 16384; }
+
+Layout make_layout(int L, int N, int B, lf_dtype dt) {
+    Layout y{};
+    const size_t M = (size_t)(L - 1), bn = (size_t)B * N;
+    const size_t es = dt == LF_BF16 ? 2 : 4;
+    size_t off = 0;
+    y.a_off = off;   y.a_stride = align_up(bn * es);   off += M * y.a_stride;
+    y.d_off = off;   y.d_stride = align_up(bn * 4);    off += M * y.d_stride;
+    y.dbf_off = off; y.dbf_stride = dt == LF_BF16 ? align_up(bn * 2) : 0; off += M * y.dbf_stride;
+    y.partial_off = off;
+    y.partial_bytes = single_sample_path(N, B, dt) ? align_up((size_t)lf::chain_partial_blocks(N) * N * 4) : 0;
+    off += y.partial_bytes;
+    y.raw_off = off;
+    y.raw_bytes = single_sample_path(N, B, dt) ? 0 : align_up(lf::split_workspace_floats(N, B, dt == LF_BF16) * 4);
+    off += y.raw_bytes;
+    y.total = off;
+    return y;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+struct lf_net {
+    int L, N, B;
+    lf_dtype dt;
+    lf_cost cost;
+    lf_sched sched;
+    char* ws;
+    Layout lay;
+    std::vector<const void*> w;       // index l-2
+    std::vector<const float*> b;
+    std::vector<float*> gw, gb;
+    const void* x1;
+    bool have_params, have_grads, fwd_done, bwd_done;
+    std::vector<hipStream_t> workers;
+    std::vector<hipEvent_t> ev_delta;  // index l-2
+    std::vector<hipEvent_t> ev_done;   // per worker stream
+    std::string err;
+
+    void* a_ptr(int l) const {         // l = 1..L
+        return l == 1 ? const_cast<void*>(x1) : ws + lay.a_off + (size_t)(l - 2) * lay.a_stride;
+    }
+    float* d_ptr(int l) const { return reinterpret_cast<float*>(ws + lay.d_off + (size_t)(l - 2) * lay.d_stride); }
+    void* dbf_ptr(int l) const {
+        return dt == LF_BF16 ? ws + lay.dbf_off + (size_t)(l - 2) * lay.dbf_stride : nullptr;
+    }
+    float* partial() const { return reinterpret_cast<float*>(ws + lay.partial_off); }
+    float* raw() const { return lay.raw_bytes ? reinterpret_cast<float*>(ws + lay.raw_off) : nullptr; }
+};
+
+namespace {
+
+lf_status fail(lf_net* net, lf_status st, const std::string& msg) {
+    if (net) net->err = msg; else g_create_error = msg;
+    return st;
+}
+
+lf_status fail_hip(lf_net* net, hipError_t e, const char* what) {
+    return fail(net, LF_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define LF_HIP(net, call)                                         \
+    do {                                                          \
+        hipError_t e_ = (call);                                   \
+        if (e_ != hipSuccess) return fail_hip(net, e_, #call);    \
+    } while (0)
+
+lf_status ensure_workers(lf_net* net, int k) {
+    const size_t M = (size_t)net->L - 1;
+    while (net->ev_delta.size() < M) {
+        hipEvent_t e;
+        LF_HIP(net, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        net->ev_delta.push_back(e);
+    }
+    const size_t want = k > 1 ? (size_t)(k < kMaxWorkerStreams ? k : kMaxWorkerStreams) : 0;
+    while (net->workers.size() < want) {
+        hipStream_t s;
+        LF_HIP(net, hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        net->workers.push_back(s);
+        hipEvent_t e;
+        LF_HIP(net, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        net->ev_done.push_back(e);
+    }
+    return LF_OK;
+}
+
+// (bp3),(bp4) of layer l on stream s.
+lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
+    const int i = l - 2;
+    if (single_sample_path(net->N, net->B, net->dt)) {
+        LF_HIP(net, lf::launch_grad_outer_f32(net->d_ptr(l), static_cast<const float*>(net->a_ptr(l - 1)),
+                                              net->gw[i], net->gb[i], net->N, s));
+    } else {
+        LF_HIP(net, lf::launch_grad_gemm(net->d_ptr(l), net->dbf_ptr(l), net->a_ptr(l - 1), net->gw[i],
+                                         net->gb[i], net->N, net->B, net->dt == LF_BF16, s));
+    }
+    return LF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lf_workspace_bytes(int L, int N, int B, lf_dtype dt) {
+    if (!valid_shape(L, N, B, dt)) return 0;
+    const size_t t = make_layout(L, N, B, dt).total;
+    return t ? t : kAlign;
+}
+
+lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost, void* workspace,
+                    size_t workspace_bytes) {
+    if (!out) return fail(nullptr, LF_EINVAL, "lf_create: out is NULL");
+    *out = nullptr;
+    if (!valid_shape(L, N, B, dt))
+        return fail(nullptr, LF_EINVAL,
+                    "lf_create: need 2 <= L <= 4096, B >= 1, N a positive multiple of 4 (fp32) or 8 (bf16)");
+    if (cost != LF_COST_QUADRATIC) return fail(nullptr, LF_EINVAL, "lf_create: unknown cost");
+    if (!workspace) return fail(nullptr, LF_EINVAL, "lf_create: workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace) % kAlign)
+        return fail(nullptr, LF_EINVAL, "lf_create: workspace must be 256-byte aligned");
+    if (workspace_bytes < lf_workspace_bytes(L, N, B, dt))
+        return fail(nullptr, LF_EINVAL, "lf_create: workspace smaller than lf_workspace_bytes()");
+    lf_net* net = new (std::nothrow) lf_net();
+    if (!net) return fail(nullptr, LF_ENOMEM, "lf_create: out of host memory");
+    net->L = L; net->N = N; net->B = B; net->dt = dt; net->cost = cost;
+    net->sched = LF_SCHED_AUTO;
+    net->ws = static_cast<char*>(workspace);
+    net->lay = make_layout(L, N, B, dt);
+    net->x1 = nullptr;
+    net->have_params = net->have_grads = net->fwd_done = net->bwd_done = false;
+    net->err = "no error";
+    try {
+        net->w.assign(L - 1, nullptr); net->b.assign(L - 1, nullptr);
+        net->gw.assign(L - 1, nullptr); net->gb.assign(L - 1, nullptr);
+    } catch (...) {
+        delete net;
+        return fail(nullptr, LF_ENOMEM, "lf_create: out of host memory");
+    }
+    *out = net;
+    return LF_OK;
+}
+
+lf_status lf_set_params(lf_net* net, const void* const* w, const void* const* b) {
+    if (!net) return LF_EINVAL;
+    if (!w || !b) return fail(net, LF_EINVAL, "lf_set_params: NULL pointer array");
+    for (int i = 0; i < net->L - 1; ++i) {
+        if (!w[i] || !b[i]) return fail(net, LF_EINVAL, "lf_set_params: NULL layer pointer");
+        if (!aligned16(w[i]) || !aligned16(b[i]))
+            return fail(net, LF_EINVAL, "lf_set_params: pointers must be 16-byte aligned");
+    }
+    for (int i = 0; i < net->L - 1; ++i) { net->w[i] = w[i]; net->b[i] = static_cast<const float*>(b[i]); }
+    net->have_params = true;
+    net->fwd_done = net->bwd_done = false;
+    return LF_OK;
+}
+
+lf_status lf_set_grad_buffers(lf_net* net, float* const* nabla_w, float* const* nabla_b) {
+    if (!net) return LF_EINVAL;
+    if (!nabla_w || !nabla_b) return fail(net, LF_EINVAL, "lf_set_grad_buffers: NULL pointer array");
+    for (int i = 0; i < net->L - 1; ++i) {
+        if (!nabla_w[i] || !nabla_b[i]) return fail(net, LF_EINVAL, "lf_set_grad_buffers: NULL layer pointer");
+        if (!aligned16(nabla_w[i]) || !aligned16(nabla_b[i]))
+            return fail(net, LF_EINVAL, "lf_set_grad_buffers: pointers must be 16-byte aligned");
+    }
+    for (int i = 0; i < net->L - 1; ++i) { net->gw[i] = nabla_w[i]; net->gb[i] = nabla_b[i]; }
+    net->have_grads = true;
+    net->bwd_done = false;
+    return LF_OK;
+}
+
+lf_status lf_set_schedule(lf_net* net, lf_sched sched) {
+    if (!net) return LF_EINVAL;
+    switch (sched) {
+        case LF_SCHED_AUTO:
+        case LF_SCHED_STREAMS:
+            net->sched = sched;
+            return LF_OK;
+        case LF_SCHED_PERSISTENT:
+            return fail(net, LF_EUNSUPPORTED, "lf_set_schedule: no persistent-kernel path for this shape");
+        default:
+            return fail(net, LF_EINVAL, "lf_set_schedule: unknown schedule");
+    }
+}
+
+lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream) {
+    if (!net) return LF_EINVAL;
+    if (!x1) return fail(net, LF_EINVAL, "lf_forward: x1 is NULL");
+    if (!aligned16(x1)) return fail(net, LF_EINVAL, "lf_forward: x1 must be 16-byte aligned");
+    if (!net->have_params) return fail(net, LF_ESTATE, "lf_forward: call lf_set_params first");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    net->x1 = x1;
+    net->fwd_done = false;
+    net->bwd_done = false;
+    const bool bf = net->dt == LF_BF16;
+    for (int l = 2; l <= net->L; ++l) {
+        if (single_sample_path(net->N, net->B, net->dt)) {
+            LF_HIP(net, lf::launch_fwd_gemv_f32(static_cast<const float*>(net->w[l - 2]), net->b[l - 2],
+                                                static_cast<const float*>(net->a_ptr(l - 1)),
+                                                static_cast<float*>(net->a_ptr(l)), net->N, s));
+        } else {
+            LF_HIP(net, lf::launch_fwd_gemm(net->w[l - 2], net->b[l - 2], net->a_ptr(l - 1), net->a_ptr(l),
+                                            net->raw(), net->N, net->B, bf, s));
+        }
+    }
+    net->fwd_done = true;
+    return LF_OK;
+}
+
+lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stream) {
+    if (!net) return LF_EINVAL;
+    if (!y) return fail(net, LF_EINVAL, "lf_backward_leapfrog: y is NULL");
+    if (!aligned16(y)) return fail(net, LF_EINVAL, "lf_backward_leapfrog: y must be 16-byte aligned");
+    if (k < 1 || k > net->L - 1) return fail(net, LF_EINVAL, "lf_backward_leapfrog: need 1 <= k <= L-1");
+    if (!net->have_params) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_params first");
+    if (!net->have_grads) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_grad_buffers first");
+    if (!net->fwd_done) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_forward first");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int L = net->L, N = net->N, B = net->B;
+    const bool bf = net->dt == LF_BF16;
+    const bool b1 = single_sample_path(N, B, net->dt);
+    net->bwd_done = false;
+    lf_status st = ensure_workers(net, k);
+    if (st != LF_OK) return st;
+    const int nstreams = (int)net->workers.size() < k ? (int)net->workers.size() : k;
+    std::vector<char> used(nstreams > 0 ? nstreams : 1, 0);
+
+    for (int l = L; l >= 2; --l) {
+        // the chain: (bp1) at L, (bp2) below
+        if (l == L) {
+            LF_HIP(net, lf::launch_output_error(net->a_ptr(L), y, net->d_ptr(L), net->dbf_ptr(L),
+                                                (size_t)B * N, bf, s));
+        } else if (b1) {
+            LF_HIP(net, lf::launch_chain_gemvT_f32(static_cast<const float*>(net->w[l - 1]), net->d_ptr(l + 1),
+                                                   static_cast<const float*>(net->a_ptr(l)), net->d_ptr(l),
+                                                   net->partial(), N, s));
+        } else {
+            LF_HIP(net, lf::launch_chain_gemm(net->w[l - 1], net->d_ptr(l + 1), net->dbf_ptr(l + 1), net->a_ptr(l),
+                                              net->d_ptr(l), net->dbf_ptr(l), net->raw(), N, B, bf, s));
+        }
+        // (bp3),(bp4) of layer l, off the chain
+        if (k == 1) {
+            st = enqueue_grads(net, l, s);
+            if (st != LF_OK) return st;
+        } else {
+            const int j = lf_schedule_worker(L, k, l) % nstreams;
+            LF_HIP(net, hipEventRecord(net->ev_delta[l - 2], s));
+            LF_HIP(net, hipStreamWaitEvent(net->workers[j], net->ev_delta[l - 2], 0));
+            st = enqueue_grads(net, l, net->workers[j]);
+            if (st != LF_OK) return st;
+            used[j] = 1;
+        }
+    }
+    if (k > 1) {   // join
+        for (int j = 0; j < nstreams; ++j) {
+            if (!used[j]) continue;
+            LF_HIP(net, hipEventRecord(net->ev_done[j], net->workers[j]));
+            LF_HIP(net, hipStreamWaitEvent(s, net->ev_done[j], 0));
+        }
+    }
+    net->bwd_done = true;
+    return LF_OK;
+}
+
+lf_status lf_grads(lf_net* net, int l, const float** nabla_w, const float** nabla_b) {
+    if (!net) return LF_EINVAL;
+    if (l < 2 || l > net->L) return fail(net, LF_EINVAL, "lf_grads: layer index must be in 2..L");
+    if (!net->bwd_done) return fail(net, LF_ESTATE, "lf_grads: no backward pass has been enqueued");
+    if (nabla_w) *nabla_w = net->gw[l - 2];
+    if (nabla_b) *nabla_b = net->gb[l - 2];
+    return LF_OK;
+}
+
+lf_status lf_activations(lf_net* net, int l, const void** a_l, const float** delta_l) {
+    if (!net) return LF_EINVAL;
+    if (l < 1 || l > net->L) return fail(net, LF_EINVAL, "lf_activations: layer index must be in 1..L");
+    if (!net->fwd_done) return fail(net, LF_ESTATE, "lf_activations: no forward pass has been enqueued");
+    if (a_l) *a_l = net->a_ptr(l);
+    if (delta_l) *delta_l = l >= 2 ? net->d_ptr(l) : nullptr;
+    return LF_OK;
+}
+
+int lf_schedule_worker(int L, int k, int l) {
+    if (L < 2 || k < 1 || k > L - 1 || l < 2 || l > L) return -1;
+    return (L - l) % k;
+}
+
+const char* lf_last_error(const lf_net* net) { return net ? net->err.c_str() : g_create_error.c_str(); }
+
+void lf_destroy(lf_net* net) {
+    if (!net) return;
+    for (hipStream_t s : net->workers) (void)hipStreamDestroy(s);
+    for (hipEvent_t e : net->ev_delta) (void)hipEventDestroy(e);
+    for (hipEvent_t e : net->ev_done) (void)hipEventDestroy(e);
+    delete net;
+}
+
+}  // extern "C"

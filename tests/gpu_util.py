@@ -1,0 +1,101 @@
+"""Helpers for the GPU parity tests: run the library on a synthetic net and compare every tensor
+with the CPU oracle, layer by layer."""
+import sys
+import time
+
+import numpy as np
+
+from oracle import backprop as O
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+# A tensor whose largest oracle entry is below this is in (or next to) the fp32 subnormal range,
+# where a relative 1e-5 is not representable; it is compared in units of the smallest subnormal.
+SUBNORMAL_SCALE = 2.0 ** -126 * 2.0 ** 10
+DENORM_ULP = 2.0 ** -149
+
+
+def log(msg):
+    sys.stderr.write(f"[{time.strftime('%H:%M:%S')}] {msg}\n")
+    sys.stderr.flush()
+
+
+def compare(name, got, want, tol, report, denorm_ulps=64.0):
+    """Normwise error max|got-want| / max|want| <= tol (or an absolute bound for subnormal tensors)."""
+    want = np.asarray(want, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64).reshape(want.shape)
+    assert np.all(np.isfinite(got)), f"{name}: non-finite values"
+    scale = float(np.max(np.abs(want)))
+    diff = float(np.max(np.abs(got - want)))
+    err = diff / scale if scale > 0 else (0.0 if diff == 0 else float("inf"))
+    if err > tol and scale < SUBNORMAL_SCALE:
+        # too close to the subnormal range for a relative bound: absolute, in denormal ulps, and listed
+        report.setdefault("subnormal", []).append((name, scale, diff / DENORM_ULP))
+        assert diff <= denorm_ulps * DENORM_ULP, f"{name}: subnormal tensor off by {diff / DENORM_ULP:.1f} denormal ulps"
+        return 0.0
+    report["worst"] = max(report.get("worst", 0.0), err)
+    assert err <= tol, f"{name}: normwise error {err:.3e} > {tol:.1e}"
+    return err
+
+
+def to_np(t):
+    return t.detach().float().cpu().numpy()
+
+
+def run_gpu(net, k, sched=None, poison=True):
+    """Build a LeapfrogNet for the synthetic net, run forward + backward(k), return it (synchronised)."""
+    import torch
+    import paper_1801_04928_amd as P
+    s = net.spec
+    g = P.LeapfrogNet(s.L, s.N, s.B, s.dtype)
+    g.load(net)
+    if sched is not None:
+        g.set_schedule(sched)
+    if poison:
+        poison_buffers(g)
+    g.forward()
+    g.backward(k)
+    torch.cuda.synchronize()
+    return g
+
+
+def poison_buffers(g):
+    """NaN in every buffer the pass must overwrite: a read before the producer has written shows up."""
+    g.workspace.view(g.torch.float32)[: g.workspace.numel() // 4].fill_(float("nan"))
+    for t in g.nabla_w + g.nabla_b:
+        t.fill_(float("nan"))
+
+
+def check_against_oracle(net, g, tol=None, sample_tiles=None, rng=None):
+    """Compare a^l, delta^l, nabla_b^l and nabla_w^l for every layer.  With sample_tiles = (count, size)
+    nabla_w is compared on that many random size x size tiles per layer, formed one by one from the
+    oracle's delta and a via eq. (bp4)."""
+    s = net.spec
+    tol = TOL[s.dtype] if tol is None else tol
+    report = {}
+    w, b = net.w_by_layer, net.b_by_layer
+    a = O.forward(w, b, net.x(), s.L)
+    for l in range(2, s.L + 1):
+        compare(f"a^{l}", to_np(g.activation(l)), a[l], tol, report)
+    for l, delta, nb, nw in O.backward_layers(w, a, net.y(), s.L, want_nabla_w=sample_tiles is None):
+        compare(f"delta^{l}", to_np(g.delta(l)), delta, tol, report)
+        gw, gb = g.grads(l)
+        compare(f"nabla_b^{l}", to_np(gb), nb, tol, report)
+        if sample_tiles is None:
+            compare(f"nabla_w^{l}", to_np(gw), nw, tol, report)
+        else:
+            count, size = sample_tiles
+            tiles = []
+            for _ in range(count):
+                j0 = int(rng.integers(0, max(1, s.N - size + 1)))
+                k0 = int(rng.integers(0, max(1, s.N - size + 1)))
+                want = delta[:, j0:j0 + size].T @ a[l - 1][:, k0:k0 + size]
+                got = to_np(gw[j0:j0 + size, k0:k0 + size])
+                tiles.append((got, want))
+            got_all = np.stack([t[0] for t in tiles])
+            want_all = np.stack([t[1] for t in tiles])
+            compare(f"nabla_w^{l}[tiles]", got_all, want_all, tol, report)
+            assert bool(g.torch.isfinite(gw).all()), f"nabla_w^{l}: non-finite values"
+        if l % 8 == 0:
+            log(f"  layer {l} checked, worst so far {report.get('worst', 0.0):.2e}")
+    return report

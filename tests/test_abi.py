@@ -1,0 +1,133 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every symbol the header
+declares, validates arguments and call order, and its schedule function agrees with Algorithm 1."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_1801_04928_amd as P
+from oracle import backprop as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "lf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lf_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    syms = _declared_symbols()
+    assert {"lf_forward", "lf_backward_leapfrog", "lf_grads"} <= set(syms)
+    lib = P.lib()
+    for s in syms:
+        assert hasattr(lib, s), f"{s} declared in lf.h but not exported"
+
+
+def test_binding_has_same_names():
+    for s in _declared_symbols():
+        assert callable(getattr(P, s)), s
+
+
+def test_workspace_bytes():
+    assert P.lf_workspace_bytes(1, 256, 1, P.LF_F32) == 0          # L < 2
+    assert P.lf_workspace_bytes(8, 255, 1, P.LF_F32) == 0          # N not a multiple of 4
+    assert P.lf_workspace_bytes(8, 260, 1, P.LF_BF16) == 0         # N not a multiple of 8 for bf16
+    assert P.lf_workspace_bytes(8, 256, 0, P.LF_F32) == 0
+    assert P.lf_workspace_bytes(8, 256, 1, 7) == 0
+    n = P.lf_workspace_bytes(8, 256, 1, P.LF_F32)
+    assert n >= 7 * 256 * 4 * 2 and n % 256 == 0                   # a^2..a^L and delta^2..delta^L
+    assert P.lf_workspace_bytes(8, 256, 4, P.LF_F32) > n
+
+
+FAKE = 1 << 20   # a "device pointer" that is only checked for alignment, never dereferenced on the host
+
+
+def _handle(L=8, N=256, B=1, dt=P.LF_F32):
+    st, h = P.lf_create(L, N, B, dt, P.LF_COST_QUADRATIC, FAKE, P.lf_workspace_bytes(L, N, B, dt))
+    assert st == P.LF_OK
+    return h
+
+
+def test_create_rejects_bad_arguments():
+    ok = P.lf_workspace_bytes(8, 256, 1, P.LF_F32)
+    for args in [(1, 256, 1, P.LF_F32, 0, FAKE, ok), (8, 254, 1, P.LF_F32, 0, FAKE, ok),
+                 (8, 256, 0, P.LF_F32, 0, FAKE, ok), (8, 256, 1, 5, 0, FAKE, ok),
+                 (8, 256, 1, P.LF_F32, 3, FAKE, ok), (8, 256, 1, P.LF_F32, 0, 0, ok),
+                 (8, 256, 1, P.LF_F32, 0, FAKE + 16, ok), (8, 256, 1, P.LF_F32, 0, FAKE, ok - 1),
+                 (5000, 256, 1, P.LF_F32, 0, FAKE, ok)]:
+        st, h = P.lf_create(*args)
+        assert st == P.LF_EINVAL and h is None, args
+        assert "lf_create" in P.lf_last_error(None)
+
+
+def test_call_order_and_argument_checks():
+    h = _handle()
+    M = 7
+    try:
+        assert P.lf_forward(h, FAKE) == P.LF_ESTATE
+        assert "lf_set_params" in P.lf_last_error(h)
+        assert P.lf_set_params(h, None, None) == P.LF_EINVAL
+        assert P.lf_set_params(h, [FAKE] * M, [FAKE] * (M - 1) + [0]) == P.LF_EINVAL
+        assert P.lf_set_params(h, [FAKE] * (M - 1) + [FAKE + 4], [FAKE] * M) == P.LF_EINVAL
+        assert P.lf_set_params(h, [FAKE] * M, [FAKE] * M) == P.LF_OK
+        assert P.lf_backward_leapfrog(h, FAKE, 1) == P.LF_ESTATE          # no grad buffers
+        assert P.lf_set_grad_buffers(h, [FAKE] * M, [FAKE + 8] * M) == P.LF_EINVAL
+        assert P.lf_set_grad_buffers(h, [FAKE] * M, [FAKE] * M) == P.LF_OK
+        assert P.lf_backward_leapfrog(h, FAKE, 1) == P.LF_ESTATE          # no forward yet
+        assert "lf_forward" in P.lf_last_error(h)
+        for k in (0, -1, 8, 100):
+            assert P.lf_backward_leapfrog(h, FAKE, k) == P.LF_EINVAL      # 1 <= k <= L-1
+        assert P.lf_backward_leapfrog(h, 0, 1) == P.LF_EINVAL
+        assert P.lf_backward_leapfrog(h, FAKE + 2, 1) == P.LF_EINVAL
+        assert P.lf_forward(h, 0) == P.LF_EINVAL
+        assert P.lf_forward(h, FAKE + 4) == P.LF_EINVAL
+        st, _, _ = P.lf_grads(h, 3)
+        assert st == P.LF_ESTATE
+        st, _, _ = P.lf_grads(h, 1)
+        assert st == P.LF_EINVAL
+        st, _, _ = P.lf_activations(h, 9)
+        assert st == P.LF_EINVAL
+        st, _, _ = P.lf_activations(h, 2)
+        assert st == P.LF_ESTATE
+        assert P.lf_set_schedule(h, 99) == P.LF_EINVAL
+        assert P.lf_set_schedule(h, P.LF_SCHED_STREAMS) == P.LF_OK
+    finally:
+        P.lf_destroy(h)
+    P.lf_destroy(None)
+
+
+def test_null_handle_is_rejected():
+    assert P.lf_forward(None, FAKE) == P.LF_EINVAL
+    assert P.lf_backward_leapfrog(None, FAKE, 1) == P.LF_EINVAL
+    assert P.lf_set_params(None, [FAKE], [FAKE]) == P.LF_EINVAL
+    assert isinstance(P.lf_last_error(None), str)
+
+
+@pytest.mark.parametrize("L", [2, 3, 8, 32, 64])
+def test_schedule_matches_algorithm1(L):
+    """The library's worker(l) equals what running Algorithm 1's index arithmetic gives."""
+    for k in range(1, L):
+        want = O.worker_of_layer(L, k)
+        for l in range(2, L + 1):
+            assert P.lf_schedule_worker(L, k, l) == want[l]
+    assert P.lf_schedule_worker(L, 0, 2) == -1
+    assert P.lf_schedule_worker(L, L, 2) == -1
+    assert P.lf_schedule_worker(L, 1, 1) == -1
+    assert P.lf_schedule_worker(L, 1, L + 1) == -1
+
+
+def test_forward_without_a_gpu_fails_loudly():
+    """No CPU fallback: on a machine without a GPU the pass reports LF_EHIP."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    h = _handle()
+    try:
+        assert P.lf_set_params(h, [FAKE] * 7, [FAKE] * 7) == P.LF_OK
+        assert P.lf_forward(h, FAKE) == P.LF_EHIP
+        assert P.lf_last_error(h)
+    finally:
+        P.lf_destroy(h)

@@ -1,0 +1,175 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs, element by element.  fp32: normwise error <= 1e-5 per tensor; bf16 storage with fp32
+accumulation: <= 2e-2.  Gradients must be bit-identical for every k."""
+import numpy as np
+import pytest
+
+from lf_inputs import config_net, make_net
+from tests.gpu_util import check_against_oracle, log, poison_buffers, run_gpu, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _free(g):
+    g.close()
+
+
+# ---------------------------------------------------------------- single sample, fp32
+@pytest.mark.parametrize("L,N,k", [
+    (2, 256, 1),        # one weight layer
+    (3, 4, 2),          # smallest width
+    (5, 260, 2),        # ragged: one full strip of 256 columns + 4
+    (8, 256, 2),        # configuration 1's shape
+    (6, 1000, 3),       # not a multiple of any tile
+    (4, 2052, 3),       # rows-per-wave 8 path, ragged
+    (3, 4100, 2),       # rows-per-wave 16 path, ragged
+    (9, 512, 8),        # k = L-1, the largest allowed
+])
+def test_single_sample_fp32_matches_oracle(L, N, k):
+    net = make_net(L, N, 1, seed=L * 1000 + N)
+    g = run_gpu(net, k)
+    rep = check_against_oracle(net, g)
+    log(f"B=1 L={L} N={N} k={k}: worst normwise error {rep['worst']:.2e}")
+    _free(g)
+
+
+def test_single_sample_outer_product_is_exact():
+    """Eq. (bp4) at B = 1 is one multiplication per entry: nabla_w^l[j][k] must equal
+    fl32(delta^l[j] * a^{l-1}[k]) of the GPU's own delta and a, bit for bit; nabla_b^l = delta^l."""
+    net = make_net(6, 772, 1, seed=5)
+    g = run_gpu(net, 2)
+    for l in range(2, 7):
+        d = to_np(g.delta(l))[0].astype(np.float32)
+        a = to_np(g.activation(l - 1))[0].astype(np.float32)
+        gw, gb = g.grads(l)
+        assert np.array_equal(to_np(gw), np.outer(d, a).astype(np.float32))
+        assert np.array_equal(to_np(gb), d)
+    _free(g)
+
+
+@pytest.mark.parametrize("L,N,B,dtype", [(12, 1024, 1, "f32"), (6, 392, 5, "f32"), (6, 264, 9, "bf16")])
+def test_gradients_bit_identical_for_every_k(L, N, B, dtype):
+    """Leapfrogging only reassigns who computes (bp3),(bp4) (Theorem 1): same bits for every k."""
+    net = make_net(L, N, B, dtype=dtype, seed=77)
+    ref = None
+    for k in (1, 2, 4, 5, L - 1):
+        g = run_gpu(net, k)
+        cur = [(to_np(g.grads(l)[0]).copy(), to_np(g.grads(l)[1]).copy()) for l in range(2, L + 1)]
+        if ref is None:
+            ref = cur
+        else:
+            for (w0, b0), (w1, b1) in zip(ref, cur):
+                assert np.array_equal(w0.view(np.uint32), w1.view(np.uint32))
+                assert np.array_equal(b0.view(np.uint32), b1.view(np.uint32))
+        _free(g)
+
+
+def test_repeated_passes_are_deterministic_and_overwrite():
+    """Gradients are overwritten (not accumulated) and identical on every pass; buffers are poisoned
+    with NaN between passes so a worker that ran ahead of its delta would show."""
+    import torch
+    net = make_net(10, 640, 1, seed=3)
+    g = run_gpu(net, 4)
+    first = [to_np(g.grads(l)[0]).copy() for l in range(2, 11)]
+    for _ in range(20):
+        poison_buffers(g)
+        g.forward()
+        g.backward(4)
+    torch.cuda.synchronize()
+    for l in range(2, 11):
+        assert np.array_equal(first[l - 2].view(np.uint32), to_np(g.grads(l)[0]).view(np.uint32))
+    _free(g)
+
+
+def test_rank_one_net_full_width():
+    """The rank-one symmetric net collapses to a scalar recurrence (see the oracle pins); checks the
+    full-length reductions of the GPU path at N = 4096 against that recurrence through the oracle."""
+    import math
+    import paper_1801_04928_amd as P
+    import torch
+    L, N = 5, 4096
+    c, beta, xi, eta = 1.7, -0.3, 0.6, 0.2
+    g = P.LeapfrogNet(L, N, 1, "f32")
+    for t in g.w:
+        t.fill_(c / N)
+    for t in g.b:
+        t.fill_(beta)
+    g.x.fill_(xi)
+    g.y.fill_(eta)
+    g.forward()
+    g.backward(2)
+    torch.cuda.synchronize()
+    alpha = {1: xi}
+    for l in range(2, L + 1):
+        alpha[l] = 1.0 / (1.0 + math.exp(-(c * alpha[l - 1] + beta)))
+    d = {L: (alpha[L] - eta) * alpha[L] * (1 - alpha[L])}
+    for l in range(L - 1, 1, -1):
+        d[l] = c * d[l + 1] * alpha[l] * (1 - alpha[l])
+    for l in range(2, L + 1):
+        gw, gb = g.grads(l)
+        np.testing.assert_allclose(to_np(gw), d[l] * alpha[l - 1], rtol=2e-5)
+        np.testing.assert_allclose(to_np(gb), d[l], rtol=2e-5)
+    _free(g)
+
+
+# ---------------------------------------------------------------- minibatch
+@pytest.mark.parametrize("L,N,B,dtype,k", [
+    (4, 132, 3, "f32", 2),       # one ragged tile in every dimension
+    (3, 260, 37, "f32", 1),
+    (5, 512, 256, "f32", 4),     # several full tiles; split-K on the chain
+    (3, 1024, 130, "f32", 2),
+    (4, 136, 5, "bf16", 2),
+    (3, 264, 70, "bf16", 1),
+    (5, 512, 192, "bf16", 4),
+    (3, 392, 1, "bf16", 2),      # B = 1 through the minibatch kernels
+])
+def test_minibatch_matches_oracle(L, N, B, dtype, k):
+    net = make_net(L, N, B, dtype=dtype, seed=L * 1000 + N + B)
+    g = run_gpu(net, k)
+    rep = check_against_oracle(net, g)
+    log(f"B={B} L={L} N={N} {dtype} k={k}: worst normwise error {rep['worst']:.2e}")
+    _free(g)
+
+
+# ---------------------------------------------------------------- the five configurations, full size
+def test_config1_full():
+    net = config_net("cfg1", cache=True)
+    g = run_gpu(net, 2)
+    rep = check_against_oracle(net, g)
+    log(f"cfg1: worst {rep['worst']:.2e}")
+    _free(g)
+
+
+@pytest.mark.parametrize("k", [1, 2, 4, 8])
+def test_config2_full(k):
+    net = config_net("cfg2", cache=True)
+    g = run_gpu(net, k)
+    rep = check_against_oracle(net, g)
+    log(f"cfg2 k={k}: worst {rep['worst']:.2e}")
+    _free(g)
+
+
+def test_config3_full():
+    """L=64: delta underflows into the fp32 subnormal range near the input; those layers are
+    compared in denormal ulps and listed."""
+    net = config_net("cfg3", cache=True)
+    g = run_gpu(net, 8)
+    rep = check_against_oracle(net, g)
+    log(f"cfg3 k=8: worst {rep['worst']:.2e}; subnormal tensors: {rep.get('subnormal', [])}")
+    _free(g)
+
+
+def test_config4_full_sampled():
+    net = config_net("cfg4", cache=True)
+    g = run_gpu(net, 4)
+    rep = check_against_oracle(net, g, sample_tiles=(8, 128), rng=np.random.default_rng(4))
+    log(f"cfg4 k=4: worst {rep['worst']:.2e}")
+    _free(g)
+
+
+def test_config5_full_sampled():
+    net = config_net("cfg5", cache=False)
+    g = run_gpu(net, 8)
+    rep = check_against_oracle(net, g, sample_tiles=(4, 128), rng=np.random.default_rng(5))
+    log(f"cfg5 k=8: worst {rep['worst']:.2e}")
+    _free(g)
