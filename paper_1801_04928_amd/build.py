@@ -10,7 +10,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblf.so")
-SOURCES = ["lf_api.hip", "b1_kernels.hip", "batched_kernels.hip"]
+SOURCES = ["lf_api.hip", "b1_kernels.hip", "batched_kernels.hip", "persistent_kernels.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

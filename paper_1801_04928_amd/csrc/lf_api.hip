@@ -7,6 +7,7 @@
 // With k = 1 the gradient kernels are enqueued in line on the caller's stream (sequential pass).
 #include "../../include/lf.h"
 #include "lf_internal.h"
+#include "persistent.h"
 
 #include <new>
 #include <string>
@@ -28,6 +29,11 @@ struct Layout {
     size_t dbf_off, dbf_stride;      // bfloat16 copies of delta (bf16 nets only)
     size_t partial_off, partial_bytes;
     size_t raw_off, raw_bytes;
+    // persistent single-sample path: tagged-word exchange buffers, pointer tables, abort word
+    size_t x_off, x_words;           // [2][kMaxGroups][N]
+    size_t dll_off, all_off, ll_words;   // [L-1][N] each
+    size_t tab_off, tab_bytes;       // w, b, nabla_w, nabla_b pointer tables, L-1 entries each
+    size_t abort_off;
     size_t total;
 };
 
@@ -55,6 +61,14 @@ Layout make_layout(int L, int N, int B, lf_dtype dt) {
     y.raw_off = off;
     y.raw_bytes = single_sample_path(N, B, dt) ? 0 : align_up(lf::split_workspace_floats(N, B, dt == LF_BF16) * 4);
     off += y.raw_bytes;
+    if (single_sample_path(N, B, dt) && lf::persistent_supported(N)) {
+        y.x_off = off;   y.x_words = (size_t)2 * lf::kMaxGroups * N;  off += align_up(y.x_words * 8);
+        y.ll_words = M * (size_t)N;
+        y.dll_off = off; off += align_up(y.ll_words * 8);
+        y.all_off = off; off += align_up(y.ll_words * 8);
+        y.tab_off = off; y.tab_bytes = 4 * M * sizeof(void*);         off += align_up(y.tab_bytes);
+        y.abort_off = off; off += kAlign;
+    }
     y.total = off;
     return y;
 }
@@ -79,6 +93,13 @@ struct lf_net {
     std::vector<hipEvent_t> ev_delta;  // index l-2
     std::vector<hipEvent_t> ev_done;   // per worker stream
     std::string err;
+    // persistent path
+    bool p_ready, p_tables_dirty;
+    int p_groups;
+    unsigned p_epoch;
+    int* p_abort_host;                 // pinned, mapped; the kernels raise it when a wait gives up
+    int* p_abort_dev_view;             // the same word as the device addresses it
+    std::vector<const void*> p_tables;
 
     void* a_ptr(int l) const {         // l = 1..L
         return l == 1 ? const_cast<void*>(x1) : ws + lay.a_off + (size_t)(l - 2) * lay.a_stride;
@@ -127,6 +148,97 @@ lf_status ensure_workers(lf_net* net, int k) {
     return LF_OK;
 }
 
+bool persistent_possible(const lf_net* net) {
+    return single_sample_path(net->N, net->B, net->dt) && lf::persistent_supported(net->N);
+}
+
+bool use_persistent(const lf_net* net) {
+    if (net->sched == LF_SCHED_STREAMS) return false;
+    return persistent_possible(net);
+}
+
+// A persistent kernel whose wait gave up has raised the pinned abort word.
+lf_status check_abort(lf_net* net) {
+    const int code = net->p_abort_host ? *reinterpret_cast<volatile int*>(net->p_abort_host) : 0;
+    if (code) {
+        static const char* const site[] = {"?", "forward gather", "chain gather", "gradient wait"};
+        return fail(net, LF_EHIP,
+                    std::string("a persistent kernel gave up waiting for its peers (") + site[(code >> 24) & 3] +
+                        ", layer " + std::to_string((code >> 10) & 0x3fff) + ", workgroup " +
+                        std::to_string(code & 0x3ff) + "); results are invalid");
+    }
+    return LF_OK;
+}
+
+// One-time device set-up of the persistent path, and upload of the pointer tables when they changed.
+lf_status prepare_persistent(lf_net* net, hipStream_t s) {
+    if (!net->p_ready) {
+        int dev = 0, cus = 0;
+        LF_HIP(net, hipGetDevice(&dev));
+        LF_HIP(net, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        net->p_groups = lf::persistent_groups(net->N, cus);
+        if (lf::persistent_rows_per_group(net->N, net->p_groups) > lf::kMaxRowsPerGroup)
+            return fail(net, LF_EUNSUPPORTED, "persistent path: too few compute units for this N");
+        if (!net->p_abort_host) {
+            void* h = nullptr;
+            LF_HIP(net, hipHostMalloc(&h, sizeof(int), hipHostMallocMapped));
+            net->p_abort_host = static_cast<int*>(h);
+            *net->p_abort_host = 0;
+            void* d = nullptr;
+            LF_HIP(net, hipHostGetDevicePointer(&d, h, 0));
+            net->p_abort_dev_view = static_cast<int*>(d);
+        }
+        // tagged words start as tag 0 (never a valid tag); the abort word as 0
+        LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.x_off, net->lay.x_words, 0ull, s));
+        LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.dll_off, net->lay.ll_words, 0ull, s));
+        LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.all_off, net->lay.ll_words, 0ull, s));
+        LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.abort_off, kAlign / 8, 0ull, s));
+        net->p_epoch = 0;
+        net->p_ready = true;
+    }
+    if (net->p_tables_dirty) {
+        const size_t M = (size_t)net->L - 1;
+        net->p_tables.resize(4 * M);
+        for (size_t i = 0; i < M; ++i) {
+            net->p_tables[i] = net->w[i];
+            net->p_tables[M + i] = net->b[i];
+            net->p_tables[2 * M + i] = net->gw[i];
+            net->p_tables[3 * M + i] = net->gb[i];
+        }
+        // ordered on the stream behind any kernel that still reads the old tables
+        LF_HIP(net, hipMemcpyAsync(net->ws + net->lay.tab_off, net->p_tables.data(), net->lay.tab_bytes,
+                                   hipMemcpyHostToDevice, s));
+        LF_HIP(net, hipStreamSynchronize(s));   // the staging vector may be rewritten after return
+        net->p_tables_dirty = false;
+    }
+    return LF_OK;
+}
+
+lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
+    const size_t M = (size_t)net->L - 1;
+    lf::PersistArgs A{};
+    A.L = net->L; A.N = net->N; A.G = net->p_groups;
+    A.RPG = lf::persistent_rows_per_group(net->N, net->p_groups);
+    A.k = k < net->p_groups ? k : net->p_groups;   // never more partitions than workgroups
+    if (++net->p_epoch >= (1u << 19)) net->p_epoch = 1;    // tags carry 19 epoch bits + 13 layer bits
+    A.epoch = net->p_epoch;
+    void** tab = reinterpret_cast<void**>(net->ws + net->lay.tab_off);
+    A.w = reinterpret_cast<const float* const*>(tab);
+    A.b = reinterpret_cast<const float* const*>(tab + M);
+    A.gw = reinterpret_cast<float* const*>(tab + 2 * M);
+    A.gb = reinterpret_cast<float* const*>(tab + 3 * M);
+    A.a1 = static_cast<const float*>(net->x1);
+    A.a_base = reinterpret_cast<float*>(net->ws + net->lay.a_off);  A.a_stride = net->lay.a_stride / 4;
+    A.d_base = reinterpret_cast<float*>(net->ws + net->lay.d_off);  A.d_stride = net->lay.d_stride / 4;
+    A.X = reinterpret_cast<unsigned long long*>(net->ws + net->lay.x_off);
+    A.DLL = reinterpret_cast<unsigned long long*>(net->ws + net->lay.dll_off);
+    A.ALL = reinterpret_cast<unsigned long long*>(net->ws + net->lay.all_off);
+    A.y = static_cast<const float*>(y);
+    A.abort_dev = reinterpret_cast<int*>(net->ws + net->lay.abort_off);
+    A.abort_host = net->p_abort_dev_view;
+    return A;
+}
+
 // (bp3),(bp4) of layer l on stream s.
 lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
     const int i = l - 2;
@@ -171,6 +283,8 @@ lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost
     net->lay = make_layout(L, N, B, dt);
     net->x1 = nullptr;
     net->have_params = net->have_grads = net->fwd_done = net->bwd_done = false;
+    net->p_ready = false; net->p_tables_dirty = true; net->p_groups = 0; net->p_epoch = 0;
+    net->p_abort_host = nullptr; net->p_abort_dev_view = nullptr;
     net->err = "no error";
     try {
         net->w.assign(L - 1, nullptr); net->b.assign(L - 1, nullptr);
@@ -193,6 +307,7 @@ lf_status lf_set_params(lf_net* net, const void* const* w, const void* const* b)
     }
     for (int i = 0; i < net->L - 1; ++i) { net->w[i] = w[i]; net->b[i] = static_cast<const float*>(b[i]); }
     net->have_params = true;
+    net->p_tables_dirty = true;
     net->fwd_done = net->bwd_done = false;
     return LF_OK;
 }
@@ -207,6 +322,7 @@ lf_status lf_set_grad_buffers(lf_net* net, float* const* nabla_w, float* const* 
     }
     for (int i = 0; i < net->L - 1; ++i) { net->gw[i] = nabla_w[i]; net->gb[i] = nabla_b[i]; }
     net->have_grads = true;
+    net->p_tables_dirty = true;
     net->bwd_done = false;
     return LF_OK;
 }
@@ -219,7 +335,11 @@ lf_status lf_set_schedule(lf_net* net, lf_sched sched) {
             net->sched = sched;
             return LF_OK;
         case LF_SCHED_PERSISTENT:
-            return fail(net, LF_EUNSUPPORTED, "lf_set_schedule: no persistent-kernel path for this shape");
+            if (!persistent_possible(net))
+                return fail(net, LF_EUNSUPPORTED,
+                            "lf_set_schedule: the persistent path needs B = 1, fp32, N <= 8192");
+            net->sched = sched;
+            return LF_OK;
         default:
             return fail(net, LF_EINVAL, "lf_set_schedule: unknown schedule");
     }
@@ -231,10 +351,20 @@ lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream) {
     if (!aligned16(x1)) return fail(net, LF_EINVAL, "lf_forward: x1 must be 16-byte aligned");
     if (!net->have_params) return fail(net, LF_ESTATE, "lf_forward: call lf_set_params first");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    lf_status st0 = check_abort(net);
+    if (st0 != LF_OK) return st0;
     net->x1 = x1;
     net->fwd_done = false;
     net->bwd_done = false;
     const bool bf = net->dt == LF_BF16;
+    if (use_persistent(net)) {
+        st0 = prepare_persistent(net, s);
+        if (st0 != LF_OK) return st0;
+        const lf::PersistArgs A = persist_args(net, nullptr, 1);
+        LF_HIP(net, lf::launch_fwd_persistent(A, s));
+        net->fwd_done = true;
+        return LF_OK;
+    }
     for (int l = 2; l <= net->L; ++l) {
         if (single_sample_path(net->N, net->B, net->dt)) {
             LF_HIP(net, lf::launch_fwd_gemv_f32(static_cast<const float*>(net->w[l - 2]), net->b[l - 2],
@@ -262,7 +392,17 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
     const bool bf = net->dt == LF_BF16;
     const bool b1 = single_sample_path(N, B, net->dt);
     net->bwd_done = false;
-    lf_status st = ensure_workers(net, k);
+    lf_status st = check_abort(net);
+    if (st != LF_OK) return st;
+    if (use_persistent(net)) {
+        st = prepare_persistent(net, s);
+        if (st != LF_OK) return st;
+        const lf::PersistArgs A = persist_args(net, y, k);
+        LF_HIP(net, lf::launch_bwd_persistent(A, s));
+        net->bwd_done = true;
+        return LF_OK;
+    }
+    st = ensure_workers(net, k);
     if (st != LF_OK) return st;
     const int nstreams = (int)net->workers.size() < k ? (int)net->workers.size() : k;
     std::vector<char> used(nstreams > 0 ? nstreams : 1, 0);
@@ -308,6 +448,8 @@ lf_status lf_grads(lf_net* net, int l, const float** nabla_w, const float** nabl
     if (!net) return LF_EINVAL;
     if (l < 2 || l > net->L) return fail(net, LF_EINVAL, "lf_grads: layer index must be in 2..L");
     if (!net->bwd_done) return fail(net, LF_ESTATE, "lf_grads: no backward pass has been enqueued");
+    const lf_status st = check_abort(net);
+    if (st != LF_OK) return st;
     if (nabla_w) *nabla_w = net->gw[l - 2];
     if (nabla_b) *nabla_b = net->gb[l - 2];
     return LF_OK;
@@ -334,6 +476,7 @@ void lf_destroy(lf_net* net) {
     for (hipStream_t s : net->workers) (void)hipStreamDestroy(s);
     for (hipEvent_t e : net->ev_delta) (void)hipEventDestroy(e);
     for (hipEvent_t e : net->ev_done) (void)hipEventDestroy(e);
+    if (net->p_abort_host) (void)hipHostFree(net->p_abort_host);
     delete net;
 }
 

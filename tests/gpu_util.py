@@ -59,9 +59,17 @@ def run_gpu(net, k, sched=None, poison=True):
     return g
 
 
-def poison_buffers(g):
-    """NaN in every buffer the pass must overwrite: a read before the producer has written shows up."""
-    g.workspace.view(g.torch.float32)[: g.workspace.numel() // 4].fill_(float("nan"))
+def poison_buffers(g, whole_workspace=True):
+    """NaN in every buffer the pass must overwrite: a read before the producer has written shows up.
+    whole_workspace=True (only before the first pass of a handle) also covers the library's internal
+    exchange buffers; afterwards only the activations and errors are poisoned, because the tagged
+    words of the persistent path must keep the tags of the previous pass."""
+    if whole_workspace:
+        g.workspace.view(g.torch.float32)[: g.workspace.numel() // 4].fill_(float("nan"))
+    else:
+        for l in range(2, g.L + 1):
+            g.activation(l).fill_(float("nan"))
+            g.delta(l).fill_(float("nan"))
     for t in g.nabla_w + g.nabla_b:
         t.fill_(float("nan"))
 

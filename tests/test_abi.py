@@ -39,7 +39,7 @@ def test_workspace_bytes():
     assert P.lf_workspace_bytes(8, 256, 1, 7) == 0
     n = P.lf_workspace_bytes(8, 256, 1, P.LF_F32)
     assert n >= 7 * 256 * 4 * 2 and n % 256 == 0                   # a^2..a^L and delta^2..delta^L
-    assert P.lf_workspace_bytes(8, 256, 4, P.LF_F32) > n
+    assert P.lf_workspace_bytes(8, 256, 8, P.LF_F32) > P.lf_workspace_bytes(8, 256, 2, P.LF_F32)
 
 
 FAKE = 1 << 20   # a "device pointer" that is only checked for alignment, never dereferenced on the host

@@ -14,7 +14,11 @@ def _free(g):
     g.close()
 
 
+SCHEDS = {"streams": 1, "persistent": 2}   # LF_SCHED_STREAMS, LF_SCHED_PERSISTENT
+
+
 # ---------------------------------------------------------------- single sample, fp32
+@pytest.mark.parametrize("sched", ["streams", "persistent"])
 @pytest.mark.parametrize("L,N,k", [
     (2, 256, 1),        # one weight layer
     (3, 4, 2),          # smallest width
@@ -25,19 +29,20 @@ def _free(g):
     (3, 4100, 2),       # rows-per-wave 16 path, ragged
     (9, 512, 8),        # k = L-1, the largest allowed
 ])
-def test_single_sample_fp32_matches_oracle(L, N, k):
+def test_single_sample_fp32_matches_oracle(L, N, k, sched):
     net = make_net(L, N, 1, seed=L * 1000 + N)
-    g = run_gpu(net, k)
+    g = run_gpu(net, k, sched=SCHEDS[sched])
     rep = check_against_oracle(net, g)
-    log(f"B=1 L={L} N={N} k={k}: worst normwise error {rep['worst']:.2e}")
+    log(f"B=1 L={L} N={N} k={k} {sched}: worst normwise error {rep['worst']:.2e}")
     _free(g)
 
 
-def test_single_sample_outer_product_is_exact():
+@pytest.mark.parametrize("sched", ["streams", "persistent"])
+def test_single_sample_outer_product_is_exact(sched):
     """Eq. (bp4) at B = 1 is one multiplication per entry: nabla_w^l[j][k] must equal
     fl32(delta^l[j] * a^{l-1}[k]) of the GPU's own delta and a, bit for bit; nabla_b^l = delta^l."""
     net = make_net(6, 772, 1, seed=5)
-    g = run_gpu(net, 2)
+    g = run_gpu(net, 2, sched=SCHEDS[sched])
     for l in range(2, 7):
         d = to_np(g.delta(l))[0].astype(np.float32)
         a = to_np(g.activation(l - 1))[0].astype(np.float32)
@@ -47,13 +52,15 @@ def test_single_sample_outer_product_is_exact():
     _free(g)
 
 
-@pytest.mark.parametrize("L,N,B,dtype", [(12, 1024, 1, "f32"), (6, 392, 5, "f32"), (6, 264, 9, "bf16")])
-def test_gradients_bit_identical_for_every_k(L, N, B, dtype):
+@pytest.mark.parametrize("L,N,B,dtype,sched", [
+    (12, 1024, 1, "f32", "streams"), (12, 1024, 1, "f32", "persistent"), (7, 2052, 1, "f32", "persistent"),
+    (6, 392, 5, "f32", None), (6, 264, 9, "bf16", None)])
+def test_gradients_bit_identical_for_every_k(L, N, B, dtype, sched):
     """Leapfrogging only reassigns who computes (bp3),(bp4) (Theorem 1): same bits for every k."""
     net = make_net(L, N, B, dtype=dtype, seed=77)
     ref = None
     for k in (1, 2, 4, 5, L - 1):
-        g = run_gpu(net, k)
+        g = run_gpu(net, k, sched=SCHEDS.get(sched))
         cur = [(to_np(g.grads(l)[0]).copy(), to_np(g.grads(l)[1]).copy()) for l in range(2, L + 1)]
         if ref is None:
             ref = cur
@@ -64,15 +71,17 @@ def test_gradients_bit_identical_for_every_k(L, N, B, dtype):
         _free(g)
 
 
-def test_repeated_passes_are_deterministic_and_overwrite():
-    """Gradients are overwritten (not accumulated) and identical on every pass; buffers are poisoned
-    with NaN between passes so a worker that ran ahead of its delta would show."""
+@pytest.mark.parametrize("sched", ["streams", "persistent"])
+def test_repeated_passes_are_deterministic_and_overwrite(sched):
+    """Gradients are overwritten (not accumulated) and identical on every pass; the activations,
+    errors and gradients are poisoned with NaN between passes so a worker that ran ahead of its
+    delta would show."""
     import torch
     net = make_net(10, 640, 1, seed=3)
-    g = run_gpu(net, 4)
+    g = run_gpu(net, 4, sched=SCHEDS[sched])
     first = [to_np(g.grads(l)[0]).copy() for l in range(2, 11)]
     for _ in range(20):
-        poison_buffers(g)
+        poison_buffers(g, whole_workspace=False)
         g.forward()
         g.backward(4)
     torch.cuda.synchronize()
@@ -140,12 +149,13 @@ def test_config1_full():
     _free(g)
 
 
+@pytest.mark.parametrize("sched", ["streams", "persistent"])
 @pytest.mark.parametrize("k", [1, 2, 4, 8])
-def test_config2_full(k):
+def test_config2_full(k, sched):
     net = config_net("cfg2", cache=True)
-    g = run_gpu(net, k)
+    g = run_gpu(net, k, sched=SCHEDS[sched])
     rep = check_against_oracle(net, g)
-    log(f"cfg2 k={k}: worst {rep['worst']:.2e}")
+    log(f"cfg2 k={k} {sched}: worst {rep['worst']:.2e}")
     _free(g)
 
 
@@ -153,10 +163,11 @@ def test_config3_full():
     """L=64: delta underflows into the fp32 subnormal range near the input; those layers are
     compared in denormal ulps and listed."""
     net = config_net("cfg3", cache=True)
-    g = run_gpu(net, 8)
-    rep = check_against_oracle(net, g)
-    log(f"cfg3 k=8: worst {rep['worst']:.2e}; subnormal tensors: {rep.get('subnormal', [])}")
-    _free(g)
+    for sched, k in (("persistent", 8), ("streams", 4)):
+        g = run_gpu(net, k, sched=SCHEDS[sched])
+        rep = check_against_oracle(net, g)
+        log(f"cfg3 k={k} {sched}: worst {rep['worst']:.2e}; subnormal tensors: {rep.get('subnormal', [])}")
+        _free(g)
 
 
 def test_config4_full_sampled():
