@@ -9,6 +9,7 @@
 #include "lf_internal.h"
 #include "persistent.h"
 
+#include <cstdlib>
 #include <new>
 #include <string>
 #include <vector>
@@ -30,7 +31,6 @@ struct Layout {
     size_t partial_off, partial_bytes;
     size_t raw_off, raw_bytes;
     // persistent single-sample path: tagged-word exchange buffers, pointer tables, abort word
-    size_t x_off, x_words;           // [2][kMaxGroups][N]
     size_t dll_off, all_off, ll_words;   // [L-1][N] each
     size_t tab_off, tab_bytes;       // w, b, nabla_w, nabla_b pointer tables, L-1 entries each
     size_t abort_off;
@@ -62,7 +62,6 @@ Layout make_layout(int L, int N, int B, lf_dtype dt) {
     y.raw_bytes = single_sample_path(N, B, dt) ? 0 : align_up(lf::split_workspace_floats(N, B, dt == LF_BF16) * 4);
     off += y.raw_bytes;
     if (single_sample_path(N, B, dt) && lf::persistent_supported(N)) {
-        y.x_off = off;   y.x_words = (size_t)2 * lf::kMaxGroups * N;  off += align_up(y.x_words * 8);
         y.ll_words = M * (size_t)N;
         y.dll_off = off; off += align_up(y.ll_words * 8);
         y.all_off = off; off += align_up(y.ll_words * 8);
@@ -95,7 +94,7 @@ struct lf_net {
     std::string err;
     // persistent path
     bool p_ready, p_tables_dirty;
-    int p_groups;
+    int p_groups, p_rpg, p_bgroups, p_tpr, p_workers;
     unsigned p_epoch;
     int* p_abort_host;                 // pinned, mapped; the kernels raise it when a wait gives up
     int* p_abort_dev_view;             // the same word as the device addresses it
@@ -176,8 +175,15 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
         int dev = 0, cus = 0;
         LF_HIP(net, hipGetDevice(&dev));
         LF_HIP(net, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        net->p_groups = lf::persistent_groups(net->N, cus);
-        if (lf::persistent_rows_per_group(net->N, net->p_groups) > lf::kMaxRowsPerGroup)
+        // LF_PERSISTENT_GROUPS / LF_PERSISTENT_GROUPS_BWD: tuning overrides of the chain workgroup counts
+        const char* env = std::getenv("LF_PERSISTENT_GROUPS");
+        const char* envb = std::getenv("LF_PERSISTENT_GROUPS_BWD");
+        lf::persistent_forward_shape(net->N, cus, env ? std::atoi(env) : 0, &net->p_groups, &net->p_rpg);
+        lf::persistent_backward_shape(net->N, cus, envb ? std::atoi(envb) : (env ? std::atoi(env) : 0),
+                                      &net->p_bgroups, &net->p_tpr);
+        net->p_workers = cus < lf::kMaxGroups ? cus : lf::kMaxGroups;
+        if (net->p_workers > net->N) net->p_workers = net->N;
+        if (net->p_rpg > lf::kMaxRowsPerGroup)
             return fail(net, LF_EUNSUPPORTED, "persistent path: too few compute units for this N");
         if (!net->p_abort_host) {
             void* h = nullptr;
@@ -189,7 +195,6 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
             net->p_abort_dev_view = static_cast<int*>(d);
         }
         // tagged words start as tag 0 (never a valid tag); the abort word as 0
-        LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.x_off, net->lay.x_words, 0ull, s));
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.dll_off, net->lay.ll_words, 0ull, s));
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.all_off, net->lay.ll_words, 0ull, s));
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.abort_off, kAlign / 8, 0ull, s));
@@ -217,9 +222,11 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
 lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     const size_t M = (size_t)net->L - 1;
     lf::PersistArgs A{};
-    A.L = net->L; A.N = net->N; A.G = net->p_groups;
-    A.RPG = lf::persistent_rows_per_group(net->N, net->p_groups);
-    A.k = k < net->p_groups ? k : net->p_groups;   // never more partitions than workgroups
+    A.L = net->L; A.N = net->N;
+    A.G = net->p_groups; A.RPG = net->p_rpg;
+    A.GB = net->p_bgroups; A.TPR = net->p_tpr;
+    A.GW = net->p_workers;
+    A.k = k < net->p_workers ? k : net->p_workers;   // never more partitions than worker workgroups
     if (++net->p_epoch >= (1u << 19)) net->p_epoch = 1;    // tags carry 19 epoch bits + 13 layer bits
     A.epoch = net->p_epoch;
     void** tab = reinterpret_cast<void**>(net->ws + net->lay.tab_off);
@@ -230,7 +237,6 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     A.a1 = static_cast<const float*>(net->x1);
     A.a_base = reinterpret_cast<float*>(net->ws + net->lay.a_off);  A.a_stride = net->lay.a_stride / 4;
     A.d_base = reinterpret_cast<float*>(net->ws + net->lay.d_off);  A.d_stride = net->lay.d_stride / 4;
-    A.X = reinterpret_cast<unsigned long long*>(net->ws + net->lay.x_off);
     A.DLL = reinterpret_cast<unsigned long long*>(net->ws + net->lay.dll_off);
     A.ALL = reinterpret_cast<unsigned long long*>(net->ws + net->lay.all_off);
     A.y = static_cast<const float*>(y);
@@ -283,7 +289,7 @@ lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost
     net->lay = make_layout(L, N, B, dt);
     net->x1 = nullptr;
     net->have_params = net->have_grads = net->fwd_done = net->bwd_done = false;
-    net->p_ready = false; net->p_tables_dirty = true; net->p_groups = 0; net->p_epoch = 0;
+    net->p_ready = false; net->p_tables_dirty = true; net->p_groups = net->p_rpg = net->p_bgroups = net->p_tpr = 0; net->p_workers = 0; net->p_epoch = 0;
     net->p_abort_host = nullptr; net->p_abort_dev_view = nullptr;
     net->err = "no error";
     try {
@@ -337,7 +343,7 @@ lf_status lf_set_schedule(lf_net* net, lf_sched sched) {
         case LF_SCHED_PERSISTENT:
             if (!persistent_possible(net))
                 return fail(net, LF_EUNSUPPORTED,
-                            "lf_set_schedule: the persistent path needs B = 1, fp32, N <= 8192");
+                            "lf_set_schedule: the persistent path needs B = 1, fp32, N <= 4096");
             net->sched = sched;
             return LF_OK;
         default:

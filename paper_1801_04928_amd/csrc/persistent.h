@@ -5,12 +5,15 @@
 
 namespace lf {
 
-constexpr int kMaxGroups = 256;          // workgroups of a persistent kernel (one per compute unit)
-constexpr int kMaxRowsPerGroup = 256;    // rows/columns one workgroup may own
-constexpr int kMaxPersistentN = 8192;
+constexpr int kMaxGroups = 256;          // chain workgroups of a persistent kernel (one per compute unit)
+constexpr int kMaxRowsPerGroup = 256;    // rows one forward workgroup may own
+constexpr int kMaxPersistentN = 4096;    // wider nets take the stream schedule
 
 struct PersistArgs {
-    int L, N, G, RPG, k;
+    int L, N;
+    int G, RPG;                          // forward: workgroups, rows per workgroup
+    int GB, TPR;                         // backward chain: workgroups, float4 column groups per strip
+    int GW, k;                           // gradient worker workgroups (k >= 2), worker partitions
     unsigned epoch;                      // tag of this launch's words (never 0)
     const float* const* w;               // device tables, index l-2
     const float* const* b;
@@ -19,7 +22,6 @@ struct PersistArgs {
     const float* a1;                     // x^1
     float* a_base;  size_t a_stride;     // a^l = a_base + (l-2)*a_stride  (floats), l >= 2
     float* d_base;  size_t d_stride;     // delta^l likewise
-    unsigned long long* X;               // [2][G][N] partial column sums of the chain step
     unsigned long long* DLL;             // [L-1][N]  delta^l as tagged words
     unsigned long long* ALL;             // [L-1][N]  a^l as tagged words (forward)
     const float* y;
@@ -27,9 +29,11 @@ struct PersistArgs {
     int* abort_host;                     // mapped pinned host word, or null
 };
 
-int persistent_groups(int N, int num_cus);
 bool persistent_supported(int N);
-int persistent_rows_per_group(int N, int G);
+// Launch shapes for width N on a device with num_cus compute units; requested > 0 overrides the
+// default number of workgroups.
+void persistent_forward_shape(int N, int num_cus, int requested, int* G, int* rpg);
+void persistent_backward_shape(int N, int num_cus, int requested, int* GB, int* tpr);
 hipError_t launch_fill_u64(void* p, size_t n_words, unsigned long long v, hipStream_t s);
 hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s);
 hipError_t launch_bwd_persistent(const PersistArgs& A, hipStream_t s);

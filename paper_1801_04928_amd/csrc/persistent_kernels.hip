@@ -2,29 +2,30 @@
 //
 // At B = 1 a layer step moves one N x N matrix and the chain has 2(L-1) dependent steps, so for
 // N ~ 1K the pass is bound by the latency of whatever separates two steps.  Here one kernel per
-// direction stays resident (one workgroup per compute unit, G <= 256 workgroups) and walks all layers;
-// consecutive layers are separated by a single exchange through memory, not by a kernel boundary.
+// direction stays resident and walks all layers; consecutive layers are separated by one exchange
+// through memory (an all-gather of N values), not by a kernel boundary.
 //
 // Exchange format ("tagged words"): a 64-bit word = (fp32 value, 32-bit tag), written and read with
 // relaxed agent-scope 64-bit atomics.  Value and tag arrive together, so a reader that sees the tag it
-// expects has the value: no fence, no separate flag.  Tags change with every pass (epoch) and layer,
-// so buffers are never cleared between passes.  These words are the per-layer ready flags that feed
-// the k workers of section 3.
+// expects has the value: no fence, no separate flag.  The tag is the pass's epoch, so buffers are never
+// cleared between passes.  The words of delta^l are also the per-layer ready flags that feed the k
+// workers of section 3.
 //
-// Ownership: workgroup g owns the index block J_g = [g*RPG, (g+1)*RPG) of every layer.
-//   forward  (z),(a): g computes a^l[J_g] from rows J_g of w^l (needs all of a^{l-1}: gathered from the
-//                     tagged words the owners published), publishes a^l[J_g].
-//   backward (bp2):   g holds delta^{l+1}[J_g], forms the partial column sums of rows J_g of w^{l+1}
-//                     (all N columns), publishes them; then gathers, for its columns J_g, the partials
-//                     of every workgroup, adds them in workgroup order and applies sigma'.  One
-//                     exchange per layer; the sum order depends on (N, G) only.
-//   (bp3),(bp4):      layer l belongs to worker (L-l) mod k = the workgroups with g mod k equal to it.
-//                     They split its rows, wait for delta^l through its tagged words and stream
-//                     nabla_w^l out with non-temporal stores in the gaps of the chain (k >= 2), or in
-//                     line before the next chain step (k = 1, the sequential pass).
+//   forward  (z),(a): workgroup g owns a block of rows of w^l, hence of a^l.  It gathers all of a^{l-1}
+//                     (tagged words published by the owners), forms its a^l entries, publishes them.
+//   backward (bp2):   workgroup g owns a block of COLUMNS of w^{l+1}, hence of delta^l: it reads its
+//                     64-byte-wide strip of every row, so each column sum is formed inside one
+//                     workgroup (fixed order) and the exchange is again an all-gather, of delta^l.
+//                     Strips of workgroups that share an L2 (equal g mod 8) are adjacent in memory.
+//   (bp3),(bp4):      layer l belongs to worker (L-l) mod k.  With k >= 2 the workers are separate
+//                     workgroups of the same kernel (partition j = those with index mod k == j); they
+//                     split the rows of nabla_w^l, wait for delta^l through its tagged words and stream
+//                     the gradient out with non-temporal stores while the chain moves on; the chain
+//                     never waits for them.  With k = 1 (the sequential pass) the chain workgroups
+//                     form the gradients in line, before stepping to the next layer.
 //
-// Every wait is bounded: a poll that exceeds its spin limit raises an abort flag that all loops
-// observe, the kernel drains, and the host reports LF_EHIP.
+// Every wait is bounded: a poll that exceeds its spin limit raises an abort word that all loops
+// observe, the kernel drains, and the host reports LF_EHIP with the place of the failed wait.
 #include "lf_internal.h"
 #include "persistent.h"
 
@@ -67,27 +68,50 @@ struct Abort {
     }
 };
 
-// Poll up to four consecutive tagged words until all carry `tag`.  n in 1..4 words are valid.
+// Poll up to four consecutive tagged words until all carry `tag`; n in 1..4 of them are valid.
+// The four loads of a round are always issued together (slots past n re-read word n-1), so a round
+// costs one memory round trip, not four.
 __device__ __forceinline__ void ll_wait4(const u64* p, int n, unsigned tag, float out[4], Abort& ab,
                                          int code) {
     out[0] = out[1] = out[2] = out[3] = 0.0f;
     if (n <= 0) return;
+    const u64* q[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) q[c] = p + min(c, n - 1);
     unsigned spin = 0;
     while (!ab.dead) {
         u64 w[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) w[c] = (c < n) ? ll_load(p + c) : 0;
-        bool ok = true;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) ok = ok && (c >= n || ll_tag(w[c]) == tag);
+        for (int c = 0; c < 4; ++c) w[c] = ll_load(q[c]);
+        const bool ok = ll_tag(w[0]) == tag && ll_tag(w[1]) == tag && ll_tag(w[2]) == tag && ll_tag(w[3]) == tag;
         if (ok) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) out[c] = (c < n) ? ll_val(w[c]) : 0.0f;
             return;
         }
         ++spin;
+        __builtin_amdgcn_s_sleep(2);   // a short back-off keeps the pollers from crowding the fabric
         if (spin > kSpinLimit) { ab.raise(code); return; }
         if ((spin & 255u) == 0u) ab.seen();
+    }
+}
+
+// Gather up to four groups of four consecutive tagged words (group i at p[i], valid if n[i] > 0) with all
+// sixteen loads in flight at once; groups that do not carry the tag yet are then polled one by one.
+__device__ __forceinline__ void ll_gather4x4(const u64* const p[4], const int n[4], unsigned tag,
+                                             float out[4][4], Abort& ab, int code) {
+    u64 w[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) w[i][c] = ll_load(p[i] + min(c, max(n[i], 1) - 1));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const bool ok = ll_tag(w[i][0]) == tag && ll_tag(w[i][1]) == tag && ll_tag(w[i][2]) == tag &&
+                        ll_tag(w[i][3]) == tag;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) out[i][c] = c < n[i] ? ll_val(w[i][c]) : 0.0f;
+        if (!ok && n[i] > 0) ll_wait4(p[i], n[i], tag, out[i], ab, code);
     }
 }
 
@@ -98,11 +122,11 @@ __device__ __forceinline__ const float* act_ptr(const PersistArgs& A, int l) {
 // ================================================================================================
 // forward
 // ================================================================================================
-// Q = float4 column groups per lane and row (Q*256 >= N); CH = groups fetched per chunk.
-template <int Q>
+// Q = float4 column groups per lane and row (Q*256 >= N); RF = rows per fetched chunk.  A wave owns RW
+// consecutive rows and fetches them RF at a time; the chunk after the one being used is always in
+// flight, also across the exchange between two layers.
+template <int Q, int RF>
 __global__ __launch_bounds__(kThreads) void k_fwd_persistent(const PersistArgs A) {
-    constexpr int CH = Q < 16 ? Q : 16;
-    constexpr int CPR = Q / CH;   // chunks per row
     __shared__ v4f s_a[Q * 64];
     __shared__ float s_bias[kMaxRowsPerGroup];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
@@ -110,33 +134,55 @@ __global__ __launch_bounds__(kThreads) void k_fwd_persistent(const PersistArgs A
     const int RW = (RPG + kWaves - 1) / kWaves;             // rows per wave
     const int wrow0 = g * RPG + wave * RW;                  // first row of this wave
     const int wrow_end = min(min(N, (g + 1) * RPG), wrow0 + RW);
-    const int nchunks = RW * CPR;
+    const int nchunks = (RW + RF - 1) / RF;
     Abort ab{A.abort_dev, A.abort_host, false};
 
-    auto load_chunk = [&](v4f (&buf)[CH], const float* W, int ci) {
-        const int r = ci / CPR, h = ci % CPR;
-        const int row = wrow0 + r;
-        const v4f* wp = reinterpret_cast<const v4f*>(W + (size_t)row * N);
+    auto load_chunk = [&](v4f (&buf)[RF][Q], const float* W, int ci) {
 #pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const int v = lane + 64 * (h * CH + u);
-            buf[u] = (row < wrow_end && v < nvec) ? wp[v] : v4f{0.f, 0.f, 0.f, 0.f};
+        for (int rr = 0; rr < RF; ++rr) {
+            // rows / column groups past the end re-read valid ones; their results are never used
+            const int row = min(wrow0 + ci * RF + rr, N - 1);
+            const v4f* wp = reinterpret_cast<const v4f*>(W + (size_t)row * N);
+#pragma unroll
+            for (int u = 0; u < Q; ++u) buf[rr][u] = wp[min(lane + 64 * u, nvec - 1)];
         }
     };
 
-    v4f cur[CH], nxt[CH];
-    load_chunk(cur, A.w[0], 0);
+    // A wait for one load also waits for every older load and store of the wave.  So nothing slow is
+    // requested just before the weights in flight are awaited: next layer's bias is requested right
+    // after this layer's results are published, where its latency overlaps the exchange.
+    const bool own = t < RPG && g * RPG + t < N;
+    float bias_next = own ? A.b[0][g * RPG + t] : 0.0f;
+    v4f cur[RF][Q], nxt[RF][Q];
+    load_chunk(nxt, A.w[0], 0);
     for (int l = 2; l <= L; ++l) {
-        if (t < RPG && g * RPG + t < N) s_bias[t] = A.b[l - 2][g * RPG + t];   // off the critical path
+        if (own) s_bias[t] = bias_next;
         // gather a^{l-1} into LDS
         if (l == 2) {
             for (int v = t; v < nvec; v += kThreads) s_a[v] = reinterpret_cast<const v4f*>(A.a1)[v];
         } else {
             const u64* src = A.ALL + (size_t)(l - 3) * N;    // words of a^{l-1}
-            for (int v = t; v < nvec; v += kThreads) {
-                float o[4];
-                ll_wait4(src + 4 * v, 4, A.epoch, o, ab, abort_code(1, l, g));
-                s_a[v] = v4f{o[0], o[1], o[2], o[3]};
+            if (nvec <= kThreads) {
+                if (t < nvec) {
+                    float o[4];
+                    ll_wait4(src + 4 * t, 4, A.epoch, o, ab, abort_code(1, l, g));
+                    s_a[t] = v4f{o[0], o[1], o[2], o[3]};
+                }
+            } else
+            for (int v0 = t; v0 < nvec; v0 += 4 * kThreads) {
+                const u64* gp[4];
+                int gn[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int v = v0 + i * kThreads;
+                    gn[i] = v < nvec ? 4 : 0;
+                    gp[i] = src + 4 * min(v, nvec - 1);
+                }
+                float o[4][4];
+                ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(1, l, g));
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (gn[i]) s_a[v0 + i * kThreads] = v4f{o[i][0], o[i][1], o[i][2], o[i][3]};
             }
         }
         __syncthreads();
@@ -144,33 +190,41 @@ __global__ __launch_bounds__(kThreads) void k_fwd_persistent(const PersistArgs A
         const float* Wn = l < L ? A.w[l - 1] : nullptr;
         float* a_out = A.a_base + (size_t)(l - 2) * A.a_stride;
         u64* pub = A.ALL + (size_t)(l - 2) * N;
-        float acc = 0.0f;
         for (int ci = 0; ci < nchunks; ++ci) {
-            if (ci + 1 < nchunks) load_chunk(nxt, W, ci + 1);
-            else if (Wn) load_chunk(nxt, Wn, 0);             // next layer's first chunk, across the exchange
-            const int r = ci / CPR, h = ci % CPR;
+            // take over the chunk requested one iteration (or one layer) ago, then request the next
 #pragma unroll
-            for (int u = 0; u < CH; ++u) {
-                const int v = lane + 64 * (h * CH + u);
+            for (int rr = 0; rr < RF; ++rr)
+#pragma unroll
+                for (int u = 0; u < Q; ++u) cur[rr][u] = nxt[rr][u];
+            if (ci + 1 < nchunks) load_chunk(nxt, W, ci + 1);
+            else if (Wn) load_chunk(nxt, Wn, 0);
+            float acc[RF];
+#pragma unroll
+            for (int rr = 0; rr < RF; ++rr) acc[rr] = 0.0f;
+#pragma unroll
+            for (int u = 0; u < Q; ++u) {
+                const int v = lane + 64 * u;
                 const v4f a = v < nvec ? s_a[v] : v4f{0.f, 0.f, 0.f, 0.f};
-                acc = fmaf(cur[u].x, a.x, acc);
-                acc = fmaf(cur[u].y, a.y, acc);
-                acc = fmaf(cur[u].z, a.z, acc);
-                acc = fmaf(cur[u].w, a.w, acc);
+#pragma unroll
+                for (int rr = 0; rr < RF; ++rr) {
+                    acc[rr] = fmaf(cur[rr][u].x, a.x, acc[rr]);
+                    acc[rr] = fmaf(cur[rr][u].y, a.y, acc[rr]);
+                    acc[rr] = fmaf(cur[rr][u].z, a.z, acc[rr]);
+                    acc[rr] = fmaf(cur[rr][u].w, a.w, acc[rr]);
+                }
             }
-            if (h == CPR - 1) {
-                const int row = wrow0 + r;
-                const float z = wave_sum(acc);
+#pragma unroll
+            for (int rr = 0; rr < RF; ++rr) {
+                const int row = wrow0 + ci * RF + rr;
+                const float z = wave_sum(acc[rr]);
                 if (lane == 0 && row < wrow_end) {
                     const float a = sigmoidf(z + s_bias[row - g * RPG]);
-                    a_out[row] = a;
                     if (l < L) ll_store(pub + row, a, A.epoch);
+                    a_out[row] = a;
                 }
-                acc = 0.0f;
             }
-#pragma unroll
-            for (int u = 0; u < CH; ++u) cur[u] = nxt[u];
         }
+        if (own && l < L) bias_next = A.b[l - 1][g * RPG + t];
         __syncthreads();   // s_a is rewritten by the next layer's gather
     }
 }
@@ -178,184 +232,221 @@ __global__ __launch_bounds__(kThreads) void k_fwd_persistent(const PersistArgs A
 // ================================================================================================
 // backward
 // ================================================================================================
-// P = float4 column groups per thread (P*1024 >= N).
-template <int P>
-__global__ __launch_bounds__(kThreads) void k_bwd_persistent(const PersistArgs A) {
-    constexpr int RC = P <= 4 ? 4 : 2;     // rows per fetched chunk (RC*P float4 in flight per thread)
-    __shared__ float s_delta[kMaxRowsPerGroup];
-    __shared__ float s_red[kWaves][kMaxRowsPerGroup];
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
-    const int N = A.N, L = A.L, G = A.G, RPG = A.RPG, k = A.k, nvec = N >> 2;
-    const int row0 = g * RPG;
-    const int nrows = max(0, min(RPG, N - row0));
-    const int nchunks = (RPG + RC - 1) / RC;
-    Abort ab{A.abort_dev, A.abort_host, false};
+constexpr int PG = kMaxPersistentN / 1024;   // float4 column groups a thread covers in a gradient row
 
-    // ---- gradient jobs of this workgroup: layers l = L - part - m k, rows [jrow_begin, jrow_end)
-    const int part = g % k, member = g / k, members = (G - part + k - 1) / k;
-    const int RM = (N + members - 1) / members;
-    const int jrow_begin = min(N, member * RM), jrow_end = min(N, jrow_begin + RM);
-    int job_layer = L - part, job_row = jrow_begin;
-    bool ja_loaded = false;
-    v4f ja[P];
-
-    // Store up to max_rows rows of pending gradient work whose delta is published.  With `wait`
-    // the call blocks (bounded) until the rows are there; otherwise it returns at the first row that
-    // is not ready.  Layers above `lowest_ready` have their delta computed by the whole grid.
-    auto grad_rows = [&](int max_rows, int lowest_ready, bool wait) {
-        while (max_rows > 0 && job_layer >= 2 && job_layer >= lowest_ready && !ab.dead) {
-            if (job_row >= jrow_end) {
-                job_layer -= k;
-                job_row = jrow_begin;
-                ja_loaded = false;
-                continue;
-            }
-            if (!ja_loaded) {
-                const v4f* ap = reinterpret_cast<const v4f*>(act_ptr(A, job_layer - 1));
+// Rows [jb, je) of nabla_w^layer and nabla_b^layer from delta values d[0..n) of rows row..row+n-1.
+__device__ __forceinline__ void store_gradient_rows(const PersistArgs& A, int layer, int row, int n,
+                                                    const float d[4], const v4f (&ja)[PG]) {
+    const int t = threadIdx.x, N = A.N, nvec = N >> 2;
+    float* gw = A.gw[layer - 2];
 #pragma unroll
-                for (int p = 0; p < P; ++p) {
-                    const int v = t + kThreads * p;
-                    ja[p] = v < nvec ? ap[v] : v4f{0.f, 0.f, 0.f, 0.f};
-                }
-                ja_loaded = true;
-            }
-            const int n = min(min(4, max_rows), jrow_end - job_row);
-            const u64* dl = A.DLL + (size_t)(job_layer - 2) * N + job_row;
-            float d[4];
-            if (wait) {
-                ll_wait4(dl, n, A.epoch, d, ab, abort_code(3, job_layer, g));
-                if (ab.dead) return;
-            } else {
-                u64 w[4];
-                bool ok = true;
+    for (int c = 0; c < 4; ++c) {
+        if (c < n) {
+            float* out = gw + (size_t)(row + c) * N;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    w[c] = c < n ? ll_load(dl + c) : 0;
-                    ok = ok && (c >= n || ll_tag(w[c]) == A.epoch);
-                    d[c] = ll_val(w[c]);
-                }
-                if (!ok) return;
-            }
-            float* gw = A.gw[job_layer - 2] + (size_t)job_row * N;
-            float* gb = A.gb[job_layer - 2] + job_row;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (c < n) {
-#pragma unroll
-                    for (int p = 0; p < P; ++p) {
-                        const int v = t + kThreads * p;
-                        if (v < nvec) {
-                            const v4f o = {d[c] * ja[p].x, d[c] * ja[p].y, d[c] * ja[p].z, d[c] * ja[p].w};
-                            __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(gw + (size_t)c * N) + v);
-                        }
-                    }
-                    if (t == 0) gb[c] = d[c];
-                }
-            }
-            job_row += n;
-            max_rows -= n;
-        }
-    };
-
-    auto load_chunk = [&](v4f (&buf)[RC][P], const float* W, int ci) {
-#pragma unroll
-        for (int rr = 0; rr < RC; ++rr) {
-            const int r = ci * RC + rr;
-            const v4f* wp = reinterpret_cast<const v4f*>(W + (size_t)(row0 + r) * N);
-#pragma unroll
-            for (int p = 0; p < P; ++p) {
+            for (int p = 0; p < PG; ++p) {
                 const int v = t + kThreads * p;
-                buf[rr][p] = (r < nrows && v < nvec) ? wp[v] : v4f{0.f, 0.f, 0.f, 0.f};
+                if (v < nvec) {
+                    const v4f o = {d[c] * ja[p].x, d[c] * ja[p].y, d[c] * ja[p].z, d[c] * ja[p].w};
+                    __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(out) + v);
+                }
+            }
+            if (t == 0) A.gb[layer - 2][row + c] = d[c];
+        }
+    }
+}
+
+__device__ __forceinline__ void load_activation_groups(const PersistArgs& A, int layer, v4f (&ja)[PG]) {
+    const v4f* ap = reinterpret_cast<const v4f*>(act_ptr(A, layer));
+    const int nvec = A.N >> 2;
+#pragma unroll
+    for (int p = 0; p < PG; ++p) ja[p] = ap[min((int)threadIdx.x + kThreads * p, nvec - 1)];
+}
+
+// Gradient workgroup (k >= 2): member of worker partition `part`; streams out its share of rows of
+// nabla_w^l, nabla_b^l for l = L - part, L - part - k, ... as soon as delta^l's words carry this
+// pass's tag.  It never feeds the chain, so the chain never waits for it.
+__device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, int nworkers, Abort& ab) {
+    const int N = A.N, L = A.L, k = A.k;
+    const int part = wid % k, member = wid / k, members = (nworkers - part + k - 1) / k;
+    const int RM = (N + members - 1) / members;
+    const int jb = min(N, member * RM), je = min(N, jb + RM);
+    if (jb >= je) return;
+    for (int layer = L - part; layer >= 2 && !ab.dead; layer -= k) {
+        v4f ja[PG];
+        load_activation_groups(A, layer - 1, ja);
+        const u64* dl = A.DLL + (size_t)(layer - 2) * N;
+        // words of the first group; afterwards the next group's words are requested before the
+        // current group's rows are stored
+        u64 nw[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) nw[c] = ll_load(dl + min(jb + c, je - 1));
+        for (int row = jb; row < je && !ab.dead; row += 4) {
+            const int n = min(4, je - row);
+            u64 cw[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) cw[c] = nw[c];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) nw[c] = ll_load(dl + min(row + 4 + c, je - 1));   // next group
+            const bool ok = ll_tag(cw[0]) == A.epoch && ll_tag(cw[1]) == A.epoch &&
+                            ll_tag(cw[2]) == A.epoch && ll_tag(cw[3]) == A.epoch;
+            float d[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) d[c] = ll_val(cw[c]);
+            if (!ok) {
+                ll_wait4(dl + row, n, A.epoch, d, ab, abort_code(3, layer, (int)blockIdx.x));
+                if (ab.dead) return;
+            }
+            store_gradient_rows(A, layer, row, n, d, ja);
+        }
+    }
+}
+
+// Workgroups [0, GB) run the delta chain; workgroups [GB, gridDim.x) are the gradient workers
+// (present when k >= 2).  TPR = threads per 16*TPR-byte row segment of the owned column strip;
+// CH = float4 loads per fetched chunk (the chunk after the one in use is always in flight, also
+// across the exchange).  At most 256 registers per thread, so that a chain and a gradient workgroup
+// fit one compute unit.
+template <int TPR, int CH>
+__global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArgs A) {
+    constexpr int CPG = 4 * TPR;              // columns per chain workgroup
+    constexpr int RPP = kThreads / TPR;       // rows covered by one load of the whole workgroup
+    __shared__ v4f s_delta4[kMaxPersistentN / 4];       // delta^{l+1}, all of it
+    __shared__ v4f s_red[kWaves][TPR];
+    float* s_delta = reinterpret_cast<float*>(s_delta4);
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
+    const int N = A.N, L = A.L, GB = A.GB, k = A.k, nvec = N >> 2;
+    Abort ab{A.abort_dev, A.abort_host, false};
+    if (g >= GB) {
+        gradient_worker(A, g - GB, (int)gridDim.x - GB, ab);
+        return;
+    }
+    // strips of workgroups on one XCD (workgroups are dealt to the 8 XCDs round-robin) are adjacent
+    const int strip = (GB % 8 == 0) ? (g % 8) * (GB / 8) + g / 8 : g;
+    const int col0 = strip * CPG;
+    const int cg = t % TPR, rs = t / TPR;
+    const int col = min(col0 + 4 * cg, N - 4);           // a partial last strip re-reads valid columns
+    const int nloads = (N + RPP - 1) / RPP, nchunks = (nloads + CH - 1) / CH;
+    // rows of the sequential pass's in-line gradients
+    const int RPGb = (N + GB - 1) / GB, jrow0 = min(N, g * RPGb), jrow1 = min(N, jrow0 + RPGb);
+
+    auto load_chunk = [&](v4f (&buf)[CH], const float* W, int ci) {
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int row = min(rs + RPP * (ci * CH + u), N - 1);   // rows past the end: delta taken as 0
+            buf[u] = *reinterpret_cast<const v4f*>(W + (size_t)row * N + col);
+        }
+    };
+    auto inline_grads = [&](int layer) {        // k = 1: rows [jrow0, jrow1) of layer's gradients
+        v4f ja[PG];
+        load_activation_groups(A, layer - 1, ja);
+        for (int row = jrow0; row < jrow1; row += 4) {
+            const int n = min(4, jrow1 - row);
+            float d[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) d[c] = s_delta[min(row + c, N - 1)];
+            store_gradient_rows(A, layer, row, n, d, ja);
+        }
+    };
+    // all of delta^layer, from its tagged words, into LDS
+    auto gather_delta = [&](int layer) {
+        const u64* src = A.DLL + (size_t)(layer - 2) * N;
+        if (nvec <= kThreads) {
+            if (t < nvec) {
+                float o[4];
+                ll_wait4(src + 4 * t, 4, A.epoch, o, ab, abort_code(2, layer, g));
+                s_delta4[t] = v4f{o[0], o[1], o[2], o[3]};
+            }
+        } else {
+            for (int v0 = t; v0 < nvec; v0 += 4 * kThreads) {
+                const u64* gp[4];
+                int gn[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int v = v0 + i * kThreads;
+                    gn[i] = v < nvec ? 4 : 0;
+                    gp[i] = src + 4 * min(v, nvec - 1);
+                }
+                float o[4][4];
+                ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(2, layer, g));
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (gn[i]) s_delta4[v0 + i * kThreads] = v4f{o[i][0], o[i][1], o[i][2], o[i][3]};
             }
         }
     };
 
-    v4f cur[RC][P], nxt[RC][P];
-    if (L > 2) load_chunk(cur, A.w[L - 2], 0);      // rows J_g of w^L, needed by the first chain step
+    // A wait for one load also waits for every older load and store of the wave.  So nothing slow is
+    // requested just before the strip loads in flight are awaited: a^{l-1} (for the next step's sigma')
+    // is requested right after delta^l is published, where its latency overlaps the exchange.
+    const bool own = t < CPG && col0 + t < N;
+    float a_next = (own && L > 2) ? act_ptr(A, L - 1)[col0 + t] : 0.0f;
+    v4f cur[CH], nxt[CH];
+    if (L > 2) load_chunk(nxt, A.w[L - 2], 0);      // my strip of w^L, needed by the first chain step
 
-    // (bp1): delta^L on the owned block
-    if (t < nrows) {
-        const int j = row0 + t;
-        const float a = act_ptr(A, L)[j];
-        const float d = (a - A.y[j]) * (a * (1.0f - a));
-        s_delta[t] = d;
-        A.d_base[(size_t)(L - 2) * A.d_stride + j] = d;
-        ll_store(A.DLL + (size_t)(L - 2) * N + j, d, A.epoch);
+    // (bp1): every chain workgroup forms all of delta^L (N cheap elements, no exchange); the owner of
+    // a column block also stores and publishes it
+    {
+        const float* aL = act_ptr(A, L);
+        for (int i = t; i < N; i += kThreads) {
+            const float a = aL[i];
+            s_delta[i] = (a - A.y[i]) * (a * (1.0f - a));
+        }
+        __syncthreads();
+        if (own) {
+            const float d = s_delta[col0 + t];
+            ll_store(A.DLL + (size_t)(L - 2) * N + col0 + t, d, A.epoch);
+            A.d_base[(size_t)(L - 2) * A.d_stride + col0 + t] = d;
+        }
     }
-    __syncthreads();
 
     for (int l = L - 1; l >= 2; --l) {
-        // k = 1: the gradients of layer l+1 sit on the chain, before the step to layer l
-        if (k == 1) grad_rows(RPG, l + 1, true);
+        const float a_l = a_next;
+        if (k == 1) inline_grads(l + 1);
 
-        const float a_l = t < nrows ? act_ptr(A, l)[row0 + t] : 0.0f;   // for sigma', off the critical path
-
-        // partial column sums over the owned rows of w^{l+1}
+        // column sums of my strip of w^{l+1}: sum_j w[j][c] delta^{l+1}[j]
         const float* W = A.w[l - 1];
         const float* Wn = l > 2 ? A.w[l - 2] : nullptr;
-        v4f acc[P];
-#pragma unroll
-        for (int p = 0; p < P; ++p) acc[p] = v4f{0.f, 0.f, 0.f, 0.f};
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
         for (int ci = 0; ci < nchunks; ++ci) {
+            // take over the chunk requested one iteration (or one step) ago, then request the next
+#pragma unroll
+            for (int u = 0; u < CH; ++u) cur[u] = nxt[u];
             if (ci + 1 < nchunks) load_chunk(nxt, W, ci + 1);
-            else if (Wn) load_chunk(nxt, Wn, 0);        // next step's first chunk, across the exchange
+            else if (Wn) load_chunk(nxt, Wn, 0);
 #pragma unroll
-            for (int rr = 0; rr < RC; ++rr) {
-                const int r = ci * RC + rr;
-                const float d = r < nrows ? s_delta[r] : 0.0f;
-#pragma unroll
-                for (int p = 0; p < P; ++p) {
-                    acc[p].x = fmaf(cur[rr][p].x, d, acc[p].x);
-                    acc[p].y = fmaf(cur[rr][p].y, d, acc[p].y);
-                    acc[p].z = fmaf(cur[rr][p].z, d, acc[p].z);
-                    acc[p].w = fmaf(cur[rr][p].w, d, acc[p].w);
-                }
-            }
-#pragma unroll
-            for (int rr = 0; rr < RC; ++rr)
-#pragma unroll
-                for (int p = 0; p < P; ++p) cur[rr][p] = nxt[rr][p];
-        }
-        // publish: X[parity][g][column]
-        const unsigned tagx = (A.epoch << 13) | (unsigned)l;
-        u64* xw = A.X + ((size_t)(l & 1) * G + g) * N;
-#pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const int v = t + kThreads * p;
-            if (v < nvec) {
-                ll_store(xw + 4 * v + 0, acc[p].x, tagx);
-                ll_store(xw + 4 * v + 1, acc[p].y, tagx);
-                ll_store(xw + 4 * v + 2, acc[p].z, tagx);
-                ll_store(xw + 4 * v + 3, acc[p].w, tagx);
+            for (int u = 0; u < CH; ++u) {
+                const int row = rs + RPP * (ci * CH + u);
+                const float d = row < N ? s_delta[row] : 0.0f;
+                acc.x = fmaf(cur[u].x, d, acc.x);
+                acc.y = fmaf(cur[u].y, d, acc.y);
+                acc.z = fmaf(cur[u].z, d, acc.z);
+                acc.w = fmaf(cur[u].w, d, acc.w);
             }
         }
-        // k >= 2: gradient work fills the wait for the other workgroups' partials
-        if (k > 1) grad_rows(2 * RPG, l + 1, false);
-
-        // gather the partials of my columns from every workgroup (thread t <-> workgroup t), add them
-        const u64* xr = A.X + ((size_t)(l & 1) * G + t) * N + row0;
-        for (int i0 = 0; i0 < RPG; i0 += 4) {
-            float v[4];
-            ll_wait4(xr + i0, t < G ? min(4, nrows - i0) : 0, tagx, v, ab, abort_code(2, l, g));
+        // add the threads that share a column group: lanes by butterfly, then the four waves in order
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const float s = wave_sum(v[c]);
-                if (lane == 0) s_red[wave][i0 + c] = s;
-            }
+        for (int off = TPR; off < kWave; off <<= 1) {
+            acc.x += __shfl_xor(acc.x, off, kWave);
+            acc.y += __shfl_xor(acc.y, off, kWave);
+            acc.z += __shfl_xor(acc.z, off, kWave);
+            acc.w += __shfl_xor(acc.w, off, kWave);
         }
+        if (lane < TPR) s_red[wave][lane] = acc;
         __syncthreads();
-        if (t < nrows) {
-            const int j = row0 + t;
-            const float u = ((s_red[0][t] + s_red[1][t]) + s_red[2][t]) + s_red[3][t];
+        if (own) {
+            const int q = t >> 2, e = t & 3;
+            const float u = ((s_red[0][q][e] + s_red[1][q][e]) + s_red[2][q][e]) + s_red[3][q][e];
             const float d = u * (a_l * (1.0f - a_l));
-            s_delta[t] = d;
-            A.d_base[(size_t)(l - 2) * A.d_stride + j] = d;
-            ll_store(A.DLL + (size_t)(l - 2) * N + j, d, A.epoch);
+            ll_store(A.DLL + (size_t)(l - 2) * N + col0 + t, d, A.epoch);
+            A.d_base[(size_t)(l - 2) * A.d_stride + col0 + t] = d;
+            if (l > 2) a_next = act_ptr(A, l - 1)[col0 + t];
         }
+        // exchange: all of delta^l (every workgroup is past its last read of delta^{l+1})
+        gather_delta(l);
         __syncthreads();
     }
-    // drain: whatever gradient work is left (all of it has its delta on the way)
-    grad_rows(0x7fffffff, 2, true);
+    if (k == 1) inline_grads(2);
 }
 
 __global__ __launch_bounds__(kThreads) void k_fill_u64(u64* p, size_t n, u64 v) {
@@ -365,21 +456,31 @@ __global__ __launch_bounds__(kThreads) void k_fill_u64(u64* p, size_t n, u64 v) 
 
 }  // namespace
 
-// Every workgroup must own at least one row: a workgroup is throttled by the gather of its own
-// columns, and one with nothing to gather would run ahead and overwrite exchange words (two buffers,
-// reused every other layer) that slower workgroups have not read yet.
-int persistent_groups(int N, int num_cus) {
-    int G = (N + 3) / 4;
-    if (G > kMaxGroups) G = kMaxGroups;
-    if (num_cus > 0 && G > num_cus) G = num_cus;
-    if (G < 1) G = 1;
-    const int rpg = (N + G - 1) / G;
-    return (N + rpg - 1) / rpg;
-}
-
 bool persistent_supported(int N) { return N % 4 == 0 && N >= 4 && N <= kMaxPersistentN; }
 
-int persistent_rows_per_group(int N, int G) { return (N + G - 1) / G; }
+// Forward: G workgroups, each owning rpg rows; every workgroup owns at least one row.
+void persistent_forward_shape(int N, int num_cus, int requested, int* G, int* rpg) {
+    int g = requested > 0 ? requested : (N <= 2048 ? 128 : kMaxGroups);
+    if (g > (N + 3) / 4) g = (N + 3) / 4;
+    if (g > kMaxGroups) g = kMaxGroups;
+    if (num_cus > 0 && g > num_cus) g = num_cus;
+    if (g < 1) g = 1;
+    *rpg = (N + g - 1) / g;
+    *G = (N + *rpg - 1) / *rpg;
+}
+
+// Backward chain: GB workgroups, each owning a strip of 4*tpr columns, tpr in {1, 2, 4, 8}.
+void persistent_backward_shape(int N, int num_cus, int requested, int* GB, int* tpr) {
+    int g = requested > 0 ? requested : (N <= 2048 ? 128 : kMaxGroups);
+    if (g > kMaxGroups) g = kMaxGroups;
+    if (num_cus > 0 && g > num_cus) g = num_cus;
+    if (g < 1) g = 1;
+    const int groups4 = (N + 3) / 4;                    // float4 column groups
+    int need = (groups4 + g - 1) / g, tp = 1;
+    while (tp < need && tp < 8) tp <<= 1;
+    *tpr = tp;
+    *GB = (groups4 + tp - 1) / tp;                       // may exceed g only if tp was capped at 8
+}
 
 hipError_t launch_fill_u64(void* p, size_t n_words, unsigned long long v, hipStream_t s) {
     if (n_words == 0) return hipSuccess;
@@ -388,21 +489,42 @@ hipError_t launch_fill_u64(void* p, size_t n_words, unsigned long long v, hipStr
 }
 
 hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s) {
-    const int q = (A.N / 4 + 63) / 64;
-    if (q <= 4) k_fwd_persistent<4><<<A.G, kThreads, 0, s>>>(A);
-    else if (q <= 8) k_fwd_persistent<8><<<A.G, kThreads, 0, s>>>(A);
-    else if (q <= 16) k_fwd_persistent<16><<<A.G, kThreads, 0, s>>>(A);
-    else k_fwd_persistent<32><<<A.G, kThreads, 0, s>>>(A);
+    const int q = (A.N / 4 + 63) / 64;                       // float4 groups per lane and row
+    const int rw = (A.RPG + kWaves - 1) / kWaves;            // rows per wave
+    if (q <= 4) {
+        if (rw >= 4) k_fwd_persistent<4, 4><<<A.G, kThreads, 0, s>>>(A);
+        else if (rw >= 2) k_fwd_persistent<4, 2><<<A.G, kThreads, 0, s>>>(A);
+        else k_fwd_persistent<4, 1><<<A.G, kThreads, 0, s>>>(A);
+    } else if (q <= 8) {
+        if (rw >= 2) k_fwd_persistent<8, 2><<<A.G, kThreads, 0, s>>>(A);
+        else k_fwd_persistent<8, 1><<<A.G, kThreads, 0, s>>>(A);
+    } else if (q <= 16) {
+        k_fwd_persistent<16, 1><<<A.G, kThreads, 0, s>>>(A);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <int TPR>
+static hipError_t launch_bwd_tpr(const PersistArgs& A, int grid, hipStream_t s) {
+    const int nloads = (A.N + kThreads / TPR - 1) / (kThreads / TPR);
+    if (nloads <= 4) k_bwd_persistent<TPR, 4><<<grid, kThreads, 0, s>>>(A);
+    else if (nloads <= 8) k_bwd_persistent<TPR, 8><<<grid, kThreads, 0, s>>>(A);
+    else k_bwd_persistent<TPR, 16><<<grid, kThreads, 0, s>>>(A);
     return hipGetLastError();
 }
 
 hipError_t launch_bwd_persistent(const PersistArgs& A, hipStream_t s) {
-    const int p = (A.N / 4 + kThreads - 1) / kThreads;
-    if (p <= 1) k_bwd_persistent<1><<<A.G, kThreads, 0, s>>>(A);
-    else if (p <= 2) k_bwd_persistent<2><<<A.G, kThreads, 0, s>>>(A);
-    else if (p <= 4) k_bwd_persistent<4><<<A.G, kThreads, 0, s>>>(A);
-    else k_bwd_persistent<8><<<A.G, kThreads, 0, s>>>(A);
-    return hipGetLastError();
+    if (A.GB > kMaxGroups * 2 || A.N > kMaxPersistentN) return hipErrorInvalidValue;
+    const int grid = A.GB + (A.k > 1 ? A.GW : 0);    // chain workgroups, then the gradient workers
+    switch (A.TPR) {
+        case 1: return launch_bwd_tpr<1>(A, grid, s);
+        case 2: return launch_bwd_tpr<2>(A, grid, s);
+        case 4: return launch_bwd_tpr<4>(A, grid, s);
+        case 8: return launch_bwd_tpr<8>(A, grid, s);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace lf

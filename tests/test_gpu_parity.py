@@ -26,10 +26,20 @@ SCHEDS = {"streams": 1, "persistent": 2}   # LF_SCHED_STREAMS, LF_SCHED_PERSISTE
     (8, 256, 2),        # configuration 1's shape
     (6, 1000, 3),       # not a multiple of any tile
     (4, 2052, 3),       # rows-per-wave 8 path, ragged
-    (3, 4100, 2),       # rows-per-wave 16 path, ragged
+    (3, 4100, 2),       # rows-per-wave 16 path, ragged (wider than the persistent path: streams only)
+    (4, 4096, 3),       # widest net of the persistent path
+    (4, 3076, 2),       # persistent path, ragged, 4 column groups per thread
     (9, 512, 8),        # k = L-1, the largest allowed
 ])
 def test_single_sample_fp32_matches_oracle(L, N, k, sched):
+    if sched == "persistent" and N > 4096:
+        import paper_1801_04928_amd as P
+        g = P.LeapfrogNet(L, N, 1, "f32")
+        with pytest.raises(P.LfError) as e:
+            g.set_schedule(P.LF_SCHED_PERSISTENT)
+        assert e.value.status == P.LF_EUNSUPPORTED
+        _free(g)
+        return
     net = make_net(L, N, 1, seed=L * 1000 + N)
     g = run_gpu(net, k, sched=SCHEDS[sched])
     rep = check_against_oracle(net, g)
