@@ -16,6 +16,34 @@ typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;
 
+// A 128-bit load that is known to hit global memory.  Pointers that travel through LDS or a table
+// lose their address space; a generic ("flat") load would then be counted against the LDS counter
+// as well, and the next LDS wait would also wait for every such load in flight.
+typedef const __attribute__((address_space(1))) v4f* global_v4f_ptr;
+__device__ __forceinline__ v4f load_global_v4f(const float* p) { return *(global_v4f_ptr)(p); }
+// Buffer addressing: the base lives in four scalar registers, each load supplies one 32-bit byte
+// offset, and an offset at or past `bytes` makes the load return zeros instead of touching memory.
+// The pointer is made wave-uniform first (a resource in vector registers would be loaded lane by lane).
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void* p, unsigned bytes) {
+    const unsigned long long a = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+    void* q = reinterpret_cast<void*>(((unsigned long long)hi << 32) | lo);
+    return __builtin_amdgcn_make_buffer_rsrc(q, 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ v4f buffer_load_v4f(__amdgpu_buffer_rsrc_t r, unsigned byte_offset) {
+    return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, 0));
+}
+
+// Streaming (non-temporal) 128-bit store to global memory.
+__device__ __forceinline__ void store_global_nt_v4f(float* p, v4f v) {
+    __builtin_nontemporal_store(v, (__attribute__((address_space(1))) v4f*)(p));
+}
+__device__ __forceinline__ void store_global_f32(float* p, float v) {
+    *(__attribute__((address_space(1))) float*)(p) = v;
+}
+
 // sigma(z) = 1/(1+e^-z), section 2.  Accurate expf and an IEEE division: the
 // O(N) epilogues are never the bottleneck.
 __device__ __forceinline__ float sigmoidf(float z) { return 1.0f / (1.0f + expf(-z)); }

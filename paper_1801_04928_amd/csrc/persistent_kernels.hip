@@ -37,6 +37,8 @@ typedef unsigned long long u64;
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr unsigned kSpinLimit = 4u << 20;   // polls before a wait gives up (seconds, not microseconds)
+constexpr int kTableLds = 1024;             // per-layer pointers kept in LDS (deeper nets read the rest
+                                            // from the device table, one memory round trip per step)
 
 __device__ __forceinline__ u64 ll_pack(float v, unsigned tag) {
     return ((u64)tag << 32) | (u64)__float_as_uint(v);
@@ -129,22 +131,30 @@ template <int Q, int RF>
 __global__ __launch_bounds__(kThreads) void k_fwd_persistent(const PersistArgs A) {
     __shared__ v4f s_a[Q * 64];
     __shared__ float s_bias[kMaxRowsPerGroup];
+    __shared__ const float* s_w[kTableLds];      // w^l and b^l pointers: a table entry fetched from
+    __shared__ const float* s_b[kTableLds];      // memory on the chain would cost a round trip per layer
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
     const int N = A.N, L = A.L, RPG = A.RPG, nvec = N >> 2;
+    for (int i = t; i < min(L - 1, kTableLds); i += kThreads) { s_w[i] = A.w[i]; s_b[i] = A.b[i]; }
+    __syncthreads();
+    auto wptr = [&](int i) { return i < kTableLds ? s_w[i] : A.w[i]; };
+    auto bptr = [&](int i) { return i < kTableLds ? s_b[i] : A.b[i]; };
     const int RW = (RPG + kWaves - 1) / kWaves;             // rows per wave
     const int wrow0 = g * RPG + wave * RW;                  // first row of this wave
     const int wrow_end = min(min(N, (g + 1) * RPG), wrow0 + RW);
-    const int nchunks = (RW + RF - 1) / RF;
+    int nchunks = (RW + RF - 1) / RF;
+    if (nchunks > 1) nchunks = (nchunks + 1) & ~1;        // even: see `layer` below
     Abort ab{A.abort_dev, A.abort_host, false};
 
     auto load_chunk = [&](v4f (&buf)[RF][Q], const float* W, int ci) {
 #pragma unroll
         for (int rr = 0; rr < RF; ++rr) {
-            // rows / column groups past the end re-read valid ones; their results are never used
+            // one buffer per row: column groups past its end load zeros; rows past the end of the
+            // matrix re-read the last row (their results are never used)
             const int row = min(wrow0 + ci * RF + rr, N - 1);
-            const v4f* wp = reinterpret_cast<const v4f*>(W + (size_t)row * N);
+            const __amdgpu_buffer_rsrc_t r = make_buffer(W + (size_t)row * N, (unsigned)N * 4u);
 #pragma unroll
-            for (int u = 0; u < Q; ++u) buf[rr][u] = wp[min(lane + 64 * u, nvec - 1)];
+            for (int u = 0; u < Q; ++u) buf[rr][u] = buffer_load_v4f(r, (unsigned)(lane + 64 * u) * 16u);
         }
     };
 
@@ -152,80 +162,105 @@ __global__ __launch_bounds__(kThreads) void k_fwd_persistent(const PersistArgs A
     // requested just before the weights in flight are awaited: next layer's bias is requested right
     // after this layer's results are published, where its latency overlaps the exchange.
     const bool own = t < RPG && g * RPG + t < N;
-    float bias_next = own ? A.b[0][g * RPG + t] : 0.0f;
-    v4f cur[RF][Q], nxt[RF][Q];
-    load_chunk(nxt, A.w[0], 0);
-    for (int l = 2; l <= L; ++l) {
-        if (own) s_bias[t] = bias_next;
-        // gather a^{l-1} into LDS
+    float bias_next = own ? bptr(0)[g * RPG + t] : 0.0f;
+
+    // a^{l-1}, from the tagged words its owners published, into LDS
+    auto gather_activation = [&](int l) {
         if (l == 2) {
             for (int v = t; v < nvec; v += kThreads) s_a[v] = reinterpret_cast<const v4f*>(A.a1)[v];
-        } else {
-            const u64* src = A.ALL + (size_t)(l - 3) * N;    // words of a^{l-1}
-            if (nvec <= kThreads) {
-                if (t < nvec) {
-                    float o[4];
-                    ll_wait4(src + 4 * t, 4, A.epoch, o, ab, abort_code(1, l, g));
-                    s_a[t] = v4f{o[0], o[1], o[2], o[3]};
-                }
-            } else
-            for (int v0 = t; v0 < nvec; v0 += 4 * kThreads) {
-                const u64* gp[4];
-                int gn[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int v = v0 + i * kThreads;
-                    gn[i] = v < nvec ? 4 : 0;
-                    gp[i] = src + 4 * min(v, nvec - 1);
-                }
-                float o[4][4];
-                ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(1, l, g));
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (gn[i]) s_a[v0 + i * kThreads] = v4f{o[i][0], o[i][1], o[i][2], o[i][3]};
-            }
+            return;
         }
-        __syncthreads();
-        const float* W = A.w[l - 2];
-        const float* Wn = l < L ? A.w[l - 1] : nullptr;
-        float* a_out = A.a_base + (size_t)(l - 2) * A.a_stride;
-        u64* pub = A.ALL + (size_t)(l - 2) * N;
-        for (int ci = 0; ci < nchunks; ++ci) {
-            // take over the chunk requested one iteration (or one layer) ago, then request the next
-#pragma unroll
-            for (int rr = 0; rr < RF; ++rr)
-#pragma unroll
-                for (int u = 0; u < Q; ++u) cur[rr][u] = nxt[rr][u];
-            if (ci + 1 < nchunks) load_chunk(nxt, W, ci + 1);
-            else if (Wn) load_chunk(nxt, Wn, 0);
-            float acc[RF];
-#pragma unroll
-            for (int rr = 0; rr < RF; ++rr) acc[rr] = 0.0f;
-#pragma unroll
-            for (int u = 0; u < Q; ++u) {
-                const int v = lane + 64 * u;
-                const v4f a = v < nvec ? s_a[v] : v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int rr = 0; rr < RF; ++rr) {
-                    acc[rr] = fmaf(cur[rr][u].x, a.x, acc[rr]);
-                    acc[rr] = fmaf(cur[rr][u].y, a.y, acc[rr]);
-                    acc[rr] = fmaf(cur[rr][u].z, a.z, acc[rr]);
-                    acc[rr] = fmaf(cur[rr][u].w, a.w, acc[rr]);
-                }
+        const u64* src = A.ALL + (size_t)(l - 3) * N;
+        if (nvec <= kThreads) {
+            if (t < nvec) {
+                float o[4];
+                ll_wait4(src + 4 * t, 4, A.epoch, o, ab, abort_code(1, l, g));
+                s_a[t] = v4f{o[0], o[1], o[2], o[3]};
             }
+            return;
+        }
+        for (int v0 = t; v0 < nvec; v0 += 4 * kThreads) {
+            const u64* gp[4];
+            int gn[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int v = v0 + i * kThreads;
+                gn[i] = v < nvec ? 4 : 0;
+                gp[i] = src + 4 * min(v, nvec - 1);
+            }
+            float o[4][4];
+            ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(1, l, g));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (gn[i]) s_a[v0 + i * kThreads] = v4f{o[i][0], o[i][1], o[i][2], o[i][3]};
+        }
+    };
+    // rows ci*RF .. of this wave: dot products with a^{l-1}, bias, sigma, publish
+    auto finish_chunk = [&](const v4f (&buf)[RF][Q], int ci, int l) {
+        float acc[RF];
+#pragma unroll
+        for (int rr = 0; rr < RF; ++rr) acc[rr] = 0.0f;
+#pragma unroll
+        for (int u = 0; u < Q; ++u) {
+            const int v = lane + 64 * u;
+            const v4f av = s_a[min(v, Q * 64 - 1)];
+            const v4f a = v < nvec ? av : v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int rr = 0; rr < RF; ++rr) {
-                const int row = wrow0 + ci * RF + rr;
-                const float z = wave_sum(acc[rr]);
-                if (lane == 0 && row < wrow_end) {
-                    const float a = sigmoidf(z + s_bias[row - g * RPG]);
-                    if (l < L) ll_store(pub + row, a, A.epoch);
-                    a_out[row] = a;
-                }
+                acc[rr] = fmaf(buf[rr][u].x, a.x, acc[rr]);
+                acc[rr] = fmaf(buf[rr][u].y, a.y, acc[rr]);
+                acc[rr] = fmaf(buf[rr][u].z, a.z, acc[rr]);
+                acc[rr] = fmaf(buf[rr][u].w, a.w, acc[rr]);
             }
         }
-        if (own && l < L) bias_next = A.b[l - 1][g * RPG + t];
+        float* a_out = A.a_base + (size_t)(l - 2) * A.a_stride;
+        u64* pub = A.ALL + (size_t)(l - 2) * N;
+#pragma unroll
+        for (int rr = 0; rr < RF; ++rr) {
+            const int row = wrow0 + ci * RF + rr;
+            const float z = wave_sum(acc[rr]);
+            if (lane == 0 && row < wrow_end) {
+                const float a = sigmoidf(z + s_bias[row - g * RPG]);
+                if (l < L) ll_store(pub + row, a, A.epoch);
+                a_out[row] = a;
+            }
+        }
+    };
+    // One layer.  On entry bufA holds (possibly still in flight) this wave's first chunk of w^l.  The
+    // two buffers alternate so that the chunk after the one in use is always in flight -- also across
+    // the exchange -- without any register copy.  With one chunk per layer the next layer's chunk ends
+    // up in bufB; with an even number of chunks it ends up in bufA again.
+    auto layer = [&](v4f (&bufA)[RF][Q], v4f (&bufB)[RF][Q], int l) {
+        if (own) s_bias[t] = bias_next;
+        gather_activation(l);
+        __syncthreads();
+        const float* W = wptr(l - 2);
+        const float* Wn = l < L ? wptr(l - 1) : nullptr;
+        if (nchunks == 1) {
+            if (Wn) load_chunk(bufB, Wn, 0);
+            finish_chunk(bufA, 0, l);
+        } else {
+            for (int ci = 0; ci < nchunks; ci += 2) {
+                load_chunk(bufB, W, ci + 1);
+                finish_chunk(bufA, ci, l);
+                if (ci + 2 < nchunks) load_chunk(bufA, W, ci + 2);
+                else if (Wn) load_chunk(bufA, Wn, 0);
+                finish_chunk(bufB, ci + 1, l);
+            }
+        }
+        if (own && l < L) bias_next = bptr(l - 1)[g * RPG + t];
         __syncthreads();   // s_a is rewritten by the next layer's gather
+    };
+
+    v4f buf0[RF][Q], buf1[RF][Q];
+    load_chunk(buf0, wptr(0), 0);
+    if (nchunks == 1) {
+        for (int l = 2; l <= L; l += 2) {
+            layer(buf0, buf1, l);
+            if (l + 1 <= L) layer(buf1, buf0, l + 1);
+        }
+    } else {
+        for (int l = 2; l <= L; ++l) layer(buf0, buf1, l);
     }
 }
 
@@ -248,19 +283,19 @@ __device__ __forceinline__ void store_gradient_rows(const PersistArgs& A, int la
                 const int v = t + kThreads * p;
                 if (v < nvec) {
                     const v4f o = {d[c] * ja[p].x, d[c] * ja[p].y, d[c] * ja[p].z, d[c] * ja[p].w};
-                    __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(out) + v);
+                    store_global_nt_v4f(out + 4 * v, o);
                 }
             }
-            if (t == 0) A.gb[layer - 2][row + c] = d[c];
+            if (t == 0) store_global_f32(A.gb[layer - 2] + row + c, d[c]);
         }
     }
 }
 
 __device__ __forceinline__ void load_activation_groups(const PersistArgs& A, int layer, v4f (&ja)[PG]) {
-    const v4f* ap = reinterpret_cast<const v4f*>(act_ptr(A, layer));
+    const float* ap = act_ptr(A, layer);
     const int nvec = A.N >> 2;
 #pragma unroll
-    for (int p = 0; p < PG; ++p) ja[p] = ap[min((int)threadIdx.x + kThreads * p, nvec - 1)];
+    for (int p = 0; p < PG; ++p) ja[p] = load_global_v4f(ap + 4 * min((int)threadIdx.x + kThreads * p, nvec - 1));
 }
 
 // Gradient workgroup (k >= 2): member of worker partition `part`; streams out its share of rows of
@@ -313,6 +348,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     constexpr int RPP = kThreads / TPR;       // rows covered by one load of the whole workgroup
     __shared__ v4f s_delta4[kMaxPersistentN / 4];       // delta^{l+1}, all of it
     __shared__ v4f s_red[kWaves][TPR];
+    __shared__ const float* s_w[kTableLds];             // w^l pointers (see the forward kernel)
     float* s_delta = reinterpret_cast<float*>(s_delta4);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
     const int N = A.N, L = A.L, GB = A.GB, k = A.k, nvec = N >> 2;
@@ -321,21 +357,27 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
         gradient_worker(A, g - GB, (int)gridDim.x - GB, ab);
         return;
     }
+    for (int i = t; i < min(L - 1, kTableLds); i += kThreads) s_w[i] = A.w[i];
+    __syncthreads();
+    auto wptr = [&](int i) { return i < kTableLds ? s_w[i] : A.w[i]; };
     // strips of workgroups on one XCD (workgroups are dealt to the 8 XCDs round-robin) are adjacent
     const int strip = (GB % 8 == 0) ? (g % 8) * (GB / 8) + g / 8 : g;
     const int col0 = strip * CPG;
     const int cg = t % TPR, rs = t / TPR;
     const int col = min(col0 + 4 * cg, N - 4);           // a partial last strip re-reads valid columns
-    const int nloads = (N + RPP - 1) / RPP, nchunks = (nloads + CH - 1) / CH;
+    const int nloads = (N + RPP - 1) / RPP;
+    int nchunks = (nloads + CH - 1) / CH;
+    if (nchunks > 1) nchunks = (nchunks + 1) & ~1;        // even: see `step` below
     // rows of the sequential pass's in-line gradients
     const int RPGb = (N + GB - 1) / GB, jrow0 = min(N, g * RPGb), jrow1 = min(N, jrow0 + RPGb);
 
+    // the whole matrix is one buffer: a row past its end loads zeros
+    const unsigned strip_offset = ((unsigned)rs * (unsigned)N + (unsigned)col) * 4u;
+    const unsigned pass_bytes = (unsigned)RPP * (unsigned)N * 4u;
     auto load_chunk = [&](v4f (&buf)[CH], const float* W, int ci) {
+        const __amdgpu_buffer_rsrc_t r = make_buffer(W, (unsigned)N * (unsigned)N * 4u);
 #pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const int row = min(rs + RPP * (ci * CH + u), N - 1);   // rows past the end: delta taken as 0
-            buf[u] = *reinterpret_cast<const v4f*>(W + (size_t)row * N + col);
-        }
+        for (int u = 0; u < CH; ++u) buf[u] = buffer_load_v4f(r, strip_offset + (unsigned)(ci * CH + u) * pass_bytes);
     };
     auto inline_grads = [&](int layer) {        // k = 1: rows [jrow0, jrow1) of layer's gradients
         v4f ja[PG];
@@ -381,8 +423,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     // is requested right after delta^l is published, where its latency overlaps the exchange.
     const bool own = t < CPG && col0 + t < N;
     float a_next = (own && L > 2) ? act_ptr(A, L - 1)[col0 + t] : 0.0f;
-    v4f cur[CH], nxt[CH];
-    if (L > 2) load_chunk(nxt, A.w[L - 2], 0);      // my strip of w^L, needed by the first chain step
+    v4f buf0[CH], buf1[CH];
+    if (L > 2) load_chunk(buf0, wptr(L - 2), 0);    // my strip of w^L, needed by the first chain step
 
     // (bp1): every chain workgroup forms all of delta^L (N cheap elements, no exchange); the owner of
     // a column block also stores and publishes it
@@ -400,28 +442,38 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
         }
     }
 
-    for (int l = L - 1; l >= 2; --l) {
+    auto fma_chunk = [&](const v4f (&buf)[CH], int ci, v4f& acc) {
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int row = rs + RPP * (ci * CH + u);
+            const float dv = s_delta[min(row, N - 1)];
+            const float d = row < N ? dv : 0.0f;
+            acc.x = fmaf(buf[u].x, d, acc.x);
+            acc.y = fmaf(buf[u].y, d, acc.y);
+            acc.z = fmaf(buf[u].z, d, acc.z);
+            acc.w = fmaf(buf[u].w, d, acc.w);
+        }
+    };
+    // One chain step, delta^{l+1} -> delta^l.  On entry bufA holds (possibly still in flight) the first
+    // chunk of my strip of w^{l+1}.  The two buffers alternate so that the chunk after the one in use is
+    // always in flight -- also across the exchange -- without any register copy.  With one chunk per step
+    // the next step's chunk ends up in bufB; with an even number of chunks in bufA again.
+    auto step = [&](v4f (&bufA)[CH], v4f (&bufB)[CH], int l) {
         const float a_l = a_next;
         if (k == 1) inline_grads(l + 1);
-
-        // column sums of my strip of w^{l+1}: sum_j w[j][c] delta^{l+1}[j]
-        const float* W = A.w[l - 1];
-        const float* Wn = l > 2 ? A.w[l - 2] : nullptr;
+        const float* W = wptr(l - 1);
+        const float* Wn = l > 2 ? wptr(l - 2) : nullptr;
         v4f acc = {0.f, 0.f, 0.f, 0.f};
-        for (int ci = 0; ci < nchunks; ++ci) {
-            // take over the chunk requested one iteration (or one step) ago, then request the next
-#pragma unroll
-            for (int u = 0; u < CH; ++u) cur[u] = nxt[u];
-            if (ci + 1 < nchunks) load_chunk(nxt, W, ci + 1);
-            else if (Wn) load_chunk(nxt, Wn, 0);
-#pragma unroll
-            for (int u = 0; u < CH; ++u) {
-                const int row = rs + RPP * (ci * CH + u);
-                const float d = row < N ? s_delta[row] : 0.0f;
-                acc.x = fmaf(cur[u].x, d, acc.x);
-                acc.y = fmaf(cur[u].y, d, acc.y);
-                acc.z = fmaf(cur[u].z, d, acc.z);
-                acc.w = fmaf(cur[u].w, d, acc.w);
+        if (nchunks == 1) {
+            if (Wn) load_chunk(bufB, Wn, 0);
+            fma_chunk(bufA, 0, acc);
+        } else {
+            for (int ci = 0; ci < nchunks; ci += 2) {
+                load_chunk(bufB, W, ci + 1);
+                fma_chunk(bufA, ci, acc);
+                if (ci + 2 < nchunks) load_chunk(bufA, W, ci + 2);
+                else if (Wn) load_chunk(bufA, Wn, 0);
+                fma_chunk(bufB, ci + 1, acc);
             }
         }
         // add the threads that share a column group: lanes by butterfly, then the four waves in order
@@ -445,6 +497,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
         // exchange: all of delta^l (every workgroup is past its last read of delta^{l+1})
         gather_delta(l);
         __syncthreads();
+    };
+
+    if (nchunks == 1) {
+        for (int l = L - 1; l >= 2; l -= 2) {
+            step(buf0, buf1, l);
+            if (l - 1 >= 2) step(buf1, buf0, l - 1);
+        }
+    } else {
+        for (int l = L - 1; l >= 2; --l) step(buf0, buf1, l);
     }
     if (k == 1) inline_grads(2);
 }
@@ -460,7 +521,7 @@ bool persistent_supported(int N) { return N % 4 == 0 && N >= 4 && N <= kMaxPersi
 
 // Forward: G workgroups, each owning rpg rows; every workgroup owns at least one row.
 void persistent_forward_shape(int N, int num_cus, int requested, int* G, int* rpg) {
-    int g = requested > 0 ? requested : (N <= 2048 ? 128 : kMaxGroups);
+    int g = requested > 0 ? requested : kMaxGroups;
     if (g > (N + 3) / 4) g = (N + 3) / 4;
     if (g > kMaxGroups) g = kMaxGroups;
     if (num_cus > 0 && g > num_cus) g = num_cus;
@@ -510,8 +571,7 @@ template <int TPR>
 static hipError_t launch_bwd_tpr(const PersistArgs& A, int grid, hipStream_t s) {
     const int nloads = (A.N + kThreads / TPR - 1) / (kThreads / TPR);
     if (nloads <= 4) k_bwd_persistent<TPR, 4><<<grid, kThreads, 0, s>>>(A);
-    else if (nloads <= 8) k_bwd_persistent<TPR, 8><<<grid, kThreads, 0, s>>>(A);
-    else k_bwd_persistent<TPR, 16><<<grid, kThreads, 0, s>>>(A);
+    else k_bwd_persistent<TPR, 8><<<grid, kThreads, 0, s>>>(A);
     return hipGetLastError();
 }
 
