@@ -35,6 +35,22 @@ def algorithmic_work(spec):
             "peak": MFMA_PEAK_TFLOPS[spec.dtype], "scale": 1e12}
 
 
+def measured_traffic(cfg_name, k):
+    """HBM bytes per launch of the backward kernel from the committed rocprofv3 counter runs
+    (profiles/traffic.json), or None when the kernel source has changed since they were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    src = os.path.join(ROOT, "paper_1801_04928_amd", "csrc", "persistent_kernels.hip")
+    try:
+        rec = json.load(open(path))
+        if rec.get("kernel_source_sha256") != hashlib.sha256(open(src, "rb").read()).hexdigest():
+            return None
+        e = rec.get(f"{cfg_name}_k{k}")
+        return None if e is None else e["fetch_bytes"] + e["write_bytes"]
+    except Exception:
+        return None
+
+
 def cpu_baseline(net, budget_s=12.0):
     """The oracle as it stands, timed on the host: whole passes for the small nets; for nets whose
     pass takes minutes, two full layers (forward + chain + gradient) scaled to the whole net."""
@@ -83,6 +99,8 @@ def main():
     ap.add_argument("--k", type=int, default=0, help="workers (0 = the configuration's largest k)")
     ap.add_argument("--sched", default="auto", choices=["auto", "streams", "persistent"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
@@ -131,8 +149,19 @@ def main():
     fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
     bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        src.fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+
     work = algorithmic_work(s)
     achieved = work["bwd"] / (bwd_ms * 1e-3) / work["scale"]
+    persistent = s.B == 1 and s.dtype == "f32" and s.N <= 4096 and args.sched != "streams"
+    kernel = "k_bwd_persistent (one launch = the whole backward pass)" if persistent else \
+        "backward pass (bp1)-(bp4), all kernels"
     out = {
         "metric": "full backprop passes/sec at 1 GPU",
         "value": steps / wall,
@@ -150,9 +179,10 @@ def main():
                    "k": k, "schedule": args.sched, "weight_matrices": s.L - 1},
         "fwd_ms": fwd_ms,
         "bwd_ms": bwd_ms,
-        "roofline": {"bound": work["bound"], "kernel": "backward pass (bp1)-(bp4)", "achieved": achieved,
+        "roofline": {"bound": work["bound"], "kernel": kernel, "achieved": achieved,
                      "peak": work["peak"], "unit": work["unit"], "frac": achieved / work["peak"],
-                     "traffic": None,
+                     "traffic": measured_traffic(s.name, k) if persistent else None,
+                     "algorithmic_per_launch": work["bwd"],
                      "fwd_achieved": work["fwd"] / (fwd_ms * 1e-3) / work["scale"]},
     }
     if not args.no_cpu_baseline:
