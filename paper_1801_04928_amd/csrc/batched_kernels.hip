@@ -29,8 +29,10 @@ template <> struct Tile<float> {
 };
 template <> struct Tile<__bf16> {
     static constexpr int BK = 64;
-    static constexpr int LDA = BK + 8;     // LDS is [i][q]: a lane reads 8 consecutive q (16 bytes)
-    static constexpr int ELEMS = BM * LDA;
+    static constexpr int LDA = BK + 8;     // QC operand: LDS is [i][q], a lane reads 8 consecutive q (16 bytes)
+    static constexpr int LDI = BM + 8;     // IC operand: LDS is [q][i] as in memory; read with the transposing
+                                           // ds_read_b64_tr_b16, which hands each lane 4 consecutive q
+    static constexpr int ELEMS = BM * LDA > BK * LDI ? BM * LDA : BK * LDI;
 };
 
 struct GemmArgs {
@@ -129,15 +131,30 @@ template <> struct Stage<__bf16, true> {   // [q][i], 8 bf16 along i; 16 threads
                 for (int c = 0; c < 8; ++c) r[u][c] = (__bf16)0.0f;
         }
     }
-    __device__ void store(__bf16* s) const {   // transposes 4 q x 8 i into 8 stores of 4 q
+    __device__ void store(__bf16* s) const {   // LDS keeps the memory layout [q][i]
         const int t = threadIdx.x, iv = (t & 15) * 8, q = (t >> 4) * 4;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            const v4bf x = {r[0][c], r[1][c], r[2][c], r[3][c]};
-            *reinterpret_cast<v4bf*>(s + (iv + c) * Tile<__bf16>::LDA + q) = x;
-        }
+        for (int u = 0; u < 4; ++u) *reinterpret_cast<v8bf*>(s + (q + u) * Tile<__bf16>::LDI + iv) = r[u];
     }
 };
+
+// MFMA operand (8 consecutive q for row i = lane % 32, starting at q0 + 8 (lane / 32)) from an LDS tile kept
+// as [q][i].  ds_read_b64_tr_b16 works on groups of 16 lanes: source lane s supplies the address of four
+// consecutive i, result lane r receives element (r % 4) of source lanes r/4, 4 + r/4, 8 + r/4, 12 + r/4.
+// With source lane s pointing at row q = s/4, columns 4 (s % 4) .. +3, result lane r holds q = 0..3 at
+// column r: four consecutive q of its own row.  Two such loads give the eight values.
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ v8bf lds_operand_transposed(const __bf16* tile, int ld, int i_base, int q0) {
+    const int lane = threadIdx.x & 63, s16 = lane & 15;
+    const int q = q0 + 8 * (lane >> 5) + (s16 >> 2);
+    const int i = i_base + 16 * ((lane >> 4) & 1) + 4 * (s16 & 3);
+    typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(tile + q * ld + i));
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(tile + (q + 4) * ld + i));
+    const v8s both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(v8bf, both);
+}
 
 // ---- the kernel -------------------------------------------------------------------------------
 template <typename T, bool P_IC, bool Q_IC, int EPI>
@@ -198,11 +215,15 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g) {
             for (int kk = 0; kk < TL::BK; kk += 16) {
                 v8bf a[2], b[2];
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    a[i] = *reinterpret_cast<const v8bf*>(&s_p[(wm + i * 32 + r32) * TL::LDA + kk + half * 8]);
+                for (int i = 0; i < 2; ++i) {
+                    if constexpr (P_IC) a[i] = lds_operand_transposed(s_p, TL::LDI, wm + i * 32, kk);
+                    else a[i] = *reinterpret_cast<const v8bf*>(&s_p[(wm + i * 32 + r32) * TL::LDA + kk + half * 8]);
+                }
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    b[j] = *reinterpret_cast<const v8bf*>(&s_q[(wn + j * 32 + r32) * TL::LDA + kk + half * 8]);
+                for (int j = 0; j < 2; ++j) {
+                    if constexpr (Q_IC) b[j] = lds_operand_transposed(s_q, TL::LDI, wn + j * 32, kk);
+                    else b[j] = *reinterpret_cast<const v8bf*>(&s_q[(wn + j * 32 + r32) * TL::LDA + kk + half * 8]);
+                }
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -266,14 +287,24 @@ __global__ __launch_bounds__(kThreads) void k_split_finish(const float* __restri
     }
 }
 
-// eq. (bp3) for a minibatch: nabla_b[j] = sum_b D[b][j], b ascending.
+// eq. (bp3) for a minibatch: nabla_b[j] = sum_b D[b][j].  A workgroup owns 32 columns; its 8 row groups
+// each add every 8th sample in ascending order, then the 8 partial sums are added in group order.
 __global__ __launch_bounds__(kThreads) void k_bias_grad(const float* __restrict__ D,
                                                         float* __restrict__ nabla_b, int N, int B) {
-    const int j = blockIdx.x * kThreads + threadIdx.x;
-    if (j >= N) return;
+    __shared__ float s_part[8][32];
+    const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    const int j = blockIdx.x * 32 + c;
     float s = 0.0f;
-    for (int b = 0; b < B; ++b) s += D[(size_t)b * N + j];
-    nabla_b[j] = s;
+    if (j < N)
+        for (int b = rg; b < B; b += 8) s += D[(size_t)b * N + j];
+    s_part[rg][c] = s;
+    __syncthreads();
+    if (rg == 0 && j < N) {
+        float t = s_part[0][c];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) t += s_part[q][c];
+        nabla_b[j] = t;
+    }
 }
 
 template <typename T, bool P_IC, bool Q_IC, int EPI>
@@ -351,7 +382,7 @@ hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void
 
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
                             float* nabla_b, int N, int B, bool bf16, hipStream_t s) {
-    k_bias_grad<<<ceil_div(N, kThreads), kThreads, 0, s>>>(D, nabla_b, N, B);
+    k_bias_grad<<<ceil_div(N, 32), kThreads, 0, s>>>(D, nabla_b, N, B);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     GemmArgs g{};
