@@ -160,8 +160,12 @@ __device__ __forceinline__ v8bf lds_operand_transposed(const __bf16* tile, int l
 template <typename T, bool P_IC, bool Q_IC, int EPI>
 __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g) {
     using TL = Tile<T>;
-    __shared__ __attribute__((aligned(16))) T s_p[TL::ELEMS];
-    __shared__ __attribute__((aligned(16))) T s_q[TL::ELEMS];
+    // one block: the two operand tiles, and afterwards the staging area of the gradient epilogue
+    constexpr int kOperandBytes = 2 * TL::ELEMS * (int)sizeof(T);
+    constexpr int kEpilogueBytes = 4 * 32 * (64 + 4) * 4;       // 4 waves x 32 rows x (64+4) floats
+    __shared__ __attribute__((aligned(16))) char s_block[kOperandBytes > kEpilogueBytes ? kOperandBytes : kEpilogueBytes];
+    T* s_p = reinterpret_cast<T*>(s_block);
+    T* s_q = s_p + TL::ELEMS;
 
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -180,22 +184,20 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    Stage<T, P_IC> sp;
-    Stage<T, Q_IC> sq;
+    // Global -> register -> LDS with a prefetch distance of three k-tiles: tile kt+3 is requested while
+    // tile kt is multiplied, which covers the memory latency even when only one or two workgroups share
+    // a compute unit.  The three register stages rotate by a 3-way unrolled loop (static indexing).
+    Stage<T, P_IC> sp[3];
+    Stage<T, Q_IC> sq[3];
     const T* P = static_cast<const T*>(g.P);
     const T* Q = static_cast<const T*>(g.Q);
-    if (kt_begin < kt_end) {
-        sp.load(P, g.ldp, m0, kt_begin * TL::BK, g.M, g.K);
-        sq.load(Q, g.ldq, n0, kt_begin * TL::BK, g.Nn, g.K);
-    }
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-        sp.store(s_p);
-        sq.store(s_q);
-        __syncthreads();
-        if (kt + 1 < kt_end) {
-            sp.load(P, g.ldp, m0, (kt + 1) * TL::BK, g.M, g.K);
-            sq.load(Q, g.ldq, n0, (kt + 1) * TL::BK, g.Nn, g.K);
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+        if (kt_begin + u < kt_end) {
+            sp[u].load(P, g.ldp, m0, (kt_begin + u) * TL::BK, g.M, g.K);
+            sq[u].load(Q, g.ldq, n0, (kt_begin + u) * TL::BK, g.Nn, g.K);
         }
+    auto multiply_tile = [&]() {
         if constexpr (sizeof(T) == 4) {
 #pragma unroll
             for (int kk = 0; kk < TL::BK; kk += 2) {
@@ -231,11 +233,50 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g) {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
             }
         }
-        __syncthreads();
+    };
+    for (int kt = kt_begin; kt < kt_end; kt += 3) {
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            if (kt + u < kt_end) {
+                sp[u].store(s_p);
+                sq[u].store(s_q);
+                __syncthreads();
+                if (kt + u + 3 < kt_end) {
+                    sp[u].load(P, g.ldp, m0, (kt + u + 3) * TL::BK, g.M, g.K);
+                    sq[u].load(Q, g.ldq, n0, (kt + u + 3) * TL::BK, g.Nn, g.K);
+                }
+                multiply_tile();
+                __syncthreads();
+            }
+        }
     }
 
     // Accumulator element e of lane (r32, half) in tile (i, j) is
     // C[m0 + wm + 32 i + 8 (e/4) + 4 half + e%4][n0 + wn + 32 j + r32].
+    if constexpr (EPI == EPI_GRAD) {
+        // nabla_w is the one large output (N x N fp32): each wave turns its accumulators through a private
+        // LDS area so that a lane stores 16 contiguous bytes and a wave 4 rows x 256 contiguous bytes.
+        constexpr int LDE = 64 + 4;
+        float* stage = reinterpret_cast<float*>(s_block) + wave * 32 * LDE;
+        float* out = static_cast<float*>(g.out);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    stage[(8 * (e >> 2) + 4 * half + (e & 3)) * LDE + j * 32 + r32] = acc[i][j][e];
+            // the area is private to the wave: no barrier, LDS operations of a wave complete in order
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int row = 4 * it + (lane >> 4), c4 = (lane & 15) * 4;
+                const v4f v = *reinterpret_cast<const v4f*>(&stage[row * LDE + c4]);
+                const int m = m0 + wm + i * 32 + row, n = n0 + wn + c4;
+                if (m < g.M && n < g.Nn) store_global_nt_v4f(out + (size_t)m * g.Nn + n, v);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -322,7 +363,7 @@ int chain_splits(int N, int B, bool bf16) {
     const int tiles = ceil_div(N, BN) * ceil_div(B, BM);
     const int kt = ceil_div(N, bf16 ? Tile<__bf16>::BK : Tile<float>::BK);
     int s = 1;
-    while (tiles * s < 192 && s < 16 && kt / (s * 2) >= 4) s *= 2;
+    while (tiles * s < 512 && s < 16 && kt / (s * 2) >= 4) s *= 2;
     return s;
 }
 
