@@ -127,8 +127,10 @@ __device__ __forceinline__ const float* act_ptr(const PersistArgs& A, int l) {
 // Q = float4 column groups per lane and row (Q*256 >= N); RF = rows per fetched chunk.  A wave owns RW
 // consecutive rows and fetches them RF at a time; the chunk after the one being used is always in
 // flight, also across the exchange between two layers.
-template <int Q, int RF>
-__global__ __launch_bounds__(kThreads) void k_fwd_persistent(const PersistArgs A) {
+// SINGLE: the wave's rows of a layer are one chunk (the latency-bound small nets); otherwise an even
+// number of chunks per layer.
+template <int Q, int RF, bool SINGLE>
+__global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArgs A) {
     __shared__ v4f s_a[Q * 64];
     __shared__ float s_bias[kMaxRowsPerGroup];
     __shared__ const float* s_w[kTableLds];      // w^l and b^l pointers: a table entry fetched from
@@ -142,8 +144,7 @@ __global__ __launch_bounds__(kThreads) void k_fwd_persistent(const PersistArgs A
     const int RW = (RPG + kWaves - 1) / kWaves;             // rows per wave
     const int wrow0 = g * RPG + wave * RW;                  // first row of this wave
     const int wrow_end = min(min(N, (g + 1) * RPG), wrow0 + RW);
-    int nchunks = (RW + RF - 1) / RF;
-    if (nchunks > 1) nchunks = (nchunks + 1) & ~1;        // even: see `layer` below
+    const int nchunks = SINGLE ? 1 : (((RW + RF - 1) / RF + 1) & ~1);   // even: see `layer` below
     Abort ab{A.abort_dev, A.abort_host, false};
 
     auto load_chunk = [&](v4f (&buf)[RF][Q], const float* W, int ci) {
@@ -236,17 +237,20 @@ __global__ __launch_bounds__(kThreads) void k_fwd_persistent(const PersistArgs A
         __syncthreads();
         const float* W = wptr(l - 2);
         const float* Wn = l < L ? wptr(l - 1) : nullptr;
-        if (nchunks == 1) {
+        if constexpr (SINGLE) {
             if (Wn) load_chunk(bufB, Wn, 0);
             finish_chunk(bufA, 0, l);
         } else {
+            // both buffers enter the layer loaded (chunks 0 and 1 were requested before the exchange, so
+            // that twice as much is in flight while the workgroups wait for each other)
             for (int ci = 0; ci < nchunks; ci += 2) {
-                load_chunk(bufB, W, ci + 1);
+                if (ci > 0) load_chunk(bufB, W, ci + 1);
                 finish_chunk(bufA, ci, l);
                 if (ci + 2 < nchunks) load_chunk(bufA, W, ci + 2);
                 else if (Wn) load_chunk(bufA, Wn, 0);
                 finish_chunk(bufB, ci + 1, l);
             }
+            if (Wn) load_chunk(bufB, Wn, 1);
         }
         if (own && l < L) bias_next = bptr(l - 1)[g * RPG + t];
         __syncthreads();   // s_a is rewritten by the next layer's gather
@@ -254,7 +258,8 @@ __global__ __launch_bounds__(kThreads) void k_fwd_persistent(const PersistArgs A
 
     v4f buf0[RF][Q], buf1[RF][Q];
     load_chunk(buf0, wptr(0), 0);
-    if (nchunks == 1) {
+    if constexpr (!SINGLE) load_chunk(buf1, wptr(0), 1);
+    if constexpr (SINGLE) {
         for (int l = 2; l <= L; l += 2) {
             layer(buf0, buf1, l);
             if (l + 1 <= L) layer(buf1, buf0, l + 1);
@@ -329,6 +334,7 @@ __device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, i
 #pragma unroll
             for (int c = 0; c < 4; ++c) d[c] = ll_val(cw[c]);
             if (!ok) {
+                __builtin_amdgcn_s_sleep(64);    // off the chain: poll gently, the chain needs the fabric
                 ll_wait4(dl + row, n, A.epoch, d, ab, abort_code(3, layer, (int)blockIdx.x));
                 if (ab.dead) return;
             }
@@ -342,7 +348,8 @@ __device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, i
 // CH = float4 loads per fetched chunk (the chunk after the one in use is always in flight, also
 // across the exchange).  At most 256 registers per thread, so that a chain and a gradient workgroup
 // fit one compute unit.
-template <int TPR, int CH>
+// SINGLE: the strip of a step is one chunk; otherwise an even number of chunks per step.
+template <int TPR, int CH, bool SINGLE>
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArgs A) {
     constexpr int CPG = 4 * TPR;              // columns per chain workgroup
     constexpr int RPP = kThreads / TPR;       // rows covered by one load of the whole workgroup
@@ -366,8 +373,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     const int cg = t % TPR, rs = t / TPR;
     const int col = min(col0 + 4 * cg, N - 4);           // a partial last strip re-reads valid columns
     const int nloads = (N + RPP - 1) / RPP;
-    int nchunks = (nloads + CH - 1) / CH;
-    if (nchunks > 1) nchunks = (nchunks + 1) & ~1;        // even: see `step` below
+    const int nchunks = SINGLE ? 1 : (((nloads + CH - 1) / CH + 1) & ~1);   // even: see `step` below
     // rows of the sequential pass's in-line gradients
     const int RPGb = (N + GB - 1) / GB, jrow0 = min(N, g * RPGb), jrow1 = min(N, jrow0 + RPGb);
 
@@ -425,6 +431,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     float a_next = (own && L > 2) ? act_ptr(A, L - 1)[col0 + t] : 0.0f;
     v4f buf0[CH], buf1[CH];
     if (L > 2) load_chunk(buf0, wptr(L - 2), 0);    // my strip of w^L, needed by the first chain step
+    if constexpr (!SINGLE) {
+        if (L > 2) load_chunk(buf1, wptr(L - 2), 1);
+    }
 
     // (bp1): every chain workgroup forms all of delta^L (N cheap elements, no exchange); the owner of
     // a column block also stores and publishes it
@@ -464,17 +473,19 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
         const float* W = wptr(l - 1);
         const float* Wn = l > 2 ? wptr(l - 2) : nullptr;
         v4f acc = {0.f, 0.f, 0.f, 0.f};
-        if (nchunks == 1) {
+        if constexpr (SINGLE) {
             if (Wn) load_chunk(bufB, Wn, 0);
             fma_chunk(bufA, 0, acc);
         } else {
+            // both buffers enter the step loaded (chunks 0 and 1 were requested before the exchange)
             for (int ci = 0; ci < nchunks; ci += 2) {
-                load_chunk(bufB, W, ci + 1);
+                if (ci > 0) load_chunk(bufB, W, ci + 1);
                 fma_chunk(bufA, ci, acc);
                 if (ci + 2 < nchunks) load_chunk(bufA, W, ci + 2);
                 else if (Wn) load_chunk(bufA, Wn, 0);
                 fma_chunk(bufB, ci + 1, acc);
             }
+            if (Wn) load_chunk(bufB, Wn, 1);
         }
         // add the threads that share a column group: lanes by butterfly, then the four waves in order
 #pragma unroll
@@ -499,7 +510,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
         __syncthreads();
     };
 
-    if (nchunks == 1) {
+    if constexpr (SINGLE) {
         for (int l = L - 1; l >= 2; l -= 2) {
             step(buf0, buf1, l);
             if (l - 1 >= 2) step(buf1, buf0, l - 1);
@@ -521,10 +532,11 @@ bool persistent_supported(int N) { return N % 4 == 0 && N >= 4 && N <= kMaxPersi
 
 // Forward: G workgroups, each owning rpg rows; every workgroup owns at least one row.
 void persistent_forward_shape(int N, int num_cus, int requested, int* G, int* rpg) {
+    // up to two workgroups per compute unit (each needs at most 256 registers per thread)
     int g = requested > 0 ? requested : kMaxGroups;
     if (g > (N + 3) / 4) g = (N + 3) / 4;
-    if (g > kMaxGroups) g = kMaxGroups;
-    if (num_cus > 0 && g > num_cus) g = num_cus;
+    if (g > 2 * kMaxGroups) g = 2 * kMaxGroups;
+    if (num_cus > 0 && g > 2 * num_cus) g = 2 * num_cus;
     if (g < 1) g = 1;
     *rpg = (N + g - 1) / g;
     *G = (N + *rpg - 1) / *rpg;
@@ -553,14 +565,17 @@ hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s) {
     const int q = (A.N / 4 + 63) / 64;                       // float4 groups per lane and row
     const int rw = (A.RPG + kWaves - 1) / kWaves;            // rows per wave
     if (q <= 4) {
-        if (rw >= 4) k_fwd_persistent<4, 4><<<A.G, kThreads, 0, s>>>(A);
-        else if (rw >= 2) k_fwd_persistent<4, 2><<<A.G, kThreads, 0, s>>>(A);
-        else k_fwd_persistent<4, 1><<<A.G, kThreads, 0, s>>>(A);
+        if (rw == 1) k_fwd_persistent<4, 1, true><<<A.G, kThreads, 0, s>>>(A);
+        else if (rw == 2) k_fwd_persistent<4, 2, true><<<A.G, kThreads, 0, s>>>(A);
+        else if (rw <= 4) k_fwd_persistent<4, 4, true><<<A.G, kThreads, 0, s>>>(A);
+        else k_fwd_persistent<4, 4, false><<<A.G, kThreads, 0, s>>>(A);
     } else if (q <= 8) {
-        if (rw >= 2) k_fwd_persistent<8, 2><<<A.G, kThreads, 0, s>>>(A);
-        else k_fwd_persistent<8, 1><<<A.G, kThreads, 0, s>>>(A);
+        if (rw == 1) k_fwd_persistent<8, 1, true><<<A.G, kThreads, 0, s>>>(A);
+        else if (rw == 2) k_fwd_persistent<8, 2, true><<<A.G, kThreads, 0, s>>>(A);
+        else k_fwd_persistent<8, 2, false><<<A.G, kThreads, 0, s>>>(A);
     } else if (q <= 16) {
-        k_fwd_persistent<16, 1><<<A.G, kThreads, 0, s>>>(A);
+        if (rw == 1) k_fwd_persistent<16, 1, true><<<A.G, kThreads, 0, s>>>(A);
+        else k_fwd_persistent<16, 1, false><<<A.G, kThreads, 0, s>>>(A);
     } else {
         return hipErrorInvalidValue;
     }
@@ -570,8 +585,9 @@ hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s) {
 template <int TPR>
 static hipError_t launch_bwd_tpr(const PersistArgs& A, int grid, hipStream_t s) {
     const int nloads = (A.N + kThreads / TPR - 1) / (kThreads / TPR);
-    if (nloads <= 4) k_bwd_persistent<TPR, 4><<<grid, kThreads, 0, s>>>(A);
-    else k_bwd_persistent<TPR, 8><<<grid, kThreads, 0, s>>>(A);
+    if (nloads <= 4) k_bwd_persistent<TPR, 4, true><<<grid, kThreads, 0, s>>>(A);
+    else if (nloads <= 8) k_bwd_persistent<TPR, 8, true><<<grid, kThreads, 0, s>>>(A);
+    else k_bwd_persistent<TPR, 8, false><<<grid, kThreads, 0, s>>>(A);
     return hipGetLastError();
 }
 
