@@ -30,7 +30,7 @@ template <> struct Tile<float> {
 template <> struct Tile<__bf16> {
     static constexpr int BK = 64;
     static constexpr int LDA = BK + 8;     // QC operand: LDS is [i][q], a lane reads 8 consecutive q (16 bytes)
-    static constexpr int LDI = BM + 8;     // IC operand: LDS is [q][i] as in memory; read with the transposing
+    static constexpr int LDI = BM + 16;    // IC operand: LDS is [q][i] as in memory; read with the transposing
                                            // ds_read_b64_tr_b16, which hands each lane 4 consecutive q
     static constexpr int ELEMS = BM * LDA > BK * LDI ? BM * LDA : BK * LDI;
 };

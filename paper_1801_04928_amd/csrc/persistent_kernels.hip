@@ -587,6 +587,7 @@ static hipError_t launch_bwd_tpr(const PersistArgs& A, int grid, hipStream_t s) 
     const int nloads = (A.N + kThreads / TPR - 1) / (kThreads / TPR);
     if (nloads <= 4) k_bwd_persistent<TPR, 4, true><<<grid, kThreads, 0, s>>>(A);
     else if (nloads <= 8) k_bwd_persistent<TPR, 8, true><<<grid, kThreads, 0, s>>>(A);
+    else if (nloads <= 32) k_bwd_persistent<TPR, 8, false><<<grid, kThreads, 0, s>>>(A);
     else k_bwd_persistent<TPR, 8, false><<<grid, kThreads, 0, s>>>(A);
     return hipGetLastError();
 }
