@@ -91,6 +91,14 @@ lf_status lf_set_grad_buffers(lf_net* net, float* const* nabla_w, float* const* 
  * LF_EUNSUPPORTED if the shape/type has no such path. */
 lf_status lf_set_schedule(lf_net* net, lf_sched sched);
 
+/* Multiply the cost by 2^log2_scale (default 0).  Eq. (bp1) then yields 2^log2_scale * delta^L and, since
+ * eqs. (bp2)-(bp4) are linear in delta, every delta^l, nabla_b^l and nabla_w^l comes out multiplied by
+ * the same power of two: exactly, as long as nothing overflows.  In deep sigmoid nets delta^l shrinks by
+ * about 4x per layer and leaves the fp32 normal range after some 60 layers; a scale keeps the lower
+ * layers' gradients at full precision (the caller divides by the scale, or folds it into the step size).
+ * LF_EINVAL unless -126 <= log2_scale <= 127. */
+lf_status lf_set_cost_scale(lf_net* net, int log2_scale);
+
 /* Forward pass, eqs. (x), (z), (a): a^1 = x^1; for l = 2..L
  * z^l = w^l a^{l-1} + b^l, a^l = sigma(z^l).  x1: [B][N] of type dt, aliased as
  * a^1 (it must stay valid and unchanged until the backward pass has finished).

@@ -180,11 +180,12 @@ template <typename T>
 __global__ __launch_bounds__(kThreads) void k_output_error(const T* __restrict__ a_L,
                                                            const T* __restrict__ y,
                                                            float* __restrict__ delta_L,
-                                                           __bf16* __restrict__ delta_bf, size_t count) {
+                                                           __bf16* __restrict__ delta_bf, size_t count,
+                                                           float scale) {
     const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= count) return;
     const float a = (float)a_L[i];
-    const float d = (a - (float)y[i]) * (a * (1.0f - a));
+    const float d = scale * ((a - (float)y[i]) * (a * (1.0f - a)));
     delta_L[i] = d;
     if (delta_bf) delta_bf[i] = (__bf16)d;
 }
@@ -233,14 +234,14 @@ hipError_t launch_grad_outer_f32(const float* delta, const float* a_prev, float*
 }
 
 hipError_t launch_output_error(const void* a_L, const void* y, float* delta_L, void* delta_bf,
-                               size_t count, bool bf16, hipStream_t s) {
+                               size_t count, bool bf16, float scale, hipStream_t s) {
     const unsigned grid = (unsigned)((count + kThreads - 1) / kThreads);
     if (bf16)
         k_output_error<__bf16><<<grid, kThreads, 0, s>>>((const __bf16*)a_L, (const __bf16*)y, delta_L,
-                                                         (__bf16*)delta_bf, count);
+                                                         (__bf16*)delta_bf, count, scale);
     else
         k_output_error<float><<<grid, kThreads, 0, s>>>((const float*)a_L, (const float*)y, delta_L,
-                                                        (__bf16*)delta_bf, count);
+                                                        (__bf16*)delta_bf, count, scale);
     return hipGetLastError();
 }
 

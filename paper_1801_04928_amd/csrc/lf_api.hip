@@ -9,6 +9,7 @@
 #include "lf_internal.h"
 #include "persistent.h"
 
+#include <cmath>
 #include <cstdlib>
 #include <new>
 #include <string>
@@ -81,6 +82,7 @@ struct lf_net {
     lf_dtype dt;
     lf_cost cost;
     lf_sched sched;
+    float cost_scale;
     char* ws;
     Layout lay;
     std::vector<const void*> w;       // index l-2
@@ -96,6 +98,7 @@ struct lf_net {
     bool p_ready, p_tables_dirty;
     int p_groups, p_rpg, p_bgroups, p_tpr, p_workers;
     unsigned p_epoch;
+    unsigned p_spin_limit;             // polls before a bounded wait gives up
     int* p_abort_host;                 // pinned, mapped; the kernels raise it when a wait gives up
     int* p_abort_dev_view;             // the same word as the device addresses it
     std::vector<const void*> p_tables;
@@ -181,6 +184,10 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
         lf::persistent_forward_shape(net->N, cus, env ? std::atoi(env) : 0, &net->p_groups, &net->p_rpg);
         lf::persistent_backward_shape(net->N, cus, envb ? std::atoi(envb) : (env ? std::atoi(env) : 0),
                                       &net->p_bgroups, &net->p_tpr);
+        // LF_PERSISTENT_SPIN_LIMIT: polls before a bounded wait gives up (default 4M, i.e. seconds).  A
+        // tiny value makes the first unlucky poll fail: the way to exercise the failure path in a test.
+        const char* envs = std::getenv("LF_PERSISTENT_SPIN_LIMIT");
+        net->p_spin_limit = envs ? (unsigned)std::strtoul(envs, nullptr, 10) : (4u << 20);
         net->p_workers = cus < lf::kMaxGroups ? cus : lf::kMaxGroups;
         if (net->p_workers > net->N) net->p_workers = net->N;
         if (net->p_rpg > lf::kMaxRowsPerGroup)
@@ -229,6 +236,8 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     A.k = k < net->p_workers ? k : net->p_workers;   // never more partitions than worker workgroups
     if (++net->p_epoch >= (1u << 19)) net->p_epoch = 1;    // tags carry 19 epoch bits + 13 layer bits
     A.epoch = net->p_epoch;
+    A.cost_scale = net->cost_scale;
+    A.spin_limit = net->p_spin_limit;
     void** tab = reinterpret_cast<void**>(net->ws + net->lay.tab_off);
     A.w = reinterpret_cast<const float* const*>(tab);
     A.b = reinterpret_cast<const float* const*>(tab + M);
@@ -285,6 +294,7 @@ lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost
     if (!net) return fail(nullptr, LF_ENOMEM, "lf_create: out of host memory");
     net->L = L; net->N = N; net->B = B; net->dt = dt; net->cost = cost;
     net->sched = LF_SCHED_AUTO;
+    net->cost_scale = 1.0f;
     net->ws = static_cast<char*>(workspace);
     net->lay = make_layout(L, N, B, dt);
     net->x1 = nullptr;
@@ -349,6 +359,14 @@ lf_status lf_set_schedule(lf_net* net, lf_sched sched) {
         default:
             return fail(net, LF_EINVAL, "lf_set_schedule: unknown schedule");
     }
+}
+
+lf_status lf_set_cost_scale(lf_net* net, int log2_scale) {
+    if (!net) return LF_EINVAL;
+    if (log2_scale < -126 || log2_scale > 127)
+        return fail(net, LF_EINVAL, "lf_set_cost_scale: need -126 <= log2_scale <= 127");
+    net->cost_scale = std::ldexp(1.0f, log2_scale);
+    return LF_OK;
 }
 
 lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream) {
@@ -417,7 +435,7 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
         // the chain: (bp1) at L, (bp2) below
         if (l == L) {
             LF_HIP(net, lf::launch_output_error(net->a_ptr(L), y, net->d_ptr(L), net->dbf_ptr(L),
-                                                (size_t)B * N, bf, s));
+                                                (size_t)B * N, bf, net->cost_scale, s));
         } else if (b1) {
             LF_HIP(net, lf::launch_chain_gemvT_f32(static_cast<const float*>(net->w[l - 1]), net->d_ptr(l + 1),
                                                    static_cast<const float*>(net->a_ptr(l)), net->d_ptr(l),

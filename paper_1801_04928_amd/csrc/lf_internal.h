@@ -72,10 +72,11 @@ hipError_t launch_grad_outer_f32(const float* delta, const float* a_prev, float*
 
 // ---- any B, either storage type ----------------------------------------------------------------
 
-// eq. (bp1): delta_L = (a_L - y) (.) a_L (1 - a_L) over count = B*N elements.  delta_bf (may be
-// NULL) receives a bfloat16 copy of delta_L for the bf16 matrix kernels.
+// eq. (bp1): delta_L = scale * (a_L - y) (.) a_L (1 - a_L) over count = B*N elements (scale: a power
+// of two, see lf_set_cost_scale).  delta_bf (may be NULL) receives a bfloat16 copy of delta_L for the
+// bf16 matrix kernels.
 hipError_t launch_output_error(const void* a_L, const void* y, float* delta_L, void* delta_bf,
-                               size_t count, bool bf16, hipStream_t s);
+                               size_t count, bool bf16, float scale, hipStream_t s);
 
 // ---- minibatch path: MFMA contractions ----------------------------------------------------------
 

@@ -15,6 +15,8 @@ struct PersistArgs {
     int GB, TPR;                         // backward chain: workgroups, float4 column groups per strip
     int GW, k;                           // gradient worker workgroups (k >= 2), worker partitions
     unsigned epoch;                      // tag of this launch's words (never 0)
+    float cost_scale;                    // power of two multiplied into delta^L (see lf_set_cost_scale)
+    unsigned spin_limit;                 // polls after which a wait gives up and raises the abort word
     const float* const* w;               // device tables, index l-2
     const float* const* b;
     float* const* gw;

@@ -36,7 +36,6 @@ typedef unsigned long long u64;
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
-constexpr unsigned kSpinLimit = 4u << 20;   // polls before a wait gives up (seconds, not microseconds)
 constexpr int kTableLds = 1024;             // per-layer pointers kept in LDS (deeper nets read the rest
                                             // from the device table, one memory round trip per step)
 
@@ -59,6 +58,7 @@ struct Abort {
     int* dev;       // device word, agent scope
     int* host;      // mapped pinned host word (may be null)
     bool dead;
+    unsigned limit; // polls before a wait gives up
     __device__ void raise(int code) {
         dead = true;
         __hip_atomic_store(dev, code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -93,7 +93,7 @@ __device__ __forceinline__ void ll_wait4(const u64* p, int n, unsigned tag, floa
         }
         ++spin;
         __builtin_amdgcn_s_sleep(2);   // a short back-off keeps the pollers from crowding the fabric
-        if (spin > kSpinLimit) { ab.raise(code); return; }
+        if (spin > ab.limit) { ab.raise(code); return; }
         if ((spin & 255u) == 0u) ab.seen();
     }
 }
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArg
     const int wrow0 = g * RPG + wave * RW;                  // first row of this wave
     const int wrow_end = min(min(N, (g + 1) * RPG), wrow0 + RW);
     const int nchunks = SINGLE ? 1 : (((RW + RF - 1) / RF + 1) & ~1);   // even: see `layer` below
-    Abort ab{A.abort_dev, A.abort_host, false};
+    Abort ab{A.abort_dev, A.abort_host, false, A.spin_limit};
 
     auto load_chunk = [&](v4f (&buf)[RF][Q], const float* W, int ci) {
 #pragma unroll
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     float* s_delta = reinterpret_cast<float*>(s_delta4);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
     const int N = A.N, L = A.L, GB = A.GB, k = A.k, nvec = N >> 2;
-    Abort ab{A.abort_dev, A.abort_host, false};
+    Abort ab{A.abort_dev, A.abort_host, false, A.spin_limit};
     if (g >= GB) {
         gradient_worker(A, g - GB, (int)gridDim.x - GB, ab);
         return;
@@ -441,7 +441,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
         const float* aL = act_ptr(A, L);
         for (int i = t; i < N; i += kThreads) {
             const float a = aL[i];
-            s_delta[i] = (a - A.y[i]) * (a * (1.0f - a));
+            s_delta[i] = A.cost_scale * ((a - A.y[i]) * (a * (1.0f - a)));
         }
         __syncthreads();
         if (own) {

@@ -92,6 +92,9 @@ def test_call_order_and_argument_checks():
         assert st == P.LF_EINVAL
         st, _, _ = P.lf_activations(h, 2)
         assert st == P.LF_ESTATE
+        assert P.lf_set_cost_scale(h, 128) == P.LF_EINVAL
+        assert P.lf_set_cost_scale(h, -127) == P.LF_EINVAL
+        assert P.lf_set_cost_scale(h, 100) == P.LF_OK
         assert P.lf_set_schedule(h, 99) == P.LF_EINVAL
         assert P.lf_set_schedule(h, P.LF_SCHED_STREAMS) == P.LF_OK
     finally:

@@ -131,6 +131,84 @@ def test_rank_one_net_full_width():
     _free(g)
 
 
+@pytest.mark.parametrize("sched", ["streams", "persistent"])
+def test_cost_scale_is_exact_and_lifts_deep_layers_out_of_the_subnormal_range(sched):
+    """A power-of-two cost scale multiplies delta^L (eq. (bp1)) and, by linearity of (bp2)-(bp4), every
+    gradient by the same power of two.  (i) Where nothing underflows the scaled result is the unscaled one
+    times the scale, bit for bit.  (ii) In a net deep enough for delta to leave the fp32 normal range the
+    scaled pass meets the relative tolerance at every layer, with no subnormal exception."""
+    import paper_1801_04928_amd as P
+    import torch
+    # (i) exactness on a shallow net
+    net = make_net(5, 516, 1, seed=9)
+    g0 = run_gpu(net, 2, sched=SCHEDS[sched])
+    g1 = P.LeapfrogNet(5, 516, 1, "f32")
+    g1.load(net)
+    g1.set_schedule(SCHEDS[sched])
+    g1.set_cost_scale(20)
+    g1.forward()
+    g1.backward(2)
+    torch.cuda.synchronize()
+    for l in range(2, 6):
+        assert np.array_equal(to_np(g1.grads(l)[0]), to_np(g0.grads(l)[0]) * np.float32(2.0 ** 20))
+        assert np.array_equal(to_np(g1.grads(l)[1]), to_np(g0.grads(l)[1]) * np.float32(2.0 ** 20))
+    _free(g0)
+    _free(g1)
+    # (ii) 72 layers: max|delta^2| is about 1e-45 unscaled
+    from oracle import backprop as O
+    from tests.gpu_util import compare
+    L, N, e = 72, 512, 110
+    net = make_net(L, N, 1, seed=10)
+    g = P.LeapfrogNet(L, N, 1, "f32")
+    g.load(net)
+    g.set_schedule(SCHEDS[sched])
+    g.set_cost_scale(e)
+    g.forward()
+    g.backward(8)
+    torch.cuda.synchronize()
+    a = O.forward(net.w_by_layer, net.b_by_layer, net.x(), L)
+    report = {}
+    for l, delta, nb, nw in O.backward_layers(net.w_by_layer, a, net.y(), L):
+        gw, gb = g.grads(l)
+        compare(f"nabla_w^{l}", to_np(gw), nw * 2.0 ** e, 1e-5, report)
+        compare(f"nabla_b^{l}", to_np(gb), nb * 2.0 ** e, 1e-5, report)
+    assert "subnormal" not in report
+    assert float(np.max(np.abs(O.backward_sequential(net.w_by_layer, a, net.y(), L)[0][2]))) < 2.0 ** -126
+    log(f"cost scale 2^{e}, L={L} {sched}: worst {report['worst']:.2e}")
+    _free(g)
+
+
+def test_persistent_wait_that_gives_up_is_reported(monkeypatch):
+    """Failure handling of the persistent path, forced from the host: with a spin limit of one poll the
+    first wait that does not find its data at once gives up.  Every kernel still exits normally; the next
+    call on the handle reports LF_EHIP and says where the wait was."""
+    import paper_1801_04928_amd as P
+    import torch
+    monkeypatch.setenv("LF_PERSISTENT_SPIN_LIMIT", "1")
+    net = make_net(12, 1024, 1, seed=1)
+    g = P.LeapfrogNet(12, 1024, 1, "f32")
+    g.load(net)
+    g.set_schedule(P.LF_SCHED_PERSISTENT)
+    g.forward()
+    torch.cuda.synchronize()
+    # the forward kernel's first gather very likely gave up; if not, the backward kernel's will
+    failed = P.lf_backward_leapfrog(g.handle, g.y.data_ptr(), 4, torch.cuda.current_stream().cuda_stream)
+    message = P.lf_last_error(g.handle)
+    if failed == P.LF_OK:
+        torch.cuda.synchronize()
+        failed, _, _ = P.lf_grads(g.handle, 2)
+        message = P.lf_last_error(g.handle)
+    assert failed == P.LF_EHIP
+    assert "gave up waiting" in message
+    # the handle stays failed (its exchange state is undefined); a new handle works
+    assert P.lf_forward(g.handle, g.x.data_ptr(), 0) == P.LF_EHIP
+    _free(g)
+    monkeypatch.delenv("LF_PERSISTENT_SPIN_LIMIT")
+    g = run_gpu(net, 4, sched=P.LF_SCHED_PERSISTENT)
+    check_against_oracle(net, g)
+    _free(g)
+
+
 # ---------------------------------------------------------------- minibatch
 @pytest.mark.parametrize("L,N,B,dtype,k", [
     (4, 132, 3, "f32", 2),       # one ragged tile in every dimension
