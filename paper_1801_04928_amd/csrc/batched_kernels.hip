@@ -38,6 +38,7 @@ template <> struct Tile<__bf16> {
 struct GemmArgs {
     const void* P;  int ldp;               // rows of P index m
     const void* Q;  int ldq;               // rows of Q index n
+    unsigned p_bytes, q_bytes;             // sizes of the two operand matrices (< 4 GiB each)
     int M, Nn, K;                          // C is M x Nn, contraction length K
     int k_tiles_per_split;                 // split-K: blockIdx.z handles this many BK tiles
     float* raw;                            // EPI_RAW: [splits][M][Nn] fp32
@@ -48,19 +49,24 @@ struct GemmArgs {
 };
 
 // ---- global -> register staging ---------------------------------------------------------------
-// Each thread stages 4 x 16 bytes per operand and tile.
+// Each thread stages 4 x 16 bytes per operand and tile.  The operand is addressed as one buffer: a
+// vector that lies outside the matrix (row past the end, or past the contraction length) is given an
+// offset past the end of the buffer and loads zeros.  No branch surrounds a load, so the compiler can
+// count the loads in flight and the prefetch depth below is real.
+constexpr unsigned kOutside = 0xFFFFFFF0u;
+
 template <typename T, bool IC> struct Stage;
 
 template <> struct Stage<float, false> {   // [i][q], float4 along q; 8 threads cover 32 q of one row
     v4f r[4];
-    __device__ void load(const float* p, int ld, int i0, int q0, int I, int Kq) {
+    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int I, int Kq) {
         const int t = threadIdx.x, qv = (t & 7) * 4;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i = (t >> 3) + 32 * u;
             const bool ok = (i0 + i < I) && (q0 + qv < Kq);
-            r[u] = ok ? *reinterpret_cast<const v4f*>(p + (size_t)(i0 + i) * ld + q0 + qv)
-                      : v4f{0.f, 0.f, 0.f, 0.f};
+            const unsigned off = ((unsigned)(i0 + i) * (unsigned)ld + (unsigned)(q0 + qv)) * 4u;
+            r[u] = buffer_load_v4f(buf, ok ? off : kOutside);
         }
     }
     __device__ void store(float* s) const {
@@ -75,14 +81,14 @@ template <> struct Stage<float, false> {   // [i][q], float4 along q; 8 threads 
 };
 template <> struct Stage<float, true> {    // [q][i], float4 along i; 32 threads cover 128 i of one q
     v4f r[4];
-    __device__ void load(const float* p, int ld, int i0, int q0, int I, int Kq) {
+    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int I, int Kq) {
         const int t = threadIdx.x, iv = (t & 31) * 4;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int q = (t >> 5) + 8 * u;
             const bool ok = (q0 + q < Kq) && (i0 + iv < I);
-            r[u] = ok ? *reinterpret_cast<const v4f*>(p + (size_t)(q0 + q) * ld + i0 + iv)
-                      : v4f{0.f, 0.f, 0.f, 0.f};
+            const unsigned off = ((unsigned)(q0 + q) * (unsigned)ld + (unsigned)(i0 + iv)) * 4u;
+            r[u] = buffer_load_v4f(buf, ok ? off : kOutside);
         }
     }
     __device__ void store(float* s) const {
@@ -95,17 +101,15 @@ template <> struct Stage<float, true> {    // [q][i], float4 along i; 32 threads
     }
 };
 template <> struct Stage<__bf16, false> {  // [i][q], 8 bf16 along q; 8 threads cover 64 q of one row
-    v8bf r[4];
-    __device__ void load(const __bf16* p, int ld, int i0, int q0, int I, int Kq) {
+    v4f r[4];
+    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int I, int Kq) {
         const int t = threadIdx.x, qv = (t & 7) * 8;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i = (t >> 3) + 32 * u;
             const bool ok = (i0 + i < I) && (q0 + qv < Kq);
-            if (ok) r[u] = *reinterpret_cast<const v8bf*>(p + (size_t)(i0 + i) * ld + q0 + qv);
-            else
-#pragma unroll
-                for (int c = 0; c < 8; ++c) r[u][c] = (__bf16)0.0f;
+            const unsigned off = ((unsigned)(i0 + i) * (unsigned)ld + (unsigned)(q0 + qv)) * 2u;
+            r[u] = buffer_load_v4f(buf, ok ? off : kOutside);
         }
     }
     __device__ void store(__bf16* s) const {
@@ -113,28 +117,26 @@ template <> struct Stage<__bf16, false> {  // [i][q], 8 bf16 along q; 8 threads 
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i = (t >> 3) + 32 * u;
-            *reinterpret_cast<v8bf*>(s + i * Tile<__bf16>::LDA + qv) = r[u];
+            *reinterpret_cast<v4f*>(s + i * Tile<__bf16>::LDA + qv) = r[u];
         }
     }
 };
 template <> struct Stage<__bf16, true> {   // [q][i], 8 bf16 along i; 16 threads cover 128 i of one q
-    v8bf r[4];
-    __device__ void load(const __bf16* p, int ld, int i0, int q0, int I, int Kq) {
+    v4f r[4];
+    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int I, int Kq) {
         const int t = threadIdx.x, iv = (t & 15) * 8;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int q = (t >> 4) * 4 + u;            // a thread holds 4 consecutive q of its 8 i
             const bool ok = (q0 + q < Kq) && (i0 + iv < I);
-            if (ok) r[u] = *reinterpret_cast<const v8bf*>(p + (size_t)(q0 + q) * ld + i0 + iv);
-            else
-#pragma unroll
-                for (int c = 0; c < 8; ++c) r[u][c] = (__bf16)0.0f;
+            const unsigned off = ((unsigned)(q0 + q) * (unsigned)ld + (unsigned)(i0 + iv)) * 2u;
+            r[u] = buffer_load_v4f(buf, ok ? off : kOutside);
         }
     }
     __device__ void store(__bf16* s) const {   // LDS keeps the memory layout [q][i]
         const int t = threadIdx.x, iv = (t & 15) * 8, q = (t >> 4) * 4;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) *reinterpret_cast<v8bf*>(s + (q + u) * Tile<__bf16>::LDI + iv) = r[u];
+        for (int u = 0; u < 4; ++u) *reinterpret_cast<v4f*>(s + (q + u) * Tile<__bf16>::LDI + iv) = r[u];
     }
 };
 
@@ -189,14 +191,15 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g) {
     // a compute unit.  The three register stages rotate by a 3-way unrolled loop (static indexing).
     Stage<T, P_IC> sp[3];
     Stage<T, Q_IC> sq[3];
-    const T* P = static_cast<const T*>(g.P);
-    const T* Q = static_cast<const T*>(g.Q);
+    const __amdgpu_buffer_rsrc_t P = make_buffer(g.P, g.p_bytes);
+    const __amdgpu_buffer_rsrc_t Q = make_buffer(g.Q, g.q_bytes);
 #pragma unroll
     for (int u = 0; u < 3; ++u)
         if (kt_begin + u < kt_end) {
             sp[u].load(P, g.ldp, m0, (kt_begin + u) * TL::BK, g.M, g.K);
             sq[u].load(Q, g.ldq, n0, (kt_begin + u) * TL::BK, g.Nn, g.K);
         }
+    __builtin_amdgcn_sched_barrier(0);   // keep the requests up here: the scheduler would sink them to their uses
     auto multiply_tile = [&]() {
         if constexpr (sizeof(T) == 4) {
 #pragma unroll
@@ -245,6 +248,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g) {
                     sp[u].load(P, g.ldp, m0, (kt + u + 3) * TL::BK, g.M, g.K);
                     sq[u].load(Q, g.ldq, n0, (kt + u + 3) * TL::BK, g.Nn, g.K);
                 }
+                __builtin_amdgcn_sched_barrier(0);   // requests stay ahead of the multiplications
                 multiply_tile();
                 __syncthreads();
             }
@@ -350,6 +354,12 @@ __global__ __launch_bounds__(kThreads) void k_bias_grad(const float* __restrict_
 
 template <typename T, bool P_IC, bool Q_IC, int EPI>
 hipError_t run(GemmArgs g, int splits, hipStream_t s) {
+    // operand sizes for the buffer addressing: P is (P_IC ? K x M : M x K), Q likewise with Nn
+    const unsigned long long pb = (unsigned long long)(P_IC ? g.K : g.M) * g.ldp * sizeof(T);
+    const unsigned long long qb = (unsigned long long)(Q_IC ? g.K : g.Nn) * g.ldq * sizeof(T);
+    if (pb >= 0xFFFFFFF0ull || qb >= 0xFFFFFFF0ull) return hipErrorInvalidValue;
+    g.p_bytes = (unsigned)pb;
+    g.q_bytes = (unsigned)qb;
     const dim3 grid(ceil_div(g.Nn, BN), ceil_div(g.M, BM), splits);
     k_gemm<T, P_IC, Q_IC, EPI><<<grid, kThreads, 0, s>>>(g);
     return hipGetLastError();
