@@ -189,6 +189,11 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
         const char* envs = std::getenv("LF_PERSISTENT_SPIN_LIMIT");
         net->p_spin_limit = envs ? (unsigned)std::strtoul(envs, nullptr, 10) : (4u << 20);
         net->p_workers = cus < lf::kMaxGroups ? cus : lf::kMaxGroups;
+        // LF_PERSISTENT_WORKERS: tuning override of the number of gradient worker workgroups
+        if (const char* envw = std::getenv("LF_PERSISTENT_WORKERS")) {
+            const int w = std::atoi(envw);
+            if (w >= 1 && w <= 2 * lf::kMaxGroups) net->p_workers = w;
+        }
         if (net->p_workers > net->N) net->p_workers = net->N;
         if (net->p_rpg > lf::kMaxRowsPerGroup)
             return fail(net, LF_EUNSUPPORTED, "persistent path: too few compute units for this N");

@@ -316,29 +316,23 @@ __device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, i
         v4f ja[PG];
         load_activation_groups(A, layer - 1, ja);
         const u64* dl = A.DLL + (size_t)(layer - 2) * N;
-        // words of the first group; afterwards the next group's words are requested before the
-        // current group's rows are stored
-        u64 nw[4];
+        // sixteen rows at a time: all their words are requested together (one round trip when delta^l
+        // is already there), rows whose words are not tagged yet are then waited for group by group
+        for (int row0 = jb; row0 < je && !ab.dead; row0 += 16) {
+            const u64* gp[4];
+            int gn[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) nw[c] = ll_load(dl + min(jb + c, je - 1));
-        for (int row = jb; row < je && !ab.dead; row += 4) {
-            const int n = min(4, je - row);
-            u64 cw[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) cw[c] = nw[c];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) nw[c] = ll_load(dl + min(row + 4 + c, je - 1));   // next group
-            const bool ok = ll_tag(cw[0]) == A.epoch && ll_tag(cw[1]) == A.epoch &&
-                            ll_tag(cw[2]) == A.epoch && ll_tag(cw[3]) == A.epoch;
-            float d[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) d[c] = ll_val(cw[c]);
-            if (!ok) {
-                __builtin_amdgcn_s_sleep(64);    // off the chain: poll gently, the chain needs the fabric
-                ll_wait4(dl + row, n, A.epoch, d, ab, abort_code(3, layer, (int)blockIdx.x));
-                if (ab.dead) return;
+            for (int i = 0; i < 4; ++i) {
+                const int r = row0 + 4 * i;
+                gn[i] = r < je ? min(4, je - r) : 0;
+                gp[i] = dl + min(r, je - 1);
             }
-            store_gradient_rows(A, layer, row, n, d, ja);
+            float d[4][4];
+            ll_gather4x4(gp, gn, A.epoch, d, ab, abort_code(3, layer, (int)blockIdx.x));
+            if (ab.dead) return;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (gn[i] > 0) store_gradient_rows(A, layer, row0 + 4 * i, gn[i], d[i], ja);
         }
     }
 }
