@@ -33,6 +33,7 @@ struct Layout {
     size_t raw_off, raw_bytes;
     // persistent single-sample path: tagged-word exchange buffers, pointer tables, abort word
     size_t dll_off, all_off, ll_words;   // [L-1][N] each
+    size_t pll_off, pll_words;           // [L-1][N][kMaxRowSplit]
     size_t tab_off, tab_bytes;       // w, b, nabla_w, nabla_b pointer tables, L-1 entries each
     size_t abort_off;
     size_t total;
@@ -66,6 +67,8 @@ Layout make_layout(int L, int N, int B, lf_dtype dt) {
         y.ll_words = M * (size_t)N;
         y.dll_off = off; off += align_up(y.ll_words * 8);
         y.all_off = off; off += align_up(y.ll_words * 8);
+        y.pll_words = y.ll_words * lf::kMaxRowSplit;
+        y.pll_off = off; off += align_up(y.pll_words * 8);
         y.tab_off = off; y.tab_bytes = 4 * M * sizeof(void*);         off += align_up(y.tab_bytes);
         y.abort_off = off; off += kAlign;
     }
@@ -96,7 +99,7 @@ struct lf_net {
     std::string err;
     // persistent path
     bool p_ready, p_tables_dirty;
-    int p_groups, p_rpg, p_bgroups, p_tpr, p_workers;
+    int p_groups, p_rpg, p_bgroups, p_tpr, p_rs, p_workers;
     unsigned p_epoch;
     unsigned p_spin_limit;             // polls before a bounded wait gives up
     int* p_abort_host;                 // pinned, mapped; the kernels raise it when a wait gives up
@@ -163,7 +166,7 @@ bool use_persistent(const lf_net* net) {
 lf_status check_abort(lf_net* net) {
     const int code = net->p_abort_host ? *reinterpret_cast<volatile int*>(net->p_abort_host) : 0;
     if (code) {
-        static const char* const site[] = {"?", "forward gather", "chain gather", "gradient wait"};
+        static const char* const site[] = {"partial-sum wait", "forward gather", "chain gather", "gradient wait"};
         return fail(net, LF_EHIP,
                     std::string("a persistent kernel gave up waiting for its peers (") + site[(code >> 24) & 3] +
                         ", layer " + std::to_string((code >> 10) & 0x3fff) + ", workgroup " +
@@ -182,8 +185,10 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
         const char* env = std::getenv("LF_PERSISTENT_GROUPS");
         const char* envb = std::getenv("LF_PERSISTENT_GROUPS_BWD");
         lf::persistent_forward_shape(net->N, cus, env ? std::atoi(env) : 0, &net->p_groups, &net->p_rpg);
+        // LF_PERSISTENT_ROW_SPLIT: row blocks per backward column strip (1, 2 or 4)
+        const char* envr = std::getenv("LF_PERSISTENT_ROW_SPLIT");
         lf::persistent_backward_shape(net->N, cus, envb ? std::atoi(envb) : (env ? std::atoi(env) : 0),
-                                      &net->p_bgroups, &net->p_tpr);
+                                      envr ? std::atoi(envr) : 0, &net->p_bgroups, &net->p_tpr, &net->p_rs);
         // LF_PERSISTENT_SPIN_LIMIT: polls before a bounded wait gives up (default 4M, i.e. seconds).  A
         // tiny value makes the first unlucky poll fail: the way to exercise the failure path in a test.
         const char* envs = std::getenv("LF_PERSISTENT_SPIN_LIMIT");
@@ -195,6 +200,11 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
             if (w >= 1 && w <= 2 * lf::kMaxGroups) net->p_workers = w;
         }
         if (net->p_workers > net->N) net->p_workers = net->N;
+        // every workgroup of a launch waits for others of it, so all of them must be resident at once:
+        // two per compute unit (256 registers per thread at most)
+        if (cus > 0 && (net->p_groups > 2 * cus || net->p_bgroups + 1 > 2 * cus))
+            return fail(net, LF_EUNSUPPORTED, "persistent path: too few compute units for this N");
+        if (cus > 0 && net->p_workers > 2 * cus - net->p_bgroups) net->p_workers = 2 * cus - net->p_bgroups;
         if (net->p_rpg > lf::kMaxRowsPerGroup)
             return fail(net, LF_EUNSUPPORTED, "persistent path: too few compute units for this N");
         if (!net->p_abort_host) {
@@ -209,6 +219,7 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
         // tagged words start as tag 0 (never a valid tag); the abort word as 0
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.dll_off, net->lay.ll_words, 0ull, s));
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.all_off, net->lay.ll_words, 0ull, s));
+        LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.pll_off, net->lay.pll_words, 0ull, s));
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.abort_off, kAlign / 8, 0ull, s));
         net->p_epoch = 0;
         net->p_ready = true;
@@ -236,7 +247,7 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     lf::PersistArgs A{};
     A.L = net->L; A.N = net->N;
     A.G = net->p_groups; A.RPG = net->p_rpg;
-    A.GB = net->p_bgroups; A.TPR = net->p_tpr;
+    A.GB = net->p_bgroups; A.TPR = net->p_tpr; A.RS = net->p_rs;
     A.GW = net->p_workers;
     A.k = k < net->p_workers ? k : net->p_workers;   // never more partitions than worker workgroups
     if (++net->p_epoch >= (1u << 19)) net->p_epoch = 1;    // tags carry 19 epoch bits + 13 layer bits
@@ -253,6 +264,7 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     A.d_base = reinterpret_cast<float*>(net->ws + net->lay.d_off);  A.d_stride = net->lay.d_stride / 4;
     A.DLL = reinterpret_cast<unsigned long long*>(net->ws + net->lay.dll_off);
     A.ALL = reinterpret_cast<unsigned long long*>(net->ws + net->lay.all_off);
+    A.PLL = reinterpret_cast<unsigned long long*>(net->ws + net->lay.pll_off);
     A.y = static_cast<const float*>(y);
     A.abort_dev = reinterpret_cast<int*>(net->ws + net->lay.abort_off);
     A.abort_host = net->p_abort_dev_view;

@@ -8,11 +8,13 @@ namespace lf {
 constexpr int kMaxGroups = 256;          // chain workgroups of a persistent kernel (one per compute unit)
 constexpr int kMaxRowsPerGroup = 256;    // rows one forward workgroup may own
 constexpr int kMaxPersistentN = 4096;    // wider nets take the stream schedule
+constexpr int kMaxRowSplit = 4;          // row blocks a backward column strip may be split into
 
 struct PersistArgs {
     int L, N;
     int G, RPG;                          // forward: workgroups, rows per workgroup
     int GB, TPR;                         // backward chain: workgroups, float4 column groups per strip
+    int RS;                              // backward chain: row blocks per strip (1 = a strip is one workgroup's)
     int GW, k;                           // gradient worker workgroups (k >= 2), worker partitions
     unsigned epoch;                      // tag of this launch's words (never 0)
     float cost_scale;                    // power of two multiplied into delta^L (see lf_set_cost_scale)
@@ -26,6 +28,7 @@ struct PersistArgs {
     float* d_base;  size_t d_stride;     // delta^l likewise
     unsigned long long* DLL;             // [L-1][N]  delta^l as tagged words
     unsigned long long* ALL;             // [L-1][N]  a^l as tagged words (forward)
+    unsigned long long* PLL;             // [L-1][N][RS]  row-block partial sums of (bp2) as tagged words
     const float* y;
     int* abort_dev;                      // device word
     int* abort_host;                     // mapped pinned host word, or null
@@ -35,7 +38,8 @@ bool persistent_supported(int N);
 // Launch shapes for width N on a device with num_cus compute units; requested > 0 overrides the
 // default number of workgroups.
 void persistent_forward_shape(int N, int num_cus, int requested, int* G, int* rpg);
-void persistent_backward_shape(int N, int num_cus, int requested, int* GB, int* tpr);
+// row_split: 1, 2 or 4 row blocks per column strip, anything else = the default for this N.
+void persistent_backward_shape(int N, int num_cus, int requested, int row_split, int* GB, int* tpr, int* rs);
 hipError_t launch_fill_u64(void* p, size_t n_words, unsigned long long v, hipStream_t s);
 hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s);
 hipError_t launch_bwd_persistent(const PersistArgs& A, hipStream_t s);

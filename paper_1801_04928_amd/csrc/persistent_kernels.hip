@@ -343,7 +343,12 @@ __device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, i
 // across the exchange).  At most 256 registers per thread, so that a chain and a gradient workgroup
 // fit one compute unit.
 // SINGLE: the strip of a step is one chunk; otherwise an even number of chunks per step.
-template <int TPR, int CH, bool SINGLE>
+// SPLIT: a strip is shared by RS workgroups, each taking a block of rows.  A strip is then a whole
+// number of 128-byte lines also for wide layers (half-line strips stream at about two thirds of the
+// rate); the price is one more exchange per step: the row blocks' partial sums go out as tagged words
+// and each of the RS workgroups finishes 1/RS of the strip's columns, adding the partials in row-block
+// order.
+template <int TPR, int CH, bool SINGLE, bool SPLIT>
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArgs A) {
     constexpr int CPG = 4 * TPR;              // columns per chain workgroup
     constexpr int RPP = kThreads / TPR;       // rows covered by one load of the whole workgroup
@@ -361,24 +366,45 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     for (int i = t; i < min(L - 1, kTableLds); i += kThreads) s_w[i] = A.w[i];
     __syncthreads();
     auto wptr = [&](int i) { return i < kTableLds ? s_w[i] : A.w[i]; };
-    // strips of workgroups on one XCD (workgroups are dealt to the 8 XCDs round-robin) are adjacent
-    const int strip = (GB % 8 == 0) ? (g % 8) * (GB / 8) + g / 8 : g;
+    // strips of workgroups on one XCD (workgroups are dealt to the 8 XCDs round-robin) are adjacent,
+    // and the workgroups that share a strip sit on one XCD
+    const int RS = SPLIT ? A.RS : 1;
+    int strip = g, rb = 0;
+    if (GB % (8 * RS) == 0) {
+        const int j = g / 8;
+        rb = j % RS;
+        strip = (g % 8) * (GB / (8 * RS)) + j / RS;
+    } else if constexpr (SPLIT) {
+        rb = g % RS;
+        strip = g / RS;
+    }
+    const int NR = SPLIT ? (N + RS - 1) / RS : N;        // rows of one row block
+    const int row_lo = min(N, rb * NR), row_hi = min(N, row_lo + NR);
     const int col0 = strip * CPG;
     const int cg = t % TPR, rs = t / TPR;
     const int col = min(col0 + 4 * cg, N - 4);           // a partial last strip re-reads valid columns
-    const int nloads = (N + RPP - 1) / RPP;
-    const int nchunks = SINGLE ? 1 : (((nloads + CH - 1) / CH + 1) & ~1);   // even: see `step` below
+    const int nloads = (NR + RPP - 1) / RPP;
+    constexpr int NB = SINGLE ? 2 : 4;                   // chunk buffers
+    const int nchunks = SINGLE ? 1 : ((nloads + CH - 1) / CH + NB - 1) / NB * NB;   // see `step` below
     // rows of the sequential pass's in-line gradients
-    const int RPGb = (N + GB - 1) / GB, jrow0 = min(N, g * RPGb), jrow1 = min(N, jrow0 + RPGb);
+    // (taken from my own row block: the only part of delta this workgroup gathers)
+    const int nstrips = GB / RS;
+    const int RPGb = (row_hi - row_lo + nstrips - 1) / nstrips;
+    const int jrow0 = min(row_hi, row_lo + strip * RPGb), jrow1 = min(row_hi, jrow0 + RPGb);
 
-    // the whole matrix is one buffer: a row past its end loads zeros
-    const unsigned strip_offset = ((unsigned)rs * (unsigned)N + (unsigned)col) * 4u;
+    // a chunk's buffer runs from the chunk's first pass to the end of my row block: a row past that end
+    // loads zeros, and the per-thread offsets are the same for every chunk
+    const unsigned strip_offset = ((unsigned)(row_lo + rs) * (unsigned)N + (unsigned)col) * 4u;
     const unsigned pass_bytes = (unsigned)RPP * (unsigned)N * 4u;
-    auto load_chunk = [&](v4f (&buf)[CH], const float* W, int ci) {
-        const __amdgpu_buffer_rsrc_t r = make_buffer(W, (unsigned)N * (unsigned)N * 4u);
+    const unsigned block_bytes = (unsigned)row_hi * (unsigned)N * 4u;
+    auto load_chunk_of = [&](v4f (&buf)[CH], const float* W, int ci, unsigned bytes) {
+        const unsigned skip = (unsigned)(ci * CH) * pass_bytes;
+        const __amdgpu_buffer_rsrc_t r = make_buffer(reinterpret_cast<const char*>(W) + skip,
+                                                     bytes > skip ? bytes - skip : 0u);
 #pragma unroll
-        for (int u = 0; u < CH; ++u) buf[u] = buffer_load_v4f(r, strip_offset + (unsigned)(ci * CH + u) * pass_bytes);
+        for (int u = 0; u < CH; ++u) buf[u] = buffer_load_v4f(r, strip_offset + (unsigned)u * pass_bytes);
     };
+    auto load_chunk = [&](v4f (&buf)[CH], const float* W, int ci) { load_chunk_of(buf, W, ci, block_bytes); };
     auto inline_grads = [&](int layer) {        // k = 1: rows [jrow0, jrow1) of layer's gradients
         v4f ja[PG];
         load_activation_groups(A, layer - 1, ja);
@@ -390,24 +416,25 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
             store_gradient_rows(A, layer, row, n, d, ja);
         }
     };
-    // all of delta^layer, from its tagged words, into LDS
+    // delta^layer's rows of my row block (float4 groups [gv0, gv1)), from their tagged words, into LDS
+    const int gv0 = row_lo >> 2, gv1 = (row_hi + 3) >> 2;
     auto gather_delta = [&](int layer) {
         const u64* src = A.DLL + (size_t)(layer - 2) * N;
         if (nvec <= kThreads) {
-            if (t < nvec) {
+            if (t >= gv0 && t < gv1) {
                 float o[4];
                 ll_wait4(src + 4 * t, 4, A.epoch, o, ab, abort_code(2, layer, g));
                 s_delta4[t] = v4f{o[0], o[1], o[2], o[3]};
             }
         } else {
-            for (int v0 = t; v0 < nvec; v0 += 4 * kThreads) {
+            for (int v0 = gv0 + t; v0 < gv1; v0 += 4 * kThreads) {
                 const u64* gp[4];
                 int gn[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int v = v0 + i * kThreads;
-                    gn[i] = v < nvec ? 4 : 0;
-                    gp[i] = src + 4 * min(v, nvec - 1);
+                    gn[i] = v < gv1 ? 4 : 0;
+                    gp[i] = src + 4 * min(v, gv1 - 1);
                 }
                 float o[4][4];
                 ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(2, layer, g));
@@ -421,12 +448,17 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     // A wait for one load also waits for every older load and store of the wave.  So nothing slow is
     // requested just before the strip loads in flight are awaited: a^{l-1} (for the next step's sigma')
     // is requested right after delta^l is published, where its latency overlaps the exchange.
-    const bool own = t < CPG && col0 + t < N;
-    float a_next = (own && L > 2) ? act_ptr(A, L - 1)[col0 + t] : 0.0f;
-    v4f buf0[CH], buf1[CH];
-    if (L > 2) load_chunk(buf0, wptr(L - 2), 0);    // my strip of w^L, needed by the first chain step
-    if constexpr (!SINGLE) {
-        if (L > 2) load_chunk(buf1, wptr(L - 2), 1);
+    // columns whose delta this workgroup finishes and publishes: its strip, or its share of it
+    const int nfin = SPLIT ? CPG / RS : CPG, fcol0 = col0 + rb * nfin;
+    const bool own = t < nfin && fcol0 + t < N;
+    float a_next = (own && L > 2) ? act_ptr(A, L - 1)[fcol0 + t] : 0.0f;
+    v4f buf[NB][CH];
+    if (L > 2) {                                     // my strip of w^L, needed by the first chain step
+        load_chunk(buf[0], wptr(L - 2), 0);
+        if constexpr (!SINGLE) {
+#pragma unroll
+            for (int j = 1; j < NB; ++j) load_chunk(buf[j], wptr(L - 2), j);
+        }
     }
 
     // (bp1): every chain workgroup forms all of delta^L (N cheap elements, no exchange); the owner of
@@ -439,28 +471,30 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
         }
         __syncthreads();
         if (own) {
-            const float d = s_delta[col0 + t];
-            ll_store(A.DLL + (size_t)(L - 2) * N + col0 + t, d, A.epoch);
-            A.d_base[(size_t)(L - 2) * A.d_stride + col0 + t] = d;
+            const float d = s_delta[fcol0 + t];
+            ll_store(A.DLL + (size_t)(L - 2) * N + fcol0 + t, d, A.epoch);
+            A.d_base[(size_t)(L - 2) * A.d_stride + fcol0 + t] = d;
         }
     }
 
     auto fma_chunk = [&](const v4f (&buf)[CH], int ci, v4f& acc) {
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
-            const int row = rs + RPP * (ci * CH + u);
+            const int row = row_lo + rs + RPP * (ci * CH + u);
             const float dv = s_delta[min(row, N - 1)];
-            const float d = row < N ? dv : 0.0f;
+            const float d = row < row_hi ? dv : 0.0f;
             acc.x = fmaf(buf[u].x, d, acc.x);
             acc.y = fmaf(buf[u].y, d, acc.y);
             acc.z = fmaf(buf[u].z, d, acc.z);
             acc.w = fmaf(buf[u].w, d, acc.w);
         }
     };
-    // One chain step, delta^{l+1} -> delta^l.  On entry bufA holds (possibly still in flight) the first
-    // chunk of my strip of w^{l+1}.  The two buffers alternate so that the chunk after the one in use is
-    // always in flight -- also across the exchange -- without any register copy.  With one chunk per step
-    // the next step's chunk ends up in bufB; with an even number of chunks in bufA again.
+    // One chain step, delta^{l+1} -> delta^l.  SINGLE: on entry bufA holds (possibly still in flight) my
+    // strip of w^{l+1}, and the next step's is requested into bufB before this one is used.  Otherwise
+    // chunk c lives in buffer c mod NB and the step has a multiple of NB chunks: on entry the first NB
+    // are loaded or in flight, and as soon as a chunk has been used its buffer is requested again, for
+    // chunk c + NB of this step or, past its end, of the next step -- so NB - 1 chunks stay in flight all
+    // the time, also across the exchange, without any register copy.
     auto step = [&](v4f (&bufA)[CH], v4f (&bufB)[CH], int l) {
         const float a_l = a_next;
         if (k == 1) inline_grads(l + 1);
@@ -471,15 +505,18 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
             if (Wn) load_chunk(bufB, Wn, 0);
             fma_chunk(bufA, 0, acc);
         } else {
-            // both buffers enter the step loaded (chunks 0 and 1 were requested before the exchange)
-            for (int ci = 0; ci < nchunks; ci += 2) {
-                if (ci > 0) load_chunk(bufB, W, ci + 1);
-                fma_chunk(bufA, ci, acc);
-                if (ci + 2 < nchunks) load_chunk(bufA, W, ci + 2);
-                else if (Wn) load_chunk(bufA, Wn, 0);
-                fma_chunk(bufB, ci + 1, acc);
+            // every refill is one unconditional load: past the last layer it reads an empty buffer
+            // (zeros, no memory traffic), so a buffer's registers are never carried around a branch
+            const float* Wnext = Wn ? Wn : W;
+            const unsigned next_bytes = Wn ? block_bytes : 0u;
+            for (int ci = 0; ci < nchunks; ci += NB) {
+                const bool same = ci + NB < nchunks;
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    fma_chunk(buf[j], ci + j, acc);
+                    load_chunk_of(buf[j], same ? W : Wnext, same ? ci + j + NB : j, same ? block_bytes : next_bytes);
+                }
             }
-            if (Wn) load_chunk(bufB, Wn, 1);
         }
         // add the threads that share a column group: lanes by butterfly, then the four waves in order
 #pragma unroll
@@ -491,7 +528,25 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
         }
         if (lane < TPR) s_red[wave][lane] = acc;
         __syncthreads();
-        if (own) {
+        if constexpr (SPLIT) {
+            // my row block's partial sums of the strip go out; the partials of my share of its columns
+            // come in, from every row block (mine included), and are added in row-block order
+            u64* pl = A.PLL + (size_t)(l - 2) * N * RS;
+            if (t < CPG && col0 + t < N) {
+                const int q = t >> 2, e = t & 3;
+                const float u = ((s_red[0][q][e] + s_red[1][q][e]) + s_red[2][q][e]) + s_red[3][q][e];
+                ll_store(pl + (size_t)(col0 + t) * RS + rb, u, A.epoch);
+            }
+            if (own) {
+                float p[4];
+                ll_wait4(pl + (size_t)(fcol0 + t) * RS, RS, A.epoch, p, ab, abort_code(0, l, g));
+                const float u = ((p[0] + p[1]) + p[2]) + p[3];      // slots past RS hold zeros
+                const float d = u * (a_l * (1.0f - a_l));
+                ll_store(A.DLL + (size_t)(l - 2) * N + fcol0 + t, d, A.epoch);
+                A.d_base[(size_t)(l - 2) * A.d_stride + fcol0 + t] = d;
+                if (l > 2) a_next = act_ptr(A, l - 1)[fcol0 + t];
+            }
+        } else if (own) {
             const int q = t >> 2, e = t & 3;
             const float u = ((s_red[0][q][e] + s_red[1][q][e]) + s_red[2][q][e]) + s_red[3][q][e];
             const float d = u * (a_l * (1.0f - a_l));
@@ -506,11 +561,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
 
     if constexpr (SINGLE) {
         for (int l = L - 1; l >= 2; l -= 2) {
-            step(buf0, buf1, l);
-            if (l - 1 >= 2) step(buf1, buf0, l - 1);
+            step(buf[0], buf[1], l);
+            if (l - 1 >= 2) step(buf[1], buf[0], l - 1);
         }
     } else {
-        for (int l = L - 1; l >= 2; --l) step(buf0, buf1, l);
+        for (int l = L - 1; l >= 2; --l) step(buf[0], buf[1], l);
     }
     if (k == 1) inline_grads(2);
 }
@@ -536,17 +591,27 @@ void persistent_forward_shape(int N, int num_cus, int requested, int* G, int* rp
     *G = (N + *rpg - 1) / *rpg;
 }
 
-// Backward chain: GB workgroups, each owning a strip of 4*tpr columns, tpr in {1, 2, 4, 8}.
-void persistent_backward_shape(int N, int num_cus, int requested, int* GB, int* tpr) {
-    int g = requested > 0 ? requested : (N <= 2048 ? 128 : kMaxGroups);
-    if (g > kMaxGroups) g = kMaxGroups;
-    if (num_cus > 0 && g > num_cus) g = num_cus;
-    if (g < 1) g = 1;
+// Backward chain: strips of 4*tpr columns, tpr in {1, 2, 4, 8}, each shared by rs row blocks;
+// GB = strips * rs workgroups.  Wide layers (N > 2048) take 128-byte strips in two row blocks.
+void persistent_backward_shape(int N, int num_cus, int requested, int row_split, int* GB, int* tpr, int* rs) {
+    int split = (row_split == 1 || row_split == 2 || row_split == 4) ? row_split : (N > 2048 ? 2 : 1);
+    while (split > 1 && N < 4 * split) split >>= 1;      // every row block holds rows
+    int cap = requested > 0 ? requested : (N <= 2048 ? 128 : kMaxGroups);
+    if (cap > kMaxGroups) cap = kMaxGroups;
+    if (num_cus > 0 && cap > num_cus) cap = num_cus;
+    if (cap < 1) cap = 1;
     const int groups4 = (N + 3) / 4;                    // float4 column groups
-    int need = (groups4 + g - 1) / g, tp = 1;
-    while (tp < need && tp < 8) tp <<= 1;
-    *tpr = tp;
-    *GB = (groups4 + tp - 1) / tp;                       // may exceed g only if tp was capped at 8
+    for (;; split >>= 1) {
+        const int aim = cap / split > 0 ? cap / split : 1;   // strips aimed at
+        int need = (groups4 + aim - 1) / aim, tp = 1;
+        while (tp < need && tp < 8) tp <<= 1;
+        while (split > 1 && 4 * tp % split != 0) tp <<= 1;   // a strip's columns divide among its row blocks
+        *tpr = tp;
+        *rs = split;
+        *GB = (groups4 + tp - 1) / tp * split;
+        // more workgroups than aimed at: only acceptable when nothing is left to give (tp capped at 8)
+        if (*GB <= cap || split == 1) return;
+    }
 }
 
 hipError_t launch_fill_u64(void* p, size_t n_words, unsigned long long v, hipStream_t s) {
@@ -579,15 +644,17 @@ hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s) {
 template <int TPR>
 static hipError_t launch_bwd_tpr(const PersistArgs& A, int grid, hipStream_t s) {
     const int nloads = (A.N + kThreads / TPR - 1) / (kThreads / TPR);
-    if (nloads <= 4) k_bwd_persistent<TPR, 4, true><<<grid, kThreads, 0, s>>>(A);
-    else if (nloads <= 8) k_bwd_persistent<TPR, 8, true><<<grid, kThreads, 0, s>>>(A);
-    else if (nloads <= 32) k_bwd_persistent<TPR, 8, false><<<grid, kThreads, 0, s>>>(A);
-    else k_bwd_persistent<TPR, 8, false><<<grid, kThreads, 0, s>>>(A);
+    if (A.RS > 1) k_bwd_persistent<TPR, 8, false, true><<<grid, kThreads, 0, s>>>(A);
+    else if (nloads <= 4) k_bwd_persistent<TPR, 4, true, false><<<grid, kThreads, 0, s>>>(A);
+    else if (nloads <= 8) k_bwd_persistent<TPR, 8, true, false><<<grid, kThreads, 0, s>>>(A);
+    else k_bwd_persistent<TPR, 8, false, false><<<grid, kThreads, 0, s>>>(A);
     return hipGetLastError();
 }
 
 hipError_t launch_bwd_persistent(const PersistArgs& A, hipStream_t s) {
     if (A.GB > kMaxGroups * 2 || A.N > kMaxPersistentN) return hipErrorInvalidValue;
+    if (A.RS != 1 && A.RS != 2 && A.RS != 4) return hipErrorInvalidValue;
+    if (A.GB % A.RS != 0 || (4 * A.TPR) % A.RS != 0) return hipErrorInvalidValue;
     const int grid = A.GB + (A.k > 1 ? A.GW : 0);    // chain workgroups, then the gradient workers
     switch (A.TPR) {
         case 1: return launch_bwd_tpr<1>(A, grid, s);

@@ -178,6 +178,35 @@ def test_cost_scale_is_exact_and_lifts_deep_layers_out_of_the_subnormal_range(sc
     _free(g)
 
 
+@pytest.mark.parametrize("L,N,k,split", [
+    (5, 64, 2, 2),        # strips of 8 columns, two row blocks of 32 rows
+    (6, 260, 3, 2),       # ragged last strip, ragged second row block
+    (4, 1028, 1, 4),      # sequential pass, four row blocks, ragged
+    (7, 2052, 4, 2),      # just past a power of two
+    (5, 3076, 2, 4),
+    (4, 4096, 3, 1),      # the widest layer with whole-height strips
+])
+def test_persistent_row_split_strips_match_oracle(monkeypatch, L, N, k, split):
+    """The persistent backward kernel with every column strip shared by `split` row blocks (the layout
+    wide layers take by default), forced at sizes that leave ragged strips and ragged row blocks."""
+    import paper_1801_04928_amd as P
+    monkeypatch.setenv("LF_PERSISTENT_ROW_SPLIT", str(split))
+    net = make_net(L, N, 1, seed=N + 31 * split)
+    g = run_gpu(net, k, sched=P.LF_SCHED_PERSISTENT)
+    rep = check_against_oracle(net, g)
+    # same bits for another k (the partial sums are added in row-block order whatever the timing)
+    ref = [to_np(t).copy() for t in g.nabla_w] + [to_np(t).copy() for t in g.nabla_b]
+    g.forward()
+    g.backward(1 if k > 1 else min(2, L - 1))
+    import torch
+    torch.cuda.synchronize()
+    got = [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]
+    for a, b in zip(ref, got):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    log(f"row split {split}: L={L} N={N} k={k}: worst {rep['worst']:.2e}")
+    _free(g)
+
+
 def test_persistent_wait_that_gives_up_is_reported(monkeypatch):
     """Failure handling of the persistent path, forced from the host: with a spin limit of one poll the
     first wait that does not find its data at once gives up.  Every kernel still exits normally; the next
