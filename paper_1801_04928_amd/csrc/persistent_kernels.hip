@@ -303,36 +303,52 @@ __device__ __forceinline__ void load_activation_groups(const PersistArgs& A, int
     for (int p = 0; p < PG; ++p) ja[p] = load_global_v4f(ap + 4 * min((int)threadIdx.x + kThreads * p, nvec - 1));
 }
 
+// Poll one tagged word until it carries `tag`, napping between polls.
+__device__ __forceinline__ float ll_wait1(const u64* p, unsigned tag, Abort& ab, int code) {
+    unsigned spin = 0;
+    while (!ab.dead) {
+        const u64 w = ll_load(p);
+        if (ll_tag(w) == tag) return ll_val(w);
+        ++spin;
+        __builtin_amdgcn_s_sleep(8);
+        if (spin > ab.limit) { ab.raise(code); break; }
+        if ((spin & 255u) == 0u) ab.seen();
+    }
+    return 0.0f;
+}
+
 // Gradient workgroup (k >= 2): member of worker partition `part`; streams out its share of rows of
 // nabla_w^l, nabla_b^l for l = L - part, L - part - k, ... as soon as delta^l's words carry this
-// pass's tag.  It never feeds the chain, so the chain never waits for it.
+// pass's tag.  It never feeds the chain, so the chain never waits for it.  Each of its rows' words is
+// polled by one thread only (the chain's own gathers read the same lines: every further poller slows
+// them down) and handed to the others through LDS.
 __device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, int nworkers, Abort& ab) {
-    const int N = A.N, L = A.L, k = A.k;
+    __shared__ float s_wd[kThreads];
+    __shared__ int s_wdead;
+    const int N = A.N, L = A.L, k = A.k, t = threadIdx.x;
     const int part = wid % k, member = wid / k, members = (nworkers - part + k - 1) / k;
     const int RM = (N + members - 1) / members;
     const int jb = min(N, member * RM), je = min(N, jb + RM);
     if (jb >= je) return;
-    for (int layer = L - part; layer >= 2 && !ab.dead; layer -= k) {
+    if (t == 0) s_wdead = 0;
+    __syncthreads();
+    for (int layer = L - part; layer >= 2; layer -= k) {
         v4f ja[PG];
         load_activation_groups(A, layer - 1, ja);
         const u64* dl = A.DLL + (size_t)(layer - 2) * N;
-        // sixteen rows at a time: all their words are requested together (one round trip when delta^l
-        // is already there), rows whose words are not tagged yet are then waited for group by group
-        for (int row0 = jb; row0 < je && !ab.dead; row0 += 16) {
-            const u64* gp[4];
-            int gn[4];
+        for (int row0 = jb; row0 < je; row0 += kThreads) {
+            const int nb = min(kThreads, je - row0);
+            if (t < nb) s_wd[t] = ll_wait1(dl + row0 + t, A.epoch, ab, abort_code(3, layer, (int)blockIdx.x));
+            if (ab.dead) s_wdead = 1;
+            __syncthreads();
+            if (s_wdead) return;                    // the same for every thread
+            for (int r = 0; r < nb; r += 4) {
+                float d[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = row0 + 4 * i;
-                gn[i] = r < je ? min(4, je - r) : 0;
-                gp[i] = dl + min(r, je - 1);
+                for (int c = 0; c < 4; ++c) d[c] = s_wd[min(r + c, nb - 1)];
+                store_gradient_rows(A, layer, row0 + r, min(4, nb - r), d, ja);
             }
-            float d[4][4];
-            ll_gather4x4(gp, gn, A.epoch, d, ab, abort_code(3, layer, (int)blockIdx.x));
-            if (ab.dead) return;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (gn[i] > 0) store_gradient_rows(A, layer, row0 + 4 * i, gn[i], d[i], ja);
+            __syncthreads();                        // the next batch overwrites s_wd
         }
     }
 }
@@ -591,10 +607,11 @@ void persistent_forward_shape(int N, int num_cus, int requested, int* G, int* rp
     *G = (N + *rpg - 1) / *rpg;
 }
 
-// Backward chain: strips of 4*tpr columns, tpr in {1, 2, 4, 8}, each shared by rs row blocks;
-// GB = strips * rs workgroups.  Wide layers (N > 2048) take 128-byte strips in two row blocks.
+// Backward chain: strips of 4*tpr columns, tpr in {1, 2, 4, 8} (16 with four row blocks), each shared by
+// rs row blocks;
+// GB = strips * rs workgroups.  Wide layers (N > 2048) take 256-byte strips in four row blocks.
 void persistent_backward_shape(int N, int num_cus, int requested, int row_split, int* GB, int* tpr, int* rs) {
-    int split = (row_split == 1 || row_split == 2 || row_split == 4) ? row_split : (N > 2048 ? 2 : 1);
+    int split = (row_split == 1 || row_split == 2 || row_split == 4) ? row_split : (N > 2048 ? 4 : 1);
     while (split > 1 && N < 4 * split) split >>= 1;      // every row block holds rows
     int cap = requested > 0 ? requested : (N <= 2048 ? 128 : kMaxGroups);
     if (cap > kMaxGroups) cap = kMaxGroups;
@@ -604,7 +621,8 @@ void persistent_backward_shape(int N, int num_cus, int requested, int row_split,
     for (;; split >>= 1) {
         const int aim = cap / split > 0 ? cap / split : 1;   // strips aimed at
         int need = (groups4 + aim - 1) / aim, tp = 1;
-        while (tp < need && tp < 8) tp <<= 1;
+        const int tp_max = split == 4 ? 16 : 8;              // strips of up to 128 bytes, 256 in four blocks
+        while (tp < need && tp < tp_max) tp <<= 1;
         while (split > 1 && 4 * tp % split != 0) tp <<= 1;   // a strip's columns divide among its row blocks
         *tpr = tp;
         *rs = split;
@@ -661,6 +679,7 @@ hipError_t launch_bwd_persistent(const PersistArgs& A, hipStream_t s) {
         case 2: return launch_bwd_tpr<2>(A, grid, s);
         case 4: return launch_bwd_tpr<4>(A, grid, s);
         case 8: return launch_bwd_tpr<8>(A, grid, s);
+        case 16: return A.RS == 4 ? launch_bwd_tpr<16>(A, grid, s) : hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }

@@ -183,7 +183,8 @@ def test_cost_scale_is_exact_and_lifts_deep_layers_out_of_the_subnormal_range(sc
     (6, 260, 3, 2),       # ragged last strip, ragged second row block
     (4, 1028, 1, 4),      # sequential pass, four row blocks, ragged
     (7, 2052, 4, 2),      # just past a power of two
-    (5, 3076, 2, 4),
+    (5, 3076, 2, 4),      # 256-byte strips, ragged
+    (3, 4096, 2, 4),
     (4, 4096, 3, 1),      # the widest layer with whole-height strips
 ])
 def test_persistent_row_split_strips_match_oracle(monkeypatch, L, N, k, split):
