@@ -32,7 +32,8 @@ struct Layout {
     size_t partial_off, partial_bytes;
     size_t raw_off, raw_bytes;
     // persistent single-sample path: tagged-word exchange buffers, pointer tables, abort word
-    size_t dll_off, all_off, ll_words;   // [L-1][N] each
+    size_t dll_off, all_off, ll_words;   // [L-1][ll_layer] each
+    size_t ll_layer; int ll_shift;       // words per layer; spacing of the eight-word groups
     size_t pll_off, pll_words;           // [L-1][N][kMaxRowSplit]
     size_t tab_off, tab_bytes;       // w, b, nabla_w, nabla_b pointer tables, L-1 entries each
     size_t abort_off;
@@ -49,6 +50,17 @@ bool valid_shape(int L, int N, int B, lf_dtype dt) {
 
 bool single_sample_path(int N, int B, lf_dtype dt) { return B == 1 && dt == LF_F32 && N <= 16384; }
 
+// Spacing of the eight-word groups of an exchanged vector: 8 << shift bytes.
+// LF_PERSISTENT_LL_STRIDE (bytes, a power of two from 64 to 65536) overrides it for tuning; it is read
+// whenever a layout is made, so it has to be the same for lf_workspace_bytes and lf_create.
+int ll_spread_shift() {
+    int bytes = 64;
+    if (const char* e = std::getenv("LF_PERSISTENT_LL_STRIDE")) bytes = std::atoi(e);
+    int shift = 3;
+    while ((8 << shift) < bytes && shift < 13) ++shift;
+    return shift;
+}
+
 Layout make_layout(int L, int N, int B, lf_dtype dt) {
     Layout y{};
     const size_t M = (size_t)(L - 1), bn = (size_t)B * N;
@@ -63,11 +75,13 @@ Layout make_layout(int L, int N, int B, lf_dtype dt) {
     y.raw_off = off;
     y.raw_bytes = single_sample_path(N, B, dt) ? 0 : align_up(lf::split_workspace_floats(N, B, dt == LF_BF16) * 4);
     off += y.raw_bytes;
-    if (single_sample_path(N, B, dt) && lf::persistent_supported(N)) {
-        y.ll_words = M * (size_t)N;
+    if (single_sample_path(N, B, dt) && lf::persistent_supported(L, N)) {
+        y.ll_shift = ll_spread_shift();
+        y.ll_layer = lf::persistent_ll_layer_words(N, y.ll_shift);
+        y.ll_words = M * y.ll_layer;
         y.dll_off = off; off += align_up(y.ll_words * 8);
         y.all_off = off; off += align_up(y.ll_words * 8);
-        y.pll_words = y.ll_words * lf::kMaxRowSplit;
+        y.pll_words = M * (size_t)N * lf::kMaxRowSplit;
         y.pll_off = off; off += align_up(y.pll_words * 8);
         y.tab_off = off; y.tab_bytes = 4 * M * sizeof(void*);         off += align_up(y.tab_bytes);
         y.abort_off = off; off += kAlign;
@@ -99,7 +113,7 @@ struct lf_net {
     std::string err;
     // persistent path
     bool p_ready, p_tables_dirty;
-    int p_groups, p_rpg, p_bgroups, p_tpr, p_rs, p_workers;
+    int p_groups, p_rpg, p_bgroups, p_tpr, p_rs, p_workers, p_nap_fwd, p_nap_bwd;
     unsigned p_epoch;
     unsigned p_spin_limit;             // polls before a bounded wait gives up
     int* p_abort_host;                 // pinned, mapped; the kernels raise it when a wait gives up
@@ -154,7 +168,7 @@ lf_status ensure_workers(lf_net* net, int k) {
 }
 
 bool persistent_possible(const lf_net* net) {
-    return single_sample_path(net->N, net->B, net->dt) && lf::persistent_supported(net->N);
+    return single_sample_path(net->N, net->B, net->dt) && lf::persistent_supported(net->L, net->N);
 }
 
 bool use_persistent(const lf_net* net) {
@@ -200,6 +214,16 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
             if (w >= 1 && w <= 2 * lf::kMaxGroups) net->p_workers = w;
         }
         if (net->p_workers > net->N) net->p_workers = net->N;
+        // LF_PERSISTENT_NAP_FWD / _BWD: pause before the first poll of an exchange, units of 256 cycles
+        const char* envnf = std::getenv("LF_PERSISTENT_NAP_FWD");
+        const char* envnb = std::getenv("LF_PERSISTENT_NAP_BWD");
+        // (measured best: about N/256 units forward, twice that backward, where a step does more work)
+        int nap = net->N / 256;
+        nap = nap < 2 ? 2 : (nap > 8 ? 8 : nap);
+        net->p_nap_fwd = envnf ? std::atoi(envnf) : nap;
+        net->p_nap_bwd = envnb ? std::atoi(envnb) : 2 * nap;
+        if (net->p_nap_fwd < 0 || net->p_nap_fwd > 1024) net->p_nap_fwd = 0;
+        if (net->p_nap_bwd < 0 || net->p_nap_bwd > 1024) net->p_nap_bwd = 0;
         // every workgroup of a launch waits for others of it, so all of them must be resident at once:
         // two per compute unit (256 registers per thread at most)
         if (cus > 0 && (net->p_groups > 2 * cus || net->p_bgroups + 1 > 2 * cus))
@@ -265,6 +289,7 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     A.DLL = reinterpret_cast<unsigned long long*>(net->ws + net->lay.dll_off);
     A.ALL = reinterpret_cast<unsigned long long*>(net->ws + net->lay.all_off);
     A.PLL = reinterpret_cast<unsigned long long*>(net->ws + net->lay.pll_off);
+    A.ll_shift = net->lay.ll_shift; A.ll_layer = net->lay.ll_layer;
     A.y = static_cast<const float*>(y);
     A.abort_dev = reinterpret_cast<int*>(net->ws + net->lay.abort_off);
     A.abort_host = net->p_abort_dev_view;
@@ -401,7 +426,8 @@ lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream) {
     if (use_persistent(net)) {
         st0 = prepare_persistent(net, s);
         if (st0 != LF_OK) return st0;
-        const lf::PersistArgs A = persist_args(net, nullptr, 1);
+        lf::PersistArgs A = persist_args(net, nullptr, 1);
+        A.nap = net->p_nap_fwd;
         LF_HIP(net, lf::launch_fwd_persistent(A, s));
         net->fwd_done = true;
         return LF_OK;
@@ -438,7 +464,8 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
     if (use_persistent(net)) {
         st = prepare_persistent(net, s);
         if (st != LF_OK) return st;
-        const lf::PersistArgs A = persist_args(net, y, k);
+        lf::PersistArgs A = persist_args(net, y, k);
+        A.nap = net->p_nap_bwd;
         LF_HIP(net, lf::launch_bwd_persistent(A, s));
         net->bwd_done = true;
         return LF_OK;

@@ -8,6 +8,7 @@ namespace lf {
 constexpr int kMaxGroups = 256;          // chain workgroups of a persistent kernel (one per compute unit)
 constexpr int kMaxRowsPerGroup = 256;    // rows one forward workgroup may own
 constexpr int kMaxPersistentN = 4096;    // wider nets take the stream schedule
+constexpr int kMaxPersistentDepth = 1025; // deeper nets too (the per-layer pointer tables live in LDS)
 constexpr int kMaxRowSplit = 4;          // row blocks a backward column strip may be split into
 
 struct PersistArgs {
@@ -19,6 +20,9 @@ struct PersistArgs {
     unsigned epoch;                      // tag of this launch's words (never 0)
     float cost_scale;                    // power of two multiplied into delta^L (see lf_set_cost_scale)
     unsigned spin_limit;                 // polls after which a wait gives up and raises the abort word
+    int nap;                             // pause before the first poll of an exchange, in units of 256 cycles
+    int ll_shift;                        // exchanged vectors: element i is word ((i >> 3) << ll_shift) + (i & 7)
+    size_t ll_layer;                     // and one layer's vector takes ll_layer words
     const float* const* w;               // device tables, index l-2
     const float* const* b;
     float* const* gw;
@@ -26,15 +30,18 @@ struct PersistArgs {
     const float* a1;                     // x^1
     float* a_base;  size_t a_stride;     // a^l = a_base + (l-2)*a_stride  (floats), l >= 2
     float* d_base;  size_t d_stride;     // delta^l likewise
-    unsigned long long* DLL;             // [L-1][N]  delta^l as tagged words
-    unsigned long long* ALL;             // [L-1][N]  a^l as tagged words (forward)
+    unsigned long long* DLL;             // [L-1][ll_layer]  delta^l as tagged words
+    unsigned long long* ALL;             // [L-1][ll_layer]  a^l as tagged words (forward)
     unsigned long long* PLL;             // [L-1][N][RS]  row-block partial sums of (bp2) as tagged words
     const float* y;
     int* abort_dev;                      // device word
     int* abort_host;                     // mapped pinned host word, or null
 };
 
-bool persistent_supported(int N);
+bool persistent_supported(int L, int N);
+// Words one layer's exchanged vector of N elements takes when groups of eight words lie 8 << ll_shift
+// bytes apart (ll_shift = 3: packed).
+size_t persistent_ll_layer_words(int N, int ll_shift);
 // Launch shapes for width N on a device with num_cus compute units; requested > 0 overrides the
 // default number of workgroups.
 void persistent_forward_shape(int N, int num_cus, int requested, int* G, int* rpg);

@@ -36,8 +36,7 @@ typedef unsigned long long u64;
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
-constexpr int kTableLds = 1024;             // per-layer pointers kept in LDS (deeper nets read the rest
-                                            // from the device table, one memory round trip per step)
+constexpr int kTableLds = kMaxPersistentDepth - 1;   // per-layer pointers, all kept in LDS
 
 __device__ __forceinline__ u64 ll_pack(float v, unsigned tag) {
     return ((u64)tag << 32) | (u64)__float_as_uint(v);
@@ -73,10 +72,11 @@ struct Abort {
 // Poll up to four consecutive tagged words until all carry `tag`; n in 1..4 of them are valid.
 // The four loads of a round are always issued together (slots past n re-read word n-1), so a round
 // costs one memory round trip, not four.
-__device__ __forceinline__ void ll_wait4(const u64* p, int n, unsigned tag, float out[4], Abort& ab,
+// Returns whether the first poll missed.
+__device__ __forceinline__ bool ll_wait4(const u64* p, int n, unsigned tag, float out[4], Abort& ab,
                                          int code) {
     out[0] = out[1] = out[2] = out[3] = 0.0f;
-    if (n <= 0) return;
+    if (n <= 0) return false;
     const u64* q[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) q[c] = p + min(c, n - 1);
@@ -89,19 +89,22 @@ __device__ __forceinline__ void ll_wait4(const u64* p, int n, unsigned tag, floa
         if (ok) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) out[c] = (c < n) ? ll_val(w[c]) : 0.0f;
-            return;
+            return spin != 0;
         }
         ++spin;
         __builtin_amdgcn_s_sleep(2);   // a short back-off keeps the pollers from crowding the fabric
-        if (spin > ab.limit) { ab.raise(code); return; }
+        if (spin > ab.limit) { ab.raise(code); return true; }
         if ((spin & 255u) == 0u) ab.seen();
     }
+    return true;
 }
 
 // Gather up to four groups of four consecutive tagged words (group i at p[i], valid if n[i] > 0) with all
 // sixteen loads in flight at once; groups that do not carry the tag yet are then polled one by one.
-__device__ __forceinline__ void ll_gather4x4(const u64* const p[4], const int n[4], unsigned tag,
+// Returns whether any group missed at the first look.
+__device__ __forceinline__ bool ll_gather4x4(const u64* const p[4], const int n[4], unsigned tag,
                                              float out[4][4], Abort& ab, int code) {
+    bool missed = false;
     u64 w[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -113,8 +116,26 @@ __device__ __forceinline__ void ll_gather4x4(const u64* const p[4], const int n[
                         ll_tag(w[i][3]) == tag;
 #pragma unroll
         for (int c = 0; c < 4; ++c) out[i][c] = c < n[i] ? ll_val(w[i][c]) : 0.0f;
-        if (!ok && n[i] > 0) ll_wait4(p[i], n[i], tag, out[i], ab, code);
+        if (!ok && n[i] > 0) {
+            missed = true;
+            ll_wait4(p[i], n[i], tag, out[i], ab, code);
+        }
     }
+    return missed;
+}
+
+// Pause before the first poll of an exchange.  The peers need about a step's time to publish; polls sent
+// earlier find nothing and only queue up, in front of the peers' stores, at the few memory channels that
+// hold the exchanged words.
+__device__ __forceinline__ void nap(int units) {
+    for (int i = 0; i < units; ++i) __builtin_amdgcn_s_sleep(4);
+}
+// Word that holds element i of an exchanged vector.  Groups of eight words (64 bytes) are spread
+// 8 << ll_shift bytes apart, so that the polls for one vector go to many memory channels instead of the
+// one or two a packed vector would occupy.  Four consecutive elements starting at a multiple of four
+// are always four consecutive words.
+__device__ __forceinline__ size_t ll_index(const PersistArgs& A, int i) {
+    return ((size_t)(i >> 3) << A.ll_shift) + (size_t)(i & 7);
 }
 
 __device__ __forceinline__ const float* act_ptr(const PersistArgs& A, int l) {
@@ -134,13 +155,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArg
     __shared__ v4f s_a[Q * 64];
     __shared__ float s_bias[kMaxRowsPerGroup];
     __shared__ const float* s_w[kTableLds];      // w^l and b^l pointers: a table entry fetched from
-    __shared__ const float* s_b[kTableLds];      // memory on the chain would cost a round trip per layer
+    __shared__ const float* s_b[kTableLds];      // memory on the chain would cost a round trip per layer,
+                                                 // and a generic load of it would be waited for together
+                                                 // with every weight load in flight
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
     const int N = A.N, L = A.L, RPG = A.RPG, nvec = N >> 2;
-    for (int i = t; i < min(L - 1, kTableLds); i += kThreads) { s_w[i] = A.w[i]; s_b[i] = A.b[i]; }
+    for (int i = t; i < L - 1; i += kThreads) { s_w[i] = A.w[i]; s_b[i] = A.b[i]; }
     __syncthreads();
-    auto wptr = [&](int i) { return i < kTableLds ? s_w[i] : A.w[i]; };
-    auto bptr = [&](int i) { return i < kTableLds ? s_b[i] : A.b[i]; };
+    auto wptr = [&](int i) { return s_w[i]; };
+    auto bptr = [&](int i) { return s_b[i]; };
     const int RW = (RPG + kWaves - 1) / kWaves;             // rows per wave
     const int wrow0 = g * RPG + wave * RW;                  // first row of this wave
     const int wrow_end = min(min(N, (g + 1) * RPG), wrow0 + RW);
@@ -159,26 +182,26 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArg
         }
     };
 
-    // A wait for one load also waits for every older load and store of the wave.  So nothing slow is
-    // requested just before the weights in flight are awaited: next layer's bias is requested right
-    // after this layer's results are published, where its latency overlaps the exchange.
+    // A wait for one load also waits for every older load and store of the wave, and for nothing newer:
+    // next layer's bias is requested ahead of next layer's weights.
     const bool own = t < RPG && g * RPG + t < N;
-    float bias_next = own ? bptr(0)[g * RPG + t] : 0.0f;
+    float bias_next = own ? load_global_f32_here(bptr(0) + g * RPG + t) : 0.0f;
 
     // a^{l-1}, from the tagged words its owners published, into LDS
-    auto gather_activation = [&](int l) {
+    auto gather_activation = [&](int l) -> bool {
+        bool missed = false;
         if (l == 2) {
             for (int v = t; v < nvec; v += kThreads) s_a[v] = reinterpret_cast<const v4f*>(A.a1)[v];
-            return;
+            return false;
         }
-        const u64* src = A.ALL + (size_t)(l - 3) * N;
+        const u64* src = A.ALL + (size_t)(l - 3) * A.ll_layer;
         if (nvec <= kThreads) {
             if (t < nvec) {
                 float o[4];
-                ll_wait4(src + 4 * t, 4, A.epoch, o, ab, abort_code(1, l, g));
+                missed = ll_wait4(src + ll_index(A, 4 * t), 4, A.epoch, o, ab, abort_code(1, l, g));
                 s_a[t] = v4f{o[0], o[1], o[2], o[3]};
             }
-            return;
+            return missed;
         }
         for (int v0 = t; v0 < nvec; v0 += 4 * kThreads) {
             const u64* gp[4];
@@ -187,14 +210,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArg
             for (int i = 0; i < 4; ++i) {
                 const int v = v0 + i * kThreads;
                 gn[i] = v < nvec ? 4 : 0;
-                gp[i] = src + 4 * min(v, nvec - 1);
+                gp[i] = src + ll_index(A, 4 * min(v, nvec - 1));
             }
             float o[4][4];
-            ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(1, l, g));
+            missed |= ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(1, l, g));
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 if (gn[i]) s_a[v0 + i * kThreads] = v4f{o[i][0], o[i][1], o[i][2], o[i][3]};
         }
+        return missed;
     };
     // rows ci*RF .. of this wave: dot products with a^{l-1}, bias, sigma, publish
     auto finish_chunk = [&](const v4f (&buf)[RF][Q], int ci, int l) {
@@ -215,14 +239,14 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArg
             }
         }
         float* a_out = A.a_base + (size_t)(l - 2) * A.a_stride;
-        u64* pub = A.ALL + (size_t)(l - 2) * N;
+        u64* pub = A.ALL + (size_t)(l - 2) * A.ll_layer;
 #pragma unroll
         for (int rr = 0; rr < RF; ++rr) {
             const int row = wrow0 + ci * RF + rr;
             const float z = wave_sum(acc[rr]);
             if (lane == 0 && row < wrow_end) {
                 const float a = sigmoidf(z + s_bias[row - g * RPG]);
-                if (l < L) ll_store(pub + row, a, A.epoch);
+                if (l < L) ll_store(pub + ll_index(A, row), a, A.epoch);
                 a_out[row] = a;
             }
         }
@@ -233,10 +257,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArg
     // up in bufB; with an even number of chunks it ends up in bufA again.
     auto layer = [&](v4f (&bufA)[RF][Q], v4f (&bufB)[RF][Q], int l) {
         if (own) s_bias[t] = bias_next;
+        if (l > 2) nap(A.nap);
         gather_activation(l);
         __syncthreads();
         const float* W = wptr(l - 2);
         const float* Wn = l < L ? wptr(l - 1) : nullptr;
+        // requested before any of the next layer's weights: the wait for it then leaves those in flight
+        if (own && l < L) bias_next = load_global_f32_here(bptr(l - 1) + g * RPG + t);
         if constexpr (SINGLE) {
             if (Wn) load_chunk(bufB, Wn, 0);
             finish_chunk(bufA, 0, l);
@@ -252,7 +279,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArg
             }
             if (Wn) load_chunk(bufB, Wn, 1);
         }
-        if (own && l < L) bias_next = bptr(l - 1)[g * RPG + t];
         __syncthreads();   // s_a is rewritten by the next layer's gather
     };
 
@@ -335,10 +361,10 @@ __device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, i
     for (int layer = L - part; layer >= 2; layer -= k) {
         v4f ja[PG];
         load_activation_groups(A, layer - 1, ja);
-        const u64* dl = A.DLL + (size_t)(layer - 2) * N;
+        const u64* dl = A.DLL + (size_t)(layer - 2) * A.ll_layer;
         for (int row0 = jb; row0 < je; row0 += kThreads) {
             const int nb = min(kThreads, je - row0);
-            if (t < nb) s_wd[t] = ll_wait1(dl + row0 + t, A.epoch, ab, abort_code(3, layer, (int)blockIdx.x));
+            if (t < nb) s_wd[t] = ll_wait1(dl + ll_index(A, row0 + t), A.epoch, ab, abort_code(3, layer, (int)blockIdx.x));
             if (ab.dead) s_wdead = 1;
             __syncthreads();
             if (s_wdead) return;                    // the same for every thread
@@ -351,6 +377,15 @@ __device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, i
             __syncthreads();                        // the next batch overwrites s_wd
         }
     }
+}
+
+// Sum, in row order, of the sixteen per-row partial sums of one column (group q, element e).
+template <int TPR>
+__device__ __forceinline__ float strip_column_sum(const v4f (&red)[kWaves * 4][TPR], int q, int e) {
+    float u = red[0][q][e];
+#pragma unroll
+    for (int r = 1; r < kWaves * 4; ++r) u += red[r][q][e];
+    return u;
 }
 
 // Workgroups [0, GB) run the delta chain; workgroups [GB, gridDim.x) are the gradient workers
@@ -369,7 +404,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     constexpr int CPG = 4 * TPR;              // columns per chain workgroup
     constexpr int RPP = kThreads / TPR;       // rows covered by one load of the whole workgroup
     __shared__ v4f s_delta4[kMaxPersistentN / 4];       // delta^{l+1}, all of it
-    __shared__ v4f s_red[kWaves][TPR];
+    __shared__ v4f s_red[kWaves * 4][TPR];              // per row of 16 lanes
     __shared__ const float* s_w[kTableLds];             // w^l pointers (see the forward kernel)
     float* s_delta = reinterpret_cast<float*>(s_delta4);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
@@ -379,9 +414,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
         gradient_worker(A, g - GB, (int)gridDim.x - GB, ab);
         return;
     }
-    for (int i = t; i < min(L - 1, kTableLds); i += kThreads) s_w[i] = A.w[i];
+    for (int i = t; i < L - 1; i += kThreads) s_w[i] = A.w[i];
     __syncthreads();
-    auto wptr = [&](int i) { return i < kTableLds ? s_w[i] : A.w[i]; };
+    auto wptr = [&](int i) { return s_w[i]; };
     // strips of workgroups on one XCD (workgroups are dealt to the 8 XCDs round-robin) are adjacent,
     // and the workgroups that share a strip sit on one XCD
     const int RS = SPLIT ? A.RS : 1;
@@ -434,12 +469,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     };
     // delta^layer's rows of my row block (float4 groups [gv0, gv1)), from their tagged words, into LDS
     const int gv0 = row_lo >> 2, gv1 = (row_hi + 3) >> 2;
-    auto gather_delta = [&](int layer) {
-        const u64* src = A.DLL + (size_t)(layer - 2) * N;
+    auto gather_delta = [&](int layer) -> bool {
+        bool missed = false;
+        const u64* src = A.DLL + (size_t)(layer - 2) * A.ll_layer;
         if (nvec <= kThreads) {
             if (t >= gv0 && t < gv1) {
                 float o[4];
-                ll_wait4(src + 4 * t, 4, A.epoch, o, ab, abort_code(2, layer, g));
+                missed = ll_wait4(src + ll_index(A, 4 * t), 4, A.epoch, o, ab, abort_code(2, layer, g));
                 s_delta4[t] = v4f{o[0], o[1], o[2], o[3]};
             }
         } else {
@@ -450,15 +486,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
                 for (int i = 0; i < 4; ++i) {
                     const int v = v0 + i * kThreads;
                     gn[i] = v < gv1 ? 4 : 0;
-                    gp[i] = src + 4 * min(v, gv1 - 1);
+                    gp[i] = src + ll_index(A, 4 * min(v, gv1 - 1));
                 }
                 float o[4][4];
-                ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(2, layer, g));
+                missed |= ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(2, layer, g));
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     if (gn[i]) s_delta4[v0 + i * kThreads] = v4f{o[i][0], o[i][1], o[i][2], o[i][3]};
             }
         }
+        return missed;
     };
 
     // A wait for one load also waits for every older load and store of the wave.  So nothing slow is
@@ -467,7 +504,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     // columns whose delta this workgroup finishes and publishes: its strip, or its share of it
     const int nfin = SPLIT ? CPG / RS : CPG, fcol0 = col0 + rb * nfin;
     const bool own = t < nfin && fcol0 + t < N;
-    float a_next = (own && L > 2) ? act_ptr(A, L - 1)[fcol0 + t] : 0.0f;
+    float a_next = (own && L > 2) ? load_global_f32_here(act_ptr(A, L - 1) + fcol0 + t) : 0.0f;
     v4f buf[NB][CH];
     if (L > 2) {                                     // my strip of w^L, needed by the first chain step
         load_chunk(buf[0], wptr(L - 2), 0);
@@ -488,7 +525,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
         __syncthreads();
         if (own) {
             const float d = s_delta[fcol0 + t];
-            ll_store(A.DLL + (size_t)(L - 2) * N + fcol0 + t, d, A.epoch);
+            ll_store(A.DLL + (size_t)(L - 2) * A.ll_layer + ll_index(A, fcol0 + t), d, A.epoch);
             A.d_base[(size_t)(L - 2) * A.d_stride + fcol0 + t] = d;
         }
     }
@@ -534,15 +571,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
                 }
             }
         }
-        // add the threads that share a column group: lanes by butterfly, then the four waves in order
-#pragma unroll
-        for (int off = TPR; off < kWave; off <<= 1) {
-            acc.x += __shfl_xor(acc.x, off, kWave);
-            acc.y += __shfl_xor(acc.y, off, kWave);
-            acc.z += __shfl_xor(acc.z, off, kWave);
-            acc.w += __shfl_xor(acc.w, off, kWave);
-        }
-        if (lane < TPR) s_red[wave][lane] = acc;
+        // add the threads that share a column group: within each row of 16 lanes by rotation; the sixteen
+        // rows of the workgroup are then added in order by the thread that finishes the column
+        acc.x = row_class_sum<TPR>(acc.x);
+        acc.y = row_class_sum<TPR>(acc.y);
+        acc.z = row_class_sum<TPR>(acc.z);
+        acc.w = row_class_sum<TPR>(acc.w);
+        if ((lane & 15) < TPR) s_red[wave * 4 + (lane >> 4)][lane & 15] = acc;
         __syncthreads();
         if constexpr (SPLIT) {
             // my row block's partial sums of the strip go out; the partials of my share of its columns
@@ -550,7 +585,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
             u64* pl = A.PLL + (size_t)(l - 2) * N * RS;
             if (t < CPG && col0 + t < N) {
                 const int q = t >> 2, e = t & 3;
-                const float u = ((s_red[0][q][e] + s_red[1][q][e]) + s_red[2][q][e]) + s_red[3][q][e];
+                const float u = strip_column_sum(s_red, q, e);
                 ll_store(pl + (size_t)(col0 + t) * RS + rb, u, A.epoch);
             }
             if (own) {
@@ -558,19 +593,20 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
                 ll_wait4(pl + (size_t)(fcol0 + t) * RS, RS, A.epoch, p, ab, abort_code(0, l, g));
                 const float u = ((p[0] + p[1]) + p[2]) + p[3];      // slots past RS hold zeros
                 const float d = u * (a_l * (1.0f - a_l));
-                ll_store(A.DLL + (size_t)(l - 2) * N + fcol0 + t, d, A.epoch);
+                ll_store(A.DLL + (size_t)(l - 2) * A.ll_layer + ll_index(A, fcol0 + t), d, A.epoch);
                 A.d_base[(size_t)(l - 2) * A.d_stride + fcol0 + t] = d;
-                if (l > 2) a_next = act_ptr(A, l - 1)[fcol0 + t];
+                if (l > 2) a_next = load_global_f32_here(act_ptr(A, l - 1) + fcol0 + t);
             }
         } else if (own) {
             const int q = t >> 2, e = t & 3;
-            const float u = ((s_red[0][q][e] + s_red[1][q][e]) + s_red[2][q][e]) + s_red[3][q][e];
+            const float u = strip_column_sum(s_red, q, e);
             const float d = u * (a_l * (1.0f - a_l));
-            ll_store(A.DLL + (size_t)(l - 2) * N + col0 + t, d, A.epoch);
+            ll_store(A.DLL + (size_t)(l - 2) * A.ll_layer + ll_index(A, col0 + t), d, A.epoch);
             A.d_base[(size_t)(l - 2) * A.d_stride + col0 + t] = d;
-            if (l > 2) a_next = act_ptr(A, l - 1)[col0 + t];
+            if (l > 2) a_next = load_global_f32_here(act_ptr(A, l - 1) + col0 + t);
         }
         // exchange: all of delta^l (every workgroup is past its last read of delta^{l+1})
+        nap(A.nap);
         gather_delta(l);
         __syncthreads();
     };
@@ -593,7 +629,13 @@ __global__ __launch_bounds__(kThreads) void k_fill_u64(u64* p, size_t n, u64 v) 
 
 }  // namespace
 
-bool persistent_supported(int N) { return N % 4 == 0 && N >= 4 && N <= kMaxPersistentN; }
+size_t persistent_ll_layer_words(int N, int ll_shift) {
+    return ((size_t)((N + 7) >> 3) << ll_shift);
+}
+
+bool persistent_supported(int L, int N) {
+    return N % 4 == 0 && N >= 4 && N <= kMaxPersistentN && L >= 2 && L <= kMaxPersistentDepth;
+}
 
 // Forward: G workgroups, each owning rpg rows; every workgroup owns at least one row.
 void persistent_forward_shape(int N, int num_cus, int requested, int* G, int* rpg) {
@@ -639,6 +681,7 @@ hipError_t launch_fill_u64(void* p, size_t n_words, unsigned long long v, hipStr
 }
 
 hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s) {
+    if (!persistent_supported(A.L, A.N)) return hipErrorInvalidValue;
     const int q = (A.N / 4 + 63) / 64;                       // float4 groups per lane and row
     const int rw = (A.RPG + kWaves - 1) / kWaves;            // rows per wave
     if (q <= 4) {
@@ -670,7 +713,7 @@ static hipError_t launch_bwd_tpr(const PersistArgs& A, int grid, hipStream_t s) 
 }
 
 hipError_t launch_bwd_persistent(const PersistArgs& A, hipStream_t s) {
-    if (A.GB > kMaxGroups * 2 || A.N > kMaxPersistentN) return hipErrorInvalidValue;
+    if (A.GB > kMaxGroups * 2 || !persistent_supported(A.L, A.N)) return hipErrorInvalidValue;
     if (A.RS != 1 && A.RS != 2 && A.RS != 4) return hipErrorInvalidValue;
     if (A.GB % A.RS != 0 || (4 * A.TPR) % A.RS != 0) return hipErrorInvalidValue;
     const int grid = A.GB + (A.k > 1 ? A.GW : 0);    // chain workgroups, then the gradient workers
