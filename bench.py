@@ -40,10 +40,12 @@ def measured_traffic(cfg_name, k):
     (profiles/traffic.json), or None when the kernel source has changed since they were taken."""
     import hashlib
     path = os.path.join(ROOT, "profiles", "traffic.json")
-    src = os.path.join(ROOT, "paper_1801_04928_amd", "csrc", "persistent_kernels.hip")
     try:
         rec = json.load(open(path))
-        if rec.get("kernel_source_sha256") != hashlib.sha256(open(src, "rb").read()).hexdigest():
+        h = hashlib.sha256()
+        for name in ("persistent_kernels.hip", "persistent.h", "lf_internal.h"):
+            h.update(open(os.path.join(ROOT, "paper_1801_04928_amd", "csrc", name), "rb").read())
+        if rec.get("kernel_source_sha256") != h.hexdigest():
             return None
         e = rec.get(f"{cfg_name}_k{k}")
         return None if e is None else e["fetch_bytes"] + e["write_bytes"]
