@@ -311,6 +311,197 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g) {
         }
 }
 
+
+// ================================================================================================
+// bf16, large shapes: 256 x 256 tile, 512 threads
+// ================================================================================================
+// With 64 x 64 wave tiles one K = 16 step reads 4 KB of LDS per wave for 4 MFMAs (128 cycles): four
+// busy SIMDs would need 128 bytes per clock, all the LDS has -- the matrix cores wait for operands half
+// of the time.  Here a wave owns 64 x 128 (6 KB per 8 MFMAs: 96 bytes per clock), eight waves (4 x 2)
+// share a 256 x 256 tile (128 flops per operand byte fetched, against 64), and LDS is double-buffered:
+// tile t is multiplied while tile t+1 goes from registers to the other buffer and tile t+2 is
+// requested, with one barrier per tile.  Two waves per SIMD cover each other's waits.
+namespace big {
+constexpr int kThreadsBig = 512;
+constexpr int TM = 256, TN = 256, TK = 64;
+constexpr int LDA = TK + 8;                // QC operand in LDS: [i][q]
+constexpr int LDI = TM + 16;               // IC operand in LDS: [q][i]
+constexpr int ELEMS = TM * LDA > TK * LDI ? TM * LDA : TK * LDI;     // per operand and buffer
+
+// 16-byte pieces of one operand tile, four per thread
+template <bool IC> struct StageBig;
+template <> struct StageBig<false> {       // [i][q]: 8 threads cover the 64 q of one row
+    v4f r[4];
+    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int I, int Kq) {
+        const int t = threadIdx.x, qv = (t & 7) * 8;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = (t >> 3) + 64 * u;
+            const bool ok = (i0 + i < I) && (q0 + qv < Kq);
+            const unsigned off = ((unsigned)(i0 + i) * (unsigned)ld + (unsigned)(q0 + qv)) * 2u;
+            r[u] = buffer_load_v4f(buf, ok ? off : kOutside);
+        }
+    }
+    __device__ void store(__bf16* s) const {
+        const int t = threadIdx.x, qv = (t & 7) * 8;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) *reinterpret_cast<v4f*>(s + ((t >> 3) + 64 * u) * LDA + qv) = r[u];
+    }
+};
+template <> struct StageBig<true> {        // [q][i]: 32 threads cover the 256 i of one q
+    v4f r[4];
+    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int I, int Kq) {
+        const int t = threadIdx.x, iv = (t & 31) * 8;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = (t >> 5) * 4 + u;
+            const bool ok = (q0 + q < Kq) && (i0 + iv < I);
+            const unsigned off = ((unsigned)(q0 + q) * (unsigned)ld + (unsigned)(i0 + iv)) * 2u;
+            r[u] = buffer_load_v4f(buf, ok ? off : kOutside);
+        }
+    }
+    __device__ void store(__bf16* s) const {
+        const int t = threadIdx.x, iv = (t & 31) * 8, q = (t >> 5) * 4;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) *reinterpret_cast<v4f*>(s + (q + u) * LDI + iv) = r[u];
+    }
+};
+
+template <bool P_IC, bool Q_IC, int EPI>
+__global__ __launch_bounds__(kThreadsBig) void k_gemm_big(const GemmArgs g) {
+    // two buffers of two operand tiles; afterwards the staging area of the gradient epilogue
+    extern __shared__ __attribute__((aligned(16))) char s_dyn[];
+    __bf16* s_base = reinterpret_cast<__bf16*>(s_dyn);
+    auto s_p = [&](int b) { return s_base + (2 * b) * ELEMS; };
+    auto s_q = [&](int b) { return s_base + (2 * b + 1) * ELEMS; };
+
+    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
+    const int r32 = lane & 31, half = lane >> 5;
+
+    const int kt_total = ceil_div(g.K, TK);
+    const int kt_begin = blockIdx.z * g.k_tiles_per_split;
+    const int kt_end = min(kt_total, kt_begin + g.k_tiles_per_split);
+    const int T = kt_end - kt_begin;
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    StageBig<P_IC> sp;
+    StageBig<Q_IC> sq;
+    const __amdgpu_buffer_rsrc_t P = make_buffer(g.P, g.p_bytes);
+    const __amdgpu_buffer_rsrc_t Q = make_buffer(g.Q, g.q_bytes);
+    auto request = [&](int t) {
+        sp.load(P, g.ldp, m0, (kt_begin + t) * TK, g.M, g.K);
+        sq.load(Q, g.ldq, n0, (kt_begin + t) * TK, g.Nn, g.K);
+    };
+    auto multiply = [&](const __bf16* tp, const __bf16* tq) {
+#pragma unroll
+        for (int kk = 0; kk < TK; kk += 16) {
+            v8bf a[2], b[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                if constexpr (P_IC) a[i] = lds_operand_transposed(tp, LDI, wm + i * 32, kk);
+                else a[i] = *reinterpret_cast<const v8bf*>(&tp[(wm + i * 32 + r32) * LDA + kk + half * 8]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (Q_IC) b[j] = lds_operand_transposed(tq, LDI, wn + j * 32, kk);
+                else b[j] = *reinterpret_cast<const v8bf*>(&tq[(wn + j * 32 + r32) * LDA + kk + half * 8]);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    if (T > 0) {
+        request(0);
+        sp.store(s_p(0));
+        sq.store(s_q(0));
+        if (T > 1) request(1);
+        __syncthreads();
+        for (int t = 0; t < T; ++t) {
+            const int cur = t & 1;
+            // buffer cur^1 was last read before the barrier that ended the previous iteration
+            if (t + 1 < T) {
+                sp.store(s_p(cur ^ 1));
+                sq.store(s_q(cur ^ 1));
+            }
+            if (t + 2 < T) request(t + 2);
+            __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the multiplications
+            multiply(s_p(cur), s_q(cur));
+            __syncthreads();
+        }
+    }
+
+    // Accumulator element e of lane (r32, half) in tile (i, j) is
+    // C[m0 + wm + 32 i + 8 (e/4) + 4 half + e%4][n0 + wn + 32 j + r32].
+    if constexpr (EPI == EPI_GRAD) {
+        // each wave turns its accumulators through a private LDS area (all operand reads are behind the
+        // last barrier) so that a lane stores 16 contiguous bytes and a wave 2 rows x 512 contiguous bytes
+        constexpr int LDE = 128 + 4;
+        float* stage = reinterpret_cast<float*>(s_dyn) + wave * 32 * LDE;
+        float* out = static_cast<float*>(g.out);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    stage[(8 * (e >> 2) + 4 * half + (e & 3)) * LDE + j * 32 + r32] = acc[i][j][e];
+#pragma unroll
+            for (int it = 0; it < 16; ++it) {
+                const int row = 2 * it + (lane >> 5), c4 = (lane & 31) * 4;
+                const v4f v = *reinterpret_cast<const v4f*>(&stage[row * LDE + c4]);
+                const int m = m0 + wm + i * 32 + row, n = n0 + wn + c4;
+                if (m < g.M && n < g.Nn) store_global_nt_v4f(out + (size_t)m * g.Nn + n, v);
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + wn + j * 32 + r32;
+            if (n >= g.Nn) continue;
+            float bias = 0.0f;
+            if constexpr (EPI == EPI_SIGMOID) bias = g.bias[n];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m0 + wm + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+                if (m >= g.M) continue;
+                const size_t o = (size_t)m * g.Nn + n;
+                const float v = acc[i][j][e];
+                if constexpr (EPI == EPI_RAW) {
+                    g.raw[(size_t)blockIdx.z * g.M * g.Nn + o] = v;
+                } else if constexpr (EPI == EPI_SIGMOID) {
+                    static_cast<__bf16*>(g.out)[o] = (__bf16)sigmoidf(v + bias);
+                } else if constexpr (EPI == EPI_SIGMA_PRIME) {
+                    const float a = (float)static_cast<const __bf16*>(g.act)[o];
+                    const float d = v * (a * (1.0f - a));
+                    static_cast<float*>(g.out)[o] = d;
+                    static_cast<__bf16*>(g.out_bf)[o] = (__bf16)d;
+                }
+            }
+        }
+}
+
+static_assert(TK == Tile<__bf16>::BK, "both bf16 kernels count k-tiles of the same length");
+constexpr int kLdsBytes = 2 * 2 * ELEMS * 2;     // two buffers x two operands x bf16
+static_assert(kLdsBytes >= 8 * 32 * (128 + 4) * 4, "the gradient epilogue's staging area fits");
+static_assert(kLdsBytes <= 160 * 1024, "LDS of one compute unit");
+}  // namespace big
+
 // Split-K second stage: sum the raw partials in split order, then the layer's epilogue.
 template <typename T, int EPI>
 __global__ __launch_bounds__(kThreads) void k_split_finish(const float* __restrict__ raw, int splits,
@@ -365,11 +556,48 @@ hipError_t run(GemmArgs g, int splits, hipStream_t s) {
     return hipGetLastError();
 }
 
+template <bool P_IC, bool Q_IC, int EPI>
+hipError_t run_big(GemmArgs g, int splits, hipStream_t s) {
+    const unsigned long long pb = (unsigned long long)(P_IC ? g.K : g.M) * g.ldp * 2ull;
+    const unsigned long long qb = (unsigned long long)(Q_IC ? g.K : g.Nn) * g.ldq * 2ull;
+    if (pb >= 0xFFFFFFF0ull || qb >= 0xFFFFFFF0ull) return hipErrorInvalidValue;
+    g.p_bytes = (unsigned)pb;
+    g.q_bytes = (unsigned)qb;
+    static bool attr_set = false;     // more than 64 KB of dynamic LDS has to be asked for once
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&big::k_gemm_big<P_IC, Q_IC, EPI>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, big::kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const dim3 grid(ceil_div(g.Nn, big::TN), ceil_div(g.M, big::TM), splits);
+    big::k_gemm_big<P_IC, Q_IC, EPI><<<grid, big::kThreadsBig, big::kLdsBytes, s>>>(g);
+    return hipGetLastError();
+}
+
 }  // namespace
 
+// Whether a net of this shape takes the 256 x 256 bf16 kernel: when the forward product has at least 64
+// such tiles.  LF_GEMM_BIG=0/1 forces the choice (tests, A/B runs); the caller decides once per net.
+bool gemm_use_big(int N, int B, bool bf16) {
+    if (!bf16) return false;
+    if (const char* e = getenv("LF_GEMM_BIG")) {
+        if (e[0] == '0') return false;
+        if (e[0] == '1') return true;
+    }
+    return ceil_div(B, big::TM) * ceil_div(N, big::TN) >= 64;
+}
+
 // Number of K splits used for the two chain-side GEMMs (output B x N is small, so a single pass over
-// K would leave most compute units idle).  Depends on the shape alone.
-int chain_splits(int N, int B, bool bf16) {
+// K would leave most compute units idle).  Depends on the shape (and the kernel chosen) alone.
+int chain_splits(int N, int B, bool bf16, bool big_tiles) {
+    if (big_tiles) {
+        const int tiles = ceil_div(N, big::TN) * ceil_div(B, big::TM);
+        const int kt = ceil_div(N, big::TK);
+        int s = 1;
+        while (tiles * s < 256 && s < 16 && kt / (s * 2) >= 4) s *= 2;      // one workgroup per compute unit
+        return s;
+    }
     const int tiles = ceil_div(N, BN) * ceil_div(B, BM);
     const int kt = ceil_div(N, bf16 ? Tile<__bf16>::BK : Tile<float>::BK);
     int s = 1;
@@ -377,22 +605,34 @@ int chain_splits(int N, int B, bool bf16) {
     return s;
 }
 
-size_t split_workspace_floats(int N, int B, bool bf16) {
-    const int s = chain_splits(N, B, bf16);
+size_t split_workspace_floats(int N, int B, bool bf16) {      // enough for either kernel
+    int s = chain_splits(N, B, bf16, false);
+    if (bf16) s = max(s, chain_splits(N, B, true, true));
     return s > 1 ? (size_t)s * B * N : 0;
 }
 
 template <typename T>
 static hipError_t fwd_impl(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
-                           int N, int B, hipStream_t s) {
+                           int N, int B, bool big_tiles, hipStream_t s) {
     constexpr bool bf = sizeof(T) == 2;
-    const int splits = chain_splits(N, B, bf);
+    const int splits = chain_splits(N, B, bf, big_tiles);
     GemmArgs g{};
     g.P = A_in; g.ldp = N; g.Q = W; g.ldq = N; g.M = B; g.Nn = N; g.K = N;
     g.k_tiles_per_split = ceil_div(ceil_div(N, Tile<T>::BK), splits);
     g.bias = bias; g.out = A_out; g.raw = raw;
-    if (splits == 1) return run<T, false, false, EPI_SIGMOID>(g, 1, s);
-    hipError_t e = run<T, false, false, EPI_RAW>(g, splits, s);
+    hipError_t e;
+    if constexpr (bf) {
+        if (big_tiles) {
+            if (splits == 1) return run_big<false, false, EPI_SIGMOID>(g, 1, s);
+            e = run_big<false, false, EPI_RAW>(g, splits, s);
+        } else {
+            if (splits == 1) return run<T, false, false, EPI_SIGMOID>(g, 1, s);
+            e = run<T, false, false, EPI_RAW>(g, splits, s);
+        }
+    } else {
+        if (splits == 1) return run<T, false, false, EPI_SIGMOID>(g, 1, s);
+        e = run<T, false, false, EPI_RAW>(g, splits, s);
+    }
     if (e != hipSuccess) return e;
     const size_t count = (size_t)B * N;
     k_split_finish<T, EPI_SIGMOID><<<(unsigned)((count + kThreads - 1) / kThreads), kThreads, 0, s>>>(
@@ -402,15 +642,26 @@ static hipError_t fwd_impl(const void* W, const float* bias, const void* A_in, v
 
 template <typename T>
 static hipError_t chain_impl(const void* W_next, const void* D_next_op, const void* A_l, float* D_l,
-                             void* D_l_bf, float* raw, int N, int B, hipStream_t s) {
+                             void* D_l_bf, float* raw, int N, int B, bool big_tiles, hipStream_t s) {
     constexpr bool bf = sizeof(T) == 2;
-    const int splits = chain_splits(N, B, bf);
+    const int splits = chain_splits(N, B, bf, big_tiles);
     GemmArgs g{};
     g.P = D_next_op; g.ldp = N; g.Q = W_next; g.ldq = N; g.M = B; g.Nn = N; g.K = N;
     g.k_tiles_per_split = ceil_div(ceil_div(N, Tile<T>::BK), splits);
     g.act = A_l; g.out = D_l; g.out_bf = D_l_bf; g.raw = raw;
-    if (splits == 1) return run<T, false, true, EPI_SIGMA_PRIME>(g, 1, s);
-    hipError_t e = run<T, false, true, EPI_RAW>(g, splits, s);
+    hipError_t e;
+    if constexpr (bf) {
+        if (big_tiles) {
+            if (splits == 1) return run_big<false, true, EPI_SIGMA_PRIME>(g, 1, s);
+            e = run_big<false, true, EPI_RAW>(g, splits, s);
+        } else {
+            if (splits == 1) return run<T, false, true, EPI_SIGMA_PRIME>(g, 1, s);
+            e = run<T, false, true, EPI_RAW>(g, splits, s);
+        }
+    } else {
+        if (splits == 1) return run<T, false, true, EPI_SIGMA_PRIME>(g, 1, s);
+        e = run<T, false, true, EPI_RAW>(g, splits, s);
+    }
     if (e != hipSuccess) return e;
     const size_t count = (size_t)B * N;
     k_split_finish<T, EPI_SIGMA_PRIME><<<(unsigned)((count + kThreads - 1) / kThreads), kThreads, 0, s>>>(
@@ -419,20 +670,20 @@ static hipError_t chain_impl(const void* W_next, const void* D_next_op, const vo
 }
 
 hipError_t launch_fwd_gemm(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
-                           int N, int B, bool bf16, hipStream_t s) {
-    return bf16 ? fwd_impl<__bf16>(W, bias, A_in, A_out, raw, N, B, s)
-                : fwd_impl<float>(W, bias, A_in, A_out, raw, N, B, s);
+                           int N, int B, bool bf16, bool big_tiles, hipStream_t s) {
+    return bf16 ? fwd_impl<__bf16>(W, bias, A_in, A_out, raw, N, B, big_tiles, s)
+                : fwd_impl<float>(W, bias, A_in, A_out, raw, N, B, false, s);
 }
 
 hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void* D_next_bf,
                              const void* A_l, float* D_l, void* D_l_bf, float* raw, int N, int B,
-                             bool bf16, hipStream_t s) {
-    return bf16 ? chain_impl<__bf16>(W_next, D_next_bf, A_l, D_l, D_l_bf, raw, N, B, s)
-                : chain_impl<float>(W_next, D_next, A_l, D_l, nullptr, raw, N, B, s);
+                             bool bf16, bool big_tiles, hipStream_t s) {
+    return bf16 ? chain_impl<__bf16>(W_next, D_next_bf, A_l, D_l, D_l_bf, raw, N, B, big_tiles, s)
+                : chain_impl<float>(W_next, D_next, A_l, D_l, nullptr, raw, N, B, false, s);
 }
 
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
-                            float* nabla_b, int N, int B, bool bf16, hipStream_t s) {
+                            float* nabla_b, int N, int B, bool bf16, bool big_tiles, hipStream_t s) {
     k_bias_grad<<<ceil_div(N, 32), kThreads, 0, s>>>(D, nabla_b, N, B);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -442,6 +693,7 @@ hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev
     if (bf16) {
         g.P = D_bf;
         g.k_tiles_per_split = ceil_div(B, Tile<__bf16>::BK);
+        if (big_tiles) return run_big<true, true, EPI_GRAD>(g, 1, s);
         return run<__bf16, true, true, EPI_GRAD>(g, 1, s);
     }
     g.P = D;

@@ -100,6 +100,7 @@ struct lf_net {
     lf_cost cost;
     lf_sched sched;
     float cost_scale;
+    bool gemm_big;                     // minibatch bf16: the 256 x 256-tile kernel (decided at creation)
     char* ws;
     Layout lay;
     std::vector<const void*> w;       // index l-2
@@ -304,7 +305,7 @@ lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
                                               net->gw[i], net->gb[i], net->N, s));
     } else {
         LF_HIP(net, lf::launch_grad_gemm(net->d_ptr(l), net->dbf_ptr(l), net->a_ptr(l - 1), net->gw[i],
-                                         net->gb[i], net->N, net->B, net->dt == LF_BF16, s));
+                                         net->gb[i], net->N, net->B, net->dt == LF_BF16, net->gemm_big, s));
     }
     return LF_OK;
 }
@@ -341,6 +342,7 @@ lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost
     net->lay = make_layout(L, N, B, dt);
     net->x1 = nullptr;
     net->have_params = net->have_grads = net->fwd_done = net->bwd_done = false;
+    net->gemm_big = lf::gemm_use_big(N, B, dt == LF_BF16);
     net->p_ready = false; net->p_tables_dirty = true; net->p_groups = net->p_rpg = net->p_bgroups = net->p_tpr = 0; net->p_workers = 0; net->p_epoch = 0;
     net->p_abort_host = nullptr; net->p_abort_dev_view = nullptr;
     net->err = "no error";
@@ -439,7 +441,7 @@ lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream) {
                                                 static_cast<float*>(net->a_ptr(l)), net->N, s));
         } else {
             LF_HIP(net, lf::launch_fwd_gemm(net->w[l - 2], net->b[l - 2], net->a_ptr(l - 1), net->a_ptr(l),
-                                            net->raw(), net->N, net->B, bf, s));
+                                            net->raw(), net->N, net->B, bf, net->gemm_big, s));
         }
     }
     net->fwd_done = true;
@@ -486,7 +488,7 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
                                                    net->partial(), N, s));
         } else {
             LF_HIP(net, lf::launch_chain_gemm(net->w[l - 1], net->d_ptr(l + 1), net->dbf_ptr(l + 1), net->a_ptr(l),
-                                              net->d_ptr(l), net->dbf_ptr(l), net->raw(), N, B, bf, s));
+                                              net->d_ptr(l), net->dbf_ptr(l), net->raw(), N, B, bf, net->gemm_big, s));
         }
         // (bp3),(bp4) of layer l, off the chain
         if (k == 1) {

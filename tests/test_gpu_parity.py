@@ -258,6 +258,22 @@ def test_minibatch_matches_oracle(L, N, B, dtype, k):
     _free(g)
 
 
+@pytest.mark.parametrize("L,N,B,k", [
+    (3, 264, 70, 1),        # one ragged 256 x 256 tile per product; k-tiles 64 + 6
+    (4, 520, 260, 2),       # 3 x 3 tiles with ragged edges, split K on the chain side
+    (3, 1024, 512, 2),      # full tiles only
+])
+def test_minibatch_bf16_large_tile_kernel_matches_oracle(monkeypatch, L, N, B, k):
+    """The 256 x 256-tile bf16 contraction kernel (the one wide bf16 nets take), forced at sizes the oracle
+    finishes quickly and that leave ragged tiles in every dimension."""
+    monkeypatch.setenv("LF_GEMM_BIG", "1")
+    net = make_net(L, N, B, dtype="bf16", seed=7 * N + B)
+    g = run_gpu(net, k)
+    rep = check_against_oracle(net, g)
+    log(f"large-tile bf16: B={B} L={L} N={N} k={k}: worst normwise error {rep['worst']:.2e}")
+    _free(g)
+
+
 # ---------------------------------------------------------------- the five configurations, full size
 def test_config1_full():
     net = config_net("cfg1", cache=True)
