@@ -332,12 +332,12 @@ constexpr int ELEMS = TM * LDA > TK * LDI ? TM * LDA : TK * LDI;     // per oper
 template <bool IC> struct StageBig;
 template <> struct StageBig<false> {       // [i][q]: 8 threads cover the 64 q of one row
     v4f r[4];
-    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int I, int Kq) {
+    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int I, int Kq, bool live) {
         const int t = threadIdx.x, qv = (t & 7) * 8;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i = (t >> 3) + 64 * u;
-            const bool ok = (i0 + i < I) && (q0 + qv < Kq);
+            const bool ok = live && (i0 + i < I) && (q0 + qv < Kq);
             const unsigned off = ((unsigned)(i0 + i) * (unsigned)ld + (unsigned)(q0 + qv)) * 2u;
             r[u] = buffer_load_v4f(buf, ok ? off : kOutside);
         }
@@ -350,12 +350,12 @@ template <> struct StageBig<false> {       // [i][q]: 8 threads cover the 64 q o
 };
 template <> struct StageBig<true> {        // [q][i]: 32 threads cover the 256 i of one q
     v4f r[4];
-    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int I, int Kq) {
+    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int I, int Kq, bool live) {
         const int t = threadIdx.x, iv = (t & 31) * 8;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int q = (t >> 5) * 4 + u;
-            const bool ok = (q0 + q < Kq) && (i0 + iv < I);
+            const bool ok = live && (q0 + q < Kq) && (i0 + iv < I);
             const unsigned off = ((unsigned)(q0 + q) * (unsigned)ld + (unsigned)(i0 + iv)) * 2u;
             r[u] = buffer_load_v4f(buf, ok ? off : kOutside);
         }
@@ -367,13 +367,39 @@ template <> struct StageBig<true> {        // [q][i]: 32 threads cover the 256 i
     }
 };
 
+// Issue order of one tile's block, as scheduling groups (mask: 0x008 MFMA, 0x020 memory read, 0x100 LDS
+// read, 0x200 LDS write).  A k = 16 step is 8 MFMAs; its operands (6 fragments, one or two LDS reads
+// each) are read during the step before; the 8 LDS writes and the 8 requests alternate, two of each per
+// step.
+template <int R, int I>      // I = 8 * step + index of the MFMA within the step
+__device__ __forceinline__ void interleave_from() {
+    if constexpr (I < 32) {
+        constexpr int step = I / 8, m = I % 8, per = (R + 7) / 8;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if constexpr (step < 3 && m * per < R) __builtin_amdgcn_sched_group_barrier(0x100, per, 0);
+        // a staged vector goes to LDS and its registers are requested again right away: every request
+        // then has a whole tile's multiplications to come back
+        if constexpr (m % 4 == 1) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        if constexpr (m % 4 == 3) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        interleave_from<R, I + 1>();
+    }
+}
+template <bool P_IC, bool Q_IC>
+__device__ __forceinline__ void interleave() {
+    constexpr int R = (P_IC ? 4 : 2) + (Q_IC ? 8 : 4);     // LDS reads per step (6, 10 or 12)
+    __builtin_amdgcn_sched_group_barrier(0x100, R, 0);      // operands of step 0
+    interleave_from<R, 0>();
+}
+
 template <bool P_IC, bool Q_IC, int EPI>
 __global__ __launch_bounds__(kThreadsBig) void k_gemm_big(const GemmArgs g) {
-    // two buffers of two operand tiles; afterwards the staging area of the gradient epilogue
-    extern __shared__ __attribute__((aligned(16))) char s_dyn[];
-    __bf16* s_base = reinterpret_cast<__bf16*>(s_dyn);
-    auto s_p = [&](int b) { return s_base + (2 * b) * ELEMS; };
-    auto s_q = [&](int b) { return s_base + (2 * b + 1) * ELEMS; };
+    // Two buffers of two operand tiles; afterwards the staging areas of the epilogue.  Four separate arrays:
+    // that writes to one buffer and reads of the other cannot touch the same memory is then visible to
+    // the compiler, which may interleave them.
+    __shared__ __attribute__((aligned(16))) __bf16 s_p0[ELEMS];
+    __shared__ __attribute__((aligned(16))) __bf16 s_q0[ELEMS];
+    __shared__ __attribute__((aligned(16))) __bf16 s_p1[ELEMS];
+    __shared__ __attribute__((aligned(16))) __bf16 s_q1[ELEMS];
 
     const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -397,9 +423,9 @@ __global__ __launch_bounds__(kThreadsBig) void k_gemm_big(const GemmArgs g) {
     StageBig<Q_IC> sq;
     const __amdgpu_buffer_rsrc_t P = make_buffer(g.P, g.p_bytes);
     const __amdgpu_buffer_rsrc_t Q = make_buffer(g.Q, g.q_bytes);
-    auto request = [&](int t) {
-        sp.load(P, g.ldp, m0, (kt_begin + t) * TK, g.M, g.K);
-        sq.load(Q, g.ldq, n0, (kt_begin + t) * TK, g.Nn, g.K);
+    auto request = [&](int t) {       // tiles past the end load zeros: no branch around a request
+        sp.load(P, g.ldp, m0, (kt_begin + t) * TK, g.M, g.K, t < T);
+        sq.load(Q, g.ldq, n0, (kt_begin + t) * TK, g.Nn, g.K, t < T);
     };
     auto multiply = [&](const __bf16* tp, const __bf16* tq) {
 #pragma unroll
@@ -423,83 +449,81 @@ __global__ __launch_bounds__(kThreadsBig) void k_gemm_big(const GemmArgs g) {
         }
     };
 
+    // One straight-line block per tile: tile t+1 goes from the registers to the other buffer (last read
+    // before the barrier that ended the previous iteration), tile t+2 is requested, tile t is multiplied.
+    // The order below is only the data flow; the instructions are interleaved by the groups declared after
+    // it, so that the matrix cores run while LDS and memory instructions issue.
+    auto tile_block = [&](const __bf16* cur_p, const __bf16* cur_q, __bf16* nxt_p, __bf16* nxt_q, int t) {
+        sp.store(nxt_p);
+        sq.store(nxt_q);
+        request(t + 2);
+        multiply(cur_p, cur_q);
+        interleave<P_IC, Q_IC>();
+        __syncthreads();
+    };
     if (T > 0) {
         request(0);
-        sp.store(s_p(0));
-        sq.store(s_q(0));
-        if (T > 1) request(1);
+        sp.store(s_p0);
+        sq.store(s_q0);
+        request(1);
         __syncthreads();
-        for (int t = 0; t < T; ++t) {
-            const int cur = t & 1;
-            // buffer cur^1 was last read before the barrier that ended the previous iteration
-            if (t + 1 < T) {
-                sp.store(s_p(cur ^ 1));
-                sq.store(s_q(cur ^ 1));
-            }
-            if (t + 2 < T) request(t + 2);
-            __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the multiplications
-            multiply(s_p(cur), s_q(cur));
-            __syncthreads();
+        for (int t = 0; t < T; t += 2) {
+            tile_block(s_p0, s_q0, s_p1, s_q1, t);
+            if (t + 1 < T) tile_block(s_p1, s_q1, s_p0, s_q0, t + 1);
         }
     }
 
     // Accumulator element e of lane (r32, half) in tile (i, j) is
     // C[m0 + wm + 32 i + 8 (e/4) + 4 half + e%4][n0 + wn + 32 j + r32].
-    if constexpr (EPI == EPI_GRAD) {
-        // each wave turns its accumulators through a private LDS area (all operand reads are behind the
-        // last barrier) so that a lane stores 16 contiguous bytes and a wave 2 rows x 512 contiguous bytes
-        constexpr int LDE = 128 + 4;
-        float* stage = reinterpret_cast<float*>(s_dyn) + wave * 32 * LDE;
-        float* out = static_cast<float*>(g.out);
+    // Every epilogue turns the wave's accumulators through a private LDS area (all operand reads are behind
+    // the last barrier), so that a lane handles 4 consecutive columns and a wave 2 rows x 512 contiguous
+    // bytes per store instruction.  LDS operations of a wave complete in order: no barrier is needed.
+    constexpr int LDE = 128 + 4;
+    static_assert(2 * 32 * LDE * 4 <= ELEMS * 2, "two waves' staging areas fit one operand buffer");
+    __bf16* const area = wave < 2 ? s_p0 : (wave < 4 ? s_q0 : (wave < 6 ? s_p1 : s_q1));
+    float* stage = reinterpret_cast<float*>(area) + (wave & 1) * 32 * LDE;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 2; ++i) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    stage[(8 * (e >> 2) + 4 * half + (e & 3)) * LDE + j * 32 + r32] = acc[i][j][e];
+            for (int e = 0; e < 16; ++e)
+                stage[(8 * (e >> 2) + 4 * half + (e & 3)) * LDE + j * 32 + r32] = acc[i][j][e];
 #pragma unroll
-            for (int it = 0; it < 16; ++it) {
-                const int row = 2 * it + (lane >> 5), c4 = (lane & 31) * 4;
-                const v4f v = *reinterpret_cast<const v4f*>(&stage[row * LDE + c4]);
-                const int m = m0 + wm + i * 32 + row, n = n0 + wn + c4;
-                if (m < g.M && n < g.Nn) store_global_nt_v4f(out + (size_t)m * g.Nn + n, v);
-            }
-        }
-        return;
-    }
+        for (int it = 0; it < 16; ++it) {
+            const int row = 2 * it + (lane >> 5), c4 = (lane & 31) * 4;
+            const v4f v = *reinterpret_cast<const v4f*>(&stage[row * LDE + c4]);
+            const int m = m0 + wm + i * 32 + row, n = n0 + wn + c4;
+            if (m >= g.M || n >= g.Nn) continue;              // Nn is a multiple of 4
+            const size_t o = (size_t)m * g.Nn + n;
+            if constexpr (EPI == EPI_GRAD) {
+                store_global_nt_v4f(static_cast<float*>(g.out) + o, v);
+            } else if constexpr (EPI == EPI_RAW) {
+                *reinterpret_cast<v4f*>(g.raw + (size_t)blockIdx.z * g.M * g.Nn + o) = v;
+            } else if constexpr (EPI == EPI_SIGMOID) {
+                const v4f bs = *reinterpret_cast<const v4f*>(g.bias + n);
+                const v4bf a = {(__bf16)sigmoidf(v.x + bs.x), (__bf16)sigmoidf(v.y + bs.y),
+                                (__bf16)sigmoidf(v.z + bs.z), (__bf16)sigmoidf(v.w + bs.w)};
+                *reinterpret_cast<v4bf*>(static_cast<__bf16*>(g.out) + o) = a;
+            } else {
+                const v4bf ab = *reinterpret_cast<const v4bf*>(static_cast<const __bf16*>(g.act) + o);
+                v4f d;
+                v4bf db;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n = n0 + wn + j * 32 + r32;
-            if (n >= g.Nn) continue;
-            float bias = 0.0f;
-            if constexpr (EPI == EPI_SIGMOID) bias = g.bias[n];
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wm + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-                if (m >= g.M) continue;
-                const size_t o = (size_t)m * g.Nn + n;
-                const float v = acc[i][j][e];
-                if constexpr (EPI == EPI_RAW) {
-                    g.raw[(size_t)blockIdx.z * g.M * g.Nn + o] = v;
-                } else if constexpr (EPI == EPI_SIGMOID) {
-                    static_cast<__bf16*>(g.out)[o] = (__bf16)sigmoidf(v + bias);
-                } else if constexpr (EPI == EPI_SIGMA_PRIME) {
-                    const float a = (float)static_cast<const __bf16*>(g.act)[o];
-                    const float d = v * (a * (1.0f - a));
-                    static_cast<float*>(g.out)[o] = d;
-                    static_cast<__bf16*>(g.out_bf)[o] = (__bf16)d;
+                for (int c = 0; c < 4; ++c) {
+                    const float a = (float)ab[c];
+                    d[c] = v[c] * (a * (1.0f - a));
+                    db[c] = (__bf16)d[c];
                 }
+                *reinterpret_cast<v4f*>(static_cast<float*>(g.out) + o) = d;
+                *reinterpret_cast<v4bf*>(static_cast<__bf16*>(g.out_bf) + o) = db;
             }
         }
+    }
 }
 
 static_assert(TK == Tile<__bf16>::BK, "both bf16 kernels count k-tiles of the same length");
-constexpr int kLdsBytes = 2 * 2 * ELEMS * 2;     // two buffers x two operands x bf16
-static_assert(kLdsBytes >= 8 * 32 * (128 + 4) * 4, "the gradient epilogue's staging area fits");
-static_assert(kLdsBytes <= 160 * 1024, "LDS of one compute unit");
+static_assert(2 * 2 * ELEMS * 2 <= 160 * 1024, "LDS of one compute unit");
 }  // namespace big
 
 // Split-K second stage: sum the raw partials in split order, then the layer's epilogue.
@@ -531,8 +555,18 @@ __global__ __launch_bounds__(kThreads) void k_bias_grad(const float* __restrict_
     const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
     const int j = blockIdx.x * 32 + c;
     float s = 0.0f;
-    if (j < N)
-        for (int b = rg; b < B; b += 8) s += D[(size_t)b * N + j];
+    if (j < N) {
+        // eight rows requested at a time, added in ascending order
+        int b = rg;
+        for (; b + 56 < B; b += 64) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = D[(size_t)(b + 8 * u) * N + j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; b < B; b += 8) s += D[(size_t)b * N + j];
+    }
     s_part[rg][c] = s;
     __syncthreads();
     if (rg == 0 && j < N) {
@@ -563,15 +597,8 @@ hipError_t run_big(GemmArgs g, int splits, hipStream_t s) {
     if (pb >= 0xFFFFFFF0ull || qb >= 0xFFFFFFF0ull) return hipErrorInvalidValue;
     g.p_bytes = (unsigned)pb;
     g.q_bytes = (unsigned)qb;
-    static bool attr_set = false;     // more than 64 KB of dynamic LDS has to be asked for once
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&big::k_gemm_big<P_IC, Q_IC, EPI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, big::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const dim3 grid(ceil_div(g.Nn, big::TN), ceil_div(g.M, big::TM), splits);
-    big::k_gemm_big<P_IC, Q_IC, EPI><<<grid, big::kThreadsBig, big::kLdsBytes, s>>>(g);
+    big::k_gemm_big<P_IC, Q_IC, EPI><<<grid, big::kThreadsBig, 0, s>>>(g);
     return hipGetLastError();
 }
 
