@@ -208,6 +208,27 @@ def test_persistent_row_split_strips_match_oracle(monkeypatch, L, N, k, split):
     _free(g)
 
 
+@pytest.mark.parametrize("stride,nap", [("1024", "0"), ("256", "3")])
+def test_persistent_exchange_layout_and_pause_knobs(monkeypatch, stride, nap):
+    """The tuning knobs that change where the exchanged words lie and when they are first polled change
+    no result: spread words (groups of eight, `stride` bytes apart) and another pause give the same bits."""
+    import paper_1801_04928_amd as P
+    import torch
+    net = make_net(6, 1000, 1, seed=77)
+    ref = run_gpu(net, 3, sched=P.LF_SCHED_PERSISTENT)
+    want = [to_np(t).copy() for t in ref.nabla_w] + [to_np(t).copy() for t in ref.nabla_b]
+    _free(ref)
+    monkeypatch.setenv("LF_PERSISTENT_LL_STRIDE", stride)
+    monkeypatch.setenv("LF_PERSISTENT_NAP_FWD", nap)
+    monkeypatch.setenv("LF_PERSISTENT_NAP_BWD", nap)
+    g = run_gpu(net, 3, sched=P.LF_SCHED_PERSISTENT)
+    check_against_oracle(net, g)
+    got = [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]
+    for a, b in zip(want, got):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    _free(g)
+
+
 def test_persistent_wait_that_gives_up_is_reported(monkeypatch):
     """Failure handling of the persistent path, forced from the host: with a spin limit of one poll the
     first wait that does not find its data at once gives up.  Every kernel still exits normally; the next
