@@ -37,6 +37,7 @@ struct Layout {
     size_t pll_off, pll_words;           // [L-1][N][kMaxRowSplit]
     size_t tab_off, tab_bytes;       // w, b, nabla_w, nabla_b pointer tables, L-1 entries each
     size_t abort_off;
+    size_t counts_off;               // per-workgroup launch counts: 3 x kMaxLaunchGroups words
     size_t total;
 };
 
@@ -85,6 +86,7 @@ Layout make_layout(int L, int N, int B, lf_dtype dt) {
         y.pll_off = off; off += align_up(y.pll_words * 8);
         y.tab_off = off; y.tab_bytes = 4 * M * sizeof(void*);         off += align_up(y.tab_bytes);
         y.abort_off = off; off += kAlign;
+        y.counts_off = off; off += align_up(3 * lf::kMaxLaunchGroups * sizeof(unsigned));
     }
     y.total = off;
     return y;
@@ -115,7 +117,6 @@ struct lf_net {
     // persistent path
     bool p_ready, p_tables_dirty;
     int p_groups, p_rpg, p_bgroups, p_tpr, p_rs, p_workers, p_nap_fwd, p_nap_bwd;
-    unsigned p_epoch;
     unsigned p_spin_limit;             // polls before a bounded wait gives up
     int* p_abort_host;                 // pinned, mapped; the kernels raise it when a wait gives up
     int* p_abort_dev_view;             // the same word as the device addresses it
@@ -246,7 +247,9 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.all_off, net->lay.ll_words, 0ull, s));
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.pll_off, net->lay.pll_words, 0ull, s));
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.abort_off, kAlign / 8, 0ull, s));
-        net->p_epoch = 0;
+        // every workgroup's launch count starts at 1
+        LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.counts_off, 3 * lf::kMaxLaunchGroups / 2,
+                                        0x0000000100000001ull, s));
         net->p_ready = true;
     }
     if (net->p_tables_dirty) {
@@ -275,8 +278,10 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     A.GB = net->p_bgroups; A.TPR = net->p_tpr; A.RS = net->p_rs;
     A.GW = net->p_workers;
     A.k = k < net->p_workers ? k : net->p_workers;   // never more partitions than worker workgroups
-    if (++net->p_epoch >= (1u << 19)) net->p_epoch = 1;    // tags carry 19 epoch bits + 13 layer bits
-    A.epoch = net->p_epoch;
+    A.epoch = 0;                                            // set by the kernel
+    A.counts_fwd = reinterpret_cast<unsigned*>(net->ws + net->lay.counts_off);
+    A.counts_bwd1 = A.counts_fwd + lf::kMaxLaunchGroups;
+    A.counts_bwdk = A.counts_bwd1 + lf::kMaxLaunchGroups;
     A.cost_scale = net->cost_scale;
     A.spin_limit = net->p_spin_limit;
     void** tab = reinterpret_cast<void**>(net->ws + net->lay.tab_off);
@@ -343,7 +348,7 @@ lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost
     net->x1 = nullptr;
     net->have_params = net->have_grads = net->fwd_done = net->bwd_done = false;
     net->gemm_big = lf::gemm_use_big(N, B, dt == LF_BF16);
-    net->p_ready = false; net->p_tables_dirty = true; net->p_groups = net->p_rpg = net->p_bgroups = net->p_tpr = 0; net->p_workers = 0; net->p_epoch = 0;
+    net->p_ready = false; net->p_tables_dirty = true; net->p_groups = net->p_rpg = net->p_bgroups = net->p_tpr = 0; net->p_workers = 0;
     net->p_abort_host = nullptr; net->p_abort_dev_view = nullptr;
     net->err = "no error";
     try {

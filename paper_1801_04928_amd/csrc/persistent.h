@@ -10,6 +10,7 @@ constexpr int kMaxRowsPerGroup = 256;    // rows one forward workgroup may own
 constexpr int kMaxPersistentN = 4096;    // wider nets take the stream schedule
 constexpr int kMaxPersistentDepth = 1025; // deeper nets too (the per-layer pointer tables live in LDS)
 constexpr int kMaxRowSplit = 4;          // row blocks a backward column strip may be split into
+constexpr int kMaxLaunchGroups = 1024;   // workgroups of one launch (chain + gradient workers)
 
 struct PersistArgs {
     int L, N;
@@ -17,7 +18,11 @@ struct PersistArgs {
     int GB, TPR;                         // backward chain: workgroups, float4 column groups per strip
     int RS;                              // backward chain: row blocks per strip (1 = a strip is one workgroup's)
     int GW, k;                           // gradient worker workgroups (k >= 2), worker partitions
-    unsigned epoch;                      // tag of this launch's words (never 0)
+    unsigned epoch;                      // tag of this launch's words (never 0): filled in by the kernel from its
+                                         // workgroup's launch count (see launch_count)
+    unsigned* counts_fwd;                // per-workgroup launch counts, kMaxLaunchGroups words each, all starting
+    unsigned* counts_bwd1;               // at 1: forward grid, backward grid with k = 1, backward grid with
+    unsigned* counts_bwdk;               // k >= 2
     float cost_scale;                    // power of two multiplied into delta^L (see lf_set_cost_scale)
     unsigned spin_limit;                 // polls after which a wait gives up and raises the abort word
     int nap;                             // pause before the first poll of an exchange, in units of 256 cycles

@@ -130,6 +130,21 @@ __device__ __forceinline__ bool ll_gather4x4(const u64* const p[4], const int n[
 __device__ __forceinline__ void nap(int units) {
     for (int i = 0; i < units; ++i) __builtin_amdgcn_s_sleep(4);
 }
+// The tag of a launch's words lives in device memory, not in the kernel's arguments: a launch recorded in a
+// HIP graph is replayed with the same arguments, and a replay whose words carried the tags of the launch
+// before it would take that launch's leftovers for fresh data.  Every workgroup keeps a launch count of
+// its own (so nothing is shared and nobody waits): it reads the count when it starts and stores count + 1
+// right away.  All workgroups of a grid are launched equally often, so their counts agree; the end of the
+// kernel orders the store before the next launch.  (The value stays in a vector register: making it
+// scalar here would put the wait for the load in front of everything the kernel can do before it first
+// needs a tag.)
+__device__ __forceinline__ unsigned launch_count(unsigned* counts) {
+    unsigned* mine = counts + blockIdx.x;
+    const unsigned c = __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) __hip_atomic_store(mine, c + 1u ? c + 1u : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return c;
+}
+
 // Word that holds element i of an exchanged vector.  Groups of eight words (64 bytes) are spread
 // 8 << ll_shift bytes apart, so that the polls for one vector go to many memory channels instead of the
 // one or two a packed vector would occupy.  Four consecutive elements starting at a multiple of four
@@ -151,7 +166,7 @@ __device__ __forceinline__ const float* act_ptr(const PersistArgs& A, int l) {
 // SINGLE: the wave's rows of a layer are one chunk (the latency-bound small nets); otherwise an even
 // number of chunks per layer.
 template <int Q, int RF, bool SINGLE>
-__global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArgs A) {
+__device__ __forceinline__ void forward_pass(const PersistArgs& A) {
     __shared__ v4f s_a[Q * 64];
     __shared__ float s_bias[kMaxRowsPerGroup];
     __shared__ const float* s_w[kTableLds];      // w^l and b^l pointers: a table entry fetched from
@@ -400,7 +415,7 @@ __device__ __forceinline__ float strip_column_sum(const v4f (&red)[kWaves * 4][T
 // and each of the RS workgroups finishes 1/RS of the strip's columns, adding the partials in row-block
 // order.
 template <int TPR, int CH, bool SINGLE, bool SPLIT>
-__global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArgs A) {
+__device__ __forceinline__ void backward_pass(const PersistArgs& A) {
     constexpr int CPG = 4 * TPR;              // columns per chain workgroup
     constexpr int RPP = kThreads / TPR;       // rows covered by one load of the whole workgroup
     __shared__ v4f s_delta4[kMaxPersistentN / 4];       // delta^{l+1}, all of it
@@ -622,6 +637,23 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArg
     if (k == 1) inline_grads(2);
 }
 
+template <int Q, int RF, bool SINGLE>
+__global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArgs args) {
+    PersistArgs A = args;
+    A.epoch = launch_count(args.counts_fwd);
+    forward_pass<Q, RF, SINGLE>(A);
+}
+// The backward kernel runs with two grids: chain workgroups only (k = 1), or chain + gradient workers.  Each
+// grid has its own counts; odd tags belong to the first, even tags to the second, so the words of one can
+// never pass for the other's.
+template <int TPR, int CH, bool SINGLE, bool SPLIT>
+__global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArgs args) {
+    PersistArgs A = args;
+    if (args.k == 1) A.epoch = 2u * launch_count(args.counts_bwd1) + 1u;
+    else A.epoch = 2u * launch_count(args.counts_bwdk);
+    backward_pass<TPR, CH, SINGLE, SPLIT>(A);
+}
+
 __global__ __launch_bounds__(kThreads) void k_fill_u64(u64* p, size_t n, u64 v) {
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads)
         p[i] = v;
@@ -681,7 +713,7 @@ hipError_t launch_fill_u64(void* p, size_t n_words, unsigned long long v, hipStr
 }
 
 hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s) {
-    if (!persistent_supported(A.L, A.N)) return hipErrorInvalidValue;
+    if (!persistent_supported(A.L, A.N) || A.G > kMaxLaunchGroups) return hipErrorInvalidValue;
     const int q = (A.N / 4 + 63) / 64;                       // float4 groups per lane and row
     const int rw = (A.RPG + kWaves - 1) / kWaves;            // rows per wave
     if (q <= 4) {
@@ -717,6 +749,7 @@ hipError_t launch_bwd_persistent(const PersistArgs& A, hipStream_t s) {
     if (A.RS != 1 && A.RS != 2 && A.RS != 4) return hipErrorInvalidValue;
     if (A.GB % A.RS != 0 || (4 * A.TPR) % A.RS != 0) return hipErrorInvalidValue;
     const int grid = A.GB + (A.k > 1 ? A.GW : 0);    // chain workgroups, then the gradient workers
+    if (grid > kMaxLaunchGroups) return hipErrorInvalidValue;
     switch (A.TPR) {
         case 1: return launch_bwd_tpr<1>(A, grid, s);
         case 2: return launch_bwd_tpr<2>(A, grid, s);

@@ -229,6 +229,41 @@ def test_persistent_exchange_layout_and_pause_knobs(monkeypatch, stride, nap):
     _free(g)
 
 
+def test_persistent_pass_replays_from_a_hip_graph():
+    """A forward + backward pass recorded in a HIP graph and replayed: every replay (with eager passes of the
+    same handle and synchronisations in between) must give the bits of the eager pass.  The launches carry
+    no per-launch argument -- the tag of the exchanged words is kept in device memory -- so a replay cannot
+    mistake the words of the launch before it for its own."""
+    import paper_1801_04928_amd as P
+    import torch
+    net = make_net(9, 516, 1, seed=21)
+    g = P.LeapfrogNet(9, 516, 1, "f32")
+    g.load(net)
+    g.set_schedule(P.LF_SCHED_PERSISTENT)
+    g.forward()
+    g.backward(3)
+    torch.cuda.synchronize()
+    check_against_oracle(net, g)
+    want = [to_np(t).copy() for t in g.nabla_w] + [to_np(t).copy() for t in g.nabla_b]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g.forward()
+        g.backward(3)
+    for replay in range(4):
+        for t in g.nabla_w + g.nabla_b:
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]
+        for a, b in zip(want, got):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), f"replay {replay} differs"
+        # eager work of the same handle between the replays
+        g.forward()
+        g.backward(1 + replay % 2)
+        torch.cuda.synchronize()
+    _free(g)
+
+
 def test_persistent_wait_that_gives_up_is_reported(monkeypatch):
     """Failure handling of the persistent path, forced from the host: with a spin limit of one poll the
     first wait that does not find its data at once gives up.  Every kernel still exits normally; the next
