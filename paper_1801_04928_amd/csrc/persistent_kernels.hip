@@ -141,7 +141,8 @@ __device__ __forceinline__ void nap(int units) {
 __device__ __forceinline__ unsigned launch_count(unsigned* counts) {
     unsigned* mine = counts + blockIdx.x;
     const unsigned c = __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (threadIdx.x == 0) __hip_atomic_store(mine, c + 1u ? c + 1u : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned next = c + 1u;
+    if (threadIdx.x == 0) __hip_atomic_store(mine, next != 0u ? next : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return c;
 }
 
