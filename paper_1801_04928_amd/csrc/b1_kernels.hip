@@ -17,7 +17,7 @@ __host__ __device__ constexpr int ceil_div(int a, int b) { return (a + b - 1) / 
 // eqs. (z),(a):  a_out[j] = sigma( sum_k W[j][k] a_in[k] + b[j] )
 // One wave owns R consecutive rows.  a_in is staged once per workgroup in LDS; a lane walks the row
 // in float4 steps of stride 64 lanes, keeps one accumulator per row, and the 64 lane sums are
-// combined with a fixed butterfly.
+// combined in a fixed order (row rotations, then the four rows of 16 lanes).
 template <int R>
 __global__ __launch_bounds__(kThreads) void k_fwd_gemv(const float* __restrict__ W,
                                                        const float* __restrict__ bias,

@@ -7,16 +7,18 @@
 //
 // Exchange format ("tagged words"): a 64-bit word = (fp32 value, 32-bit tag), written and read with
 // relaxed agent-scope 64-bit atomics.  Value and tag arrive together, so a reader that sees the tag it
-// expects has the value: no fence, no separate flag.  The tag is the pass's epoch, so buffers are never
-// cleared between passes.  The words of delta^l are also the per-layer ready flags that feed the k
+// expects has the value: no fence, no separate flag.  The tag is the launch's epoch (a per-workgroup launch
+// count kept in device memory), so buffers are never cleared between passes.  The words of delta^l are also the per-layer ready flags that feed the k
 // workers of section 3.
 //
 //   forward  (z),(a): workgroup g owns a block of rows of w^l, hence of a^l.  It gathers all of a^{l-1}
 //                     (tagged words published by the owners), forms its a^l entries, publishes them.
 //   backward (bp2):   workgroup g owns a block of COLUMNS of w^{l+1}, hence of delta^l: it reads its
-//                     64-byte-wide strip of every row, so each column sum is formed inside one
+//                     strip (16 to 128 bytes wide) of every row, so each column sum is formed inside one
 //                     workgroup (fixed order) and the exchange is again an all-gather, of delta^l.
 //                     Strips of workgroups that share an L2 (equal g mod 8) are adjacent in memory.
+//                     Wide layers: 256-byte strips shared by four workgroups, each taking a block of
+//                     rows; their partial sums are exchanged first, then delta^l.
 //   (bp3),(bp4):      layer l belongs to worker (L-l) mod k.  With k >= 2 the workers are separate
 //                     workgroups of the same kernel (partition j = those with index mod k == j); they
 //                     split the rows of nabla_w^l, wait for delta^l through its tagged words and stream
@@ -406,10 +408,10 @@ __device__ __forceinline__ float strip_column_sum(const v4f (&red)[kWaves * 4][T
 
 // Workgroups [0, GB) run the delta chain; workgroups [GB, gridDim.x) are the gradient workers
 // (present when k >= 2).  TPR = threads per 16*TPR-byte row segment of the owned column strip;
-// CH = float4 loads per fetched chunk (the chunk after the one in use is always in flight, also
-// across the exchange).  At most 256 registers per thread, so that a chain and a gradient workgroup
-// fit one compute unit.
-// SINGLE: the strip of a step is one chunk; otherwise an even number of chunks per step.
+// CH = float4 loads per fetched chunk (chunks after the one in use are always in flight, also across
+// the exchange).  At most 256 registers per thread, so that a chain and a gradient workgroup fit one
+// compute unit.
+// SINGLE: the strip of a step is one chunk; otherwise a multiple of four chunks per step.
 // SPLIT: a strip is shared by RS workgroups, each taking a block of rows.  A strip is then a whole
 // number of 128-byte lines also for wide layers (half-line strips stream at about two thirds of the
 // rate); the price is one more exchange per step: the row blocks' partial sums go out as tagged words
