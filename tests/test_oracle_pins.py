@@ -117,6 +117,36 @@ def test_hand_computed_one_neuron():
     assert C == 0.125
 
 
+def test_exact_small_cases_from_golden_file():
+    """tests/golden/exact_small_cases.txt: values derived by hand from eqs. (z),(a),(bp1)-(bp4) for nets
+    with all-zero parameters (every activation exactly 1/2, every sigma' exactly 1/4)."""
+    import os
+    want = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "exact_small_cases.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            case, name, *vals = line.split()
+            want[(case, name)] = np.array([float(v) for v in vals])
+    z1 = {2: np.zeros((1, 1))}
+    a, delta, nb, nw, C = O.full_pass(z1, {2: np.zeros(1)}, [[0.8]], [[0.0]], 2)
+    got = {("one_neuron", "a2"): a[2], ("one_neuron", "delta2"): delta[2], ("one_neuron", "nabla_b2"): nb[2],
+           ("one_neuron", "nabla_w2"): nw[2], ("one_neuron", "C"): C}
+    w = {2: np.zeros((2, 2)), 3: np.zeros((2, 2))}
+    b = {2: np.zeros(2), 3: np.zeros(2)}
+    a, delta, nb, nw, C = O.full_pass(w, b, [[1.0, 0.5]], [[0.0, 1.0]], 3)
+    got.update({("two_by_two", "delta3"): delta[3], ("two_by_two", "delta2"): delta[2],
+                ("two_by_two", "nabla_w3"): nw[3], ("two_by_two", "nabla_b3"): nb[3],
+                ("two_by_two", "nabla_w2"): nw[2], ("two_by_two", "C"): C})
+    a, delta, nb, nw, C = O.full_pass(z1, {2: np.zeros(1)}, [[0.8], [0.4]], [[0.0], [1.0]], 2)
+    got.update({("two_samples", "nabla_b2"): nb[2], ("two_samples", "nabla_w2"): nw[2], ("two_samples", "C"): C})
+    assert set(got) == set(want)
+    for key, v in want.items():
+        g = np.asarray(got[key], dtype=np.float64).reshape(-1)
+        assert g.shape == v.shape, key
+        assert np.allclose(g, v, rtol=0, atol=1e-16), (key, g, v)
+
+
 def test_hand_computed_two_layers_scalar():
     """L=3, N=1, scalar chain written out with math.exp only."""
     w2, w3, b2, b3, x, y = 0.7, -1.3, 0.2, 0.4, 0.9, 0.25
