@@ -21,17 +21,23 @@ HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 
 
+def matrix_sizes(spec):
+    """Entries of w^l, l = 2..L: n_l * n_{l-1} (N^2 when every layer has N neurons)."""
+    return [spec.width(l) * spec.width(l - 1) for l in range(2, spec.L + 1)]
+
+
 def algorithmic_work(spec):
-    """Per backward pass.  B = 1: bytes the method must move, 4 N^2 per matrix read or written:
-    M-1 chain reads of w^{l+1} plus M writes of nabla_w^l (vectors are O(N), ignored).
-    Minibatch: 2 N^2 B flops for each of the M-1 chain and M gradient contractions."""
-    M = spec.L - 1
+    """Per backward pass.  B = 1: bytes the method must move, 4 bytes per entry of a matrix read or written:
+    the chain reads w^{l+1} for l = L-1..2, the workers write nabla_w^l for l = 2..L (vectors are O(N),
+    ignored).  Minibatch: 2 B flops per matrix entry for each chain and each gradient contraction."""
+    sizes = matrix_sizes(spec)
+    every, chain = sum(sizes), sum(sizes[1:])        # the chain never reads w^2
     if spec.B == 1:
         es = 4 if spec.dtype == "f32" else 2
-        return {"bound": "hbm", "bwd": (es * (M - 1) + 4 * M) * spec.N * spec.N,
-                "fwd": es * M * spec.N * spec.N, "unit": "GB/s", "peak": HBM_PEAK_GBS, "scale": 1e9}
-    f = 2.0 * spec.N * spec.N * spec.B
-    return {"bound": "mfma", "bwd": f * (2 * M - 1), "fwd": f * M, "unit": "TFLOP/s",
+        return {"bound": "hbm", "bwd": es * chain + 4 * every,
+                "fwd": es * every, "unit": "GB/s", "peak": HBM_PEAK_GBS, "scale": 1e9}
+    f = 2.0 * spec.B
+    return {"bound": "mfma", "bwd": f * (chain + every), "fwd": f * every, "unit": "TFLOP/s",
             "peak": MFMA_PEAK_TFLOPS[spec.dtype], "scale": 1e12}
 
 
@@ -67,8 +73,8 @@ def cpu_baseline(net, gpu_net=None, budget_s=12.0):
         cores = os.cpu_count() or 1
     s = net.spec
     M = s.L - 1
-    flops_pass = 6.0 * s.N * s.N * s.B * M
-    if flops_pass < 5e10:
+    flops_pass = 6.0 * s.B * sum(matrix_sizes(s))
+    if flops_pass < 5e10 or s.widths:
         w = {l: net.w(l) for l in range(2, s.L + 1)}
         b = {l: net.b(l) for l in range(2, s.L + 1)}
         x, y = net.x(), net.y()
@@ -113,6 +119,10 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--widths", default="",
+                    help="instead of --config: neurons of layers 1..L, comma-separated (with --batch, --dtype)")
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--k", type=int, default=0, help="workers (0 = the configuration's largest k)")
     ap.add_argument("--sched", default="auto", choices=["auto", "streams", "persistent"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -127,19 +137,28 @@ def main():
 
     import torch
     import paper_1801_04928_amd as P
-    from lf_inputs import config_net
+    from lf_inputs import config_net, make_net
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    net = config_net(args.config, cache=args.config in ("cfg1", "cfg2"))
-    s = net.spec
-    k = args.k or max(s.ks)
-    steps = args.steps if args.config in ("cfg1", "cfg2") else min(args.steps, 20)
-    warmup = args.warmup if args.config in ("cfg1", "cfg2") else min(args.warmup, 3)
+    if args.widths:
+        widths = [int(v) for v in args.widths.split(",")]
+        net = make_net(len(widths), widths, args.batch, dtype=args.dtype, seed=0, cache=True,
+                       name="widths " + "-".join(str(v) for v in widths))
+        s = net.spec
+        k = args.k or min(8, s.L - 1)
+        small = 6.0 * s.B * sum(matrix_sizes(s)) < 1e10
+    else:
+        net = config_net(args.config, cache=args.config in ("cfg1", "cfg2"))
+        s = net.spec
+        k = args.k or max(s.ks)
+        small = args.config in ("cfg1", "cfg2")
+    steps = args.steps if small else min(args.steps, 20)
+    warmup = args.warmup if small else min(args.warmup, 3)
 
-    g = P.LeapfrogNet(s.L, s.N, s.B, s.dtype)
+    g = P.LeapfrogNet(s.L, list(s.widths) if s.widths else s.N, s.B, s.dtype)
     g.load(net)
     g.set_schedule({"auto": P.LF_SCHED_AUTO, "streams": P.LF_SCHED_STREAMS,
                     "persistent": P.LF_SCHED_PERSISTENT}[args.sched])
@@ -207,7 +226,7 @@ def main():
             achievable = {"value": 2.0 * 8192 ** 3 / (best * 1e-3) / 1e12, "unit": "TFLOP/s",
                           "what": f"torch.matmul 8192^3 {s.dtype} (vendor library), best of 5"}
             del a_, b_, c_
-    persistent = s.B == 1 and s.dtype == "f32" and s.N <= 4096 and args.sched != "streams"
+    persistent = s.B == 1 and s.dtype == "f32" and s.N <= 4096 and args.sched != "streams" and not s.widths
     kernel = "k_bwd_persistent (one launch = the whole backward pass)" if persistent else \
         "backward pass (bp1)-(bp4), all kernels"
     out = {
@@ -230,7 +249,7 @@ def main():
         "bwd_ms_median": bwd_list[len(bwd_list) // 2],
         "bwd_ms_min": bwd_list[0],
         "bwd_passes_per_s": 1e3 / bwd_ms,
-        "weights_cache_warm": bool(4 * (s.L - 1) * s.N * s.N * (1 if s.dtype == "f32" else 0.5) < 256e6),
+        "weights_cache_warm": bool(4 * sum(matrix_sizes(s)) * (1 if s.dtype == "f32" else 0.5) < 256e6),
         "roofline": {"bound": work["bound"], "kernel": kernel, "achieved": achieved,
                      "peak": work["peak"], "unit": work["unit"], "frac": achieved / work["peak"],
                      "traffic": measured_traffic(s.name, k) if persistent else None,

@@ -36,6 +36,11 @@
  *     thread-safe; different handles are independent.
  *   - Shape limits: N a multiple of 4 (fp32) or 8 (bf16) so rows stay 16-byte
  *     aligned; 2 <= L <= 4096; 1 <= B; 1 <= k <= L-1.
+ *   - Layers of different widths (lf_create_widths): section 2 fixes N neurons per
+ *     layer only for its cost analysis and notes that the equations hold in general.
+ *     With n_l neurons in layer l, w^l and nabla_w^l are n_l x n_{l-1} (row-major,
+ *     row stride n_{l-1}), b^l, nabla_b^l, a^l, delta^l have n_l entries per sample,
+ *     x^1 is [B][n_1] and y is [B][n_L].  Every n_l obeys the limit on N above.
  */
 #ifndef LF_H
 #define LF_H
@@ -82,8 +87,17 @@ size_t lf_workspace_bytes(int L, int N, int B, lf_dtype dt);
 lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost,
                     void* workspace, size_t workspace_bytes);
 
+/* The same two calls for a net whose layers differ in width (section 2: the equations are valid for any
+ * widths).  n: HOST array of L entries, n[l-1] = neurons of layer l, read during the call only.  Such a
+ * net runs the stream schedule (the persistent kernels need equal widths: LF_SCHED_PERSISTENT is then
+ * LF_EUNSUPPORTED, LF_SCHED_AUTO picks streams).  With all n[l-1] equal this is lf_create. */
+size_t lf_workspace_bytes_widths(int L, const int* n, int B, lf_dtype dt);
+lf_status lf_create_widths(lf_net** out, int L, const int* n, int B, lf_dtype dt, lf_cost cost,
+                           void* workspace, size_t workspace_bytes);
+
 /* Register w^l and b^l, l = 2..L (section 2).  w[i]: N*N elements of type dt;
- * b[i]: N floats.  The pointers are kept; the data may change between passes. */
+ * b[i]: N floats (n_l x n_{l-1} and n_l for layer l = i+2 of a net made by lf_create_widths).  The pointers
+ * are kept; the data may change between passes. */
 lf_status lf_set_params(lf_net* net, const void* const* w, const void* const* b);
 
 /* Register where nabla_w^l (N*N floats) and nabla_b^l (N floats) are written,

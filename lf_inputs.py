@@ -10,9 +10,10 @@ Notation follows the paper (section 2): layers are numbered 1..L, a^1 = x^1,
 weights and biases exist for l = 2..L, every layer has N neurons, and
 w^l is N x N with w^l[j][k] the weight from neuron k of layer l-1 into
 neuron j of layer l.  A minibatch of B samples is stored sample-major:
-x[b][n].
+x[b][n].  A spec may instead give every layer its own width n_l (the
+paper's equations hold for any widths); w^l is then n_l x n_{l-1}.
 
-Distributions: w^l ~ N(0, var=1/N), b^l ~ N(0, var=b_var), x, y ~ U[0,1).
+Distributions: w^l ~ N(0, var=1/n_{l-1}), b^l ~ N(0, var=b_var), x, y ~ U[0,1).
 The second argument of N(.,.) is read as a variance throughout.
 
 Every tensor has its own random stream, keyed by
@@ -49,6 +50,11 @@ class NetSpec:
     ks: Tuple[int, ...]   # worker counts k the configuration is run with
     b_var: float      # variance of the bias init
     seed: int = 0
+    widths: Tuple[int, ...] = ()   # neurons of layers 1..L when they differ; empty = N everywhere
+
+    def width(self, l: int) -> int:
+        """Neurons of layer l, l = 1..L."""
+        return self.widths[l - 1] if self.widths else self.N
 
 
 # The five benchmark configurations.
@@ -71,6 +77,8 @@ class SyntheticNet:
             raise ValueError("need L >= 2, N >= 1, B >= 1")
         if spec.dtype not in ("f32", "bf16"):
             raise ValueError("dtype must be 'f32' or 'bf16'")
+        if spec.widths and (len(spec.widths) != spec.L or min(spec.widths) < 1):
+            raise ValueError("widths needs one positive entry per layer")
         self.spec = spec
         self._cache = {} if cache else None
 
@@ -93,11 +101,11 @@ class SyntheticNet:
 
     def w(self, l: int) -> np.ndarray:
         self._check_layer(l)
-        N = self.spec.N
+        rows, cols = self.spec.width(l), self.spec.width(l - 1)
 
         def make():
-            g = self._rng(_KIND_W, l).standard_normal((N, N), dtype=np.float32)
-            g *= np.float32(1.0 / np.sqrt(N))
+            g = self._rng(_KIND_W, l).standard_normal((rows, cols), dtype=np.float32)
+            g *= np.float32(1.0 / np.sqrt(cols))
             return self._store(g)
         return self._memo(("w", l), make)
 
@@ -105,7 +113,7 @@ class SyntheticNet:
         self._check_layer(l)
 
         def make():
-            g = self._rng(_KIND_B, l).standard_normal(self.spec.N, dtype=np.float32)
+            g = self._rng(_KIND_B, l).standard_normal(self.spec.width(l), dtype=np.float32)
             g *= np.float32(np.sqrt(self.spec.b_var))
             return g
         return self._memo(("b", l), make)
@@ -113,12 +121,12 @@ class SyntheticNet:
     def x(self) -> np.ndarray:
         s = self.spec
         return self._memo(("x", 0), lambda: self._store(
-            self._rng(_KIND_X, 0).random((s.B, s.N), dtype=np.float32)))
+            self._rng(_KIND_X, 0).random((s.B, s.width(1)), dtype=np.float32)))
 
     def y(self) -> np.ndarray:
         s = self.spec
         return self._memo(("y", 0), lambda: self._store(
-            self._rng(_KIND_Y, 0).random((s.B, s.N), dtype=np.float32)))
+            self._rng(_KIND_Y, 0).random((s.B, s.width(s.L)), dtype=np.float32)))
 
     # Views indexable by the paper's layer index, for code that wants w[l], b[l].
     class _ByLayer:
@@ -140,10 +148,14 @@ class SyntheticNet:
         return SyntheticNet._ByLayer(self.b, self.spec.L)
 
 
-def make_net(L: int, N: int, B: int = 1, dtype: str = "f32", b_var: float = 0.1,
+def make_net(L: int, N, B: int = 1, dtype: str = "f32", b_var: float = 0.1,
              seed: int = 0, cache: bool = True, name: str = "custom") -> SyntheticNet:
-    """A net of arbitrary shape with the configurations' init recipe."""
-    return SyntheticNet(NetSpec(name, L, N, B, dtype, (1,), b_var, seed), cache=cache)
+    """A net of arbitrary shape with the configurations' init recipe.  N: the neurons of every layer, or a
+    sequence of L widths (layer 1 first)."""
+    if isinstance(N, int):
+        return SyntheticNet(NetSpec(name, L, N, B, dtype, (1,), b_var, seed), cache=cache)
+    widths = tuple(int(v) for v in N)
+    return SyntheticNet(NetSpec(name, L, max(widths), B, dtype, (1,), b_var, seed, widths), cache=cache)
 
 
 def config_net(name: str, cache: bool = False) -> SyntheticNet:

@@ -11,6 +11,9 @@ a^1 = x^1, weights w^l (N x N, w^l[j][k] = weight into neuron j of layer l
 from neuron k of layer l-1) and biases b^l for l = 2..L.  A minibatch is
 stored sample-major: a^l has shape (B, N), row b is sample b, so
 "w^l a^{l-1}" for all samples at once is  a_prev @ w.T .
+Nothing here assumes equal widths (the paper fixes N per layer for its cost
+analysis only): every product takes its shape from w^l, which may be
+n_l x n_{l-1}.
 
 Arguments `w` and `b` are indexable by the paper's layer index (w[l] for
 l = 2..L): a dict, or any object with __getitem__.  Entries of any float type
@@ -32,7 +35,8 @@ Pins (tests/test_oracle_pins.py): central finite differences of C for every
 weight and bias of tiny nets; an fp64 autograd cross-check; the one-layer
 closed form; the all-zero-weights closed form; the rank-one symmetric net
 whose pass collapses to a scalar recurrence at any N; hand-computed values;
-Algorithm 1 run literally equals the sequential pass bit for bit for every k.
+Algorithm 1 run literally equals the sequential pass bit for bit for every k;
+finite differences and Algorithm 1 = sequential again for unequal widths.
 """
 from __future__ import annotations
 

@@ -42,6 +42,9 @@ def lib() -> C.CDLL:
         vp, vpp, i, sz = C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_size_t
         L.lf_workspace_bytes.restype, L.lf_workspace_bytes.argtypes = sz, [i, i, i, i]
         L.lf_create.restype, L.lf_create.argtypes = i, [vpp, i, i, i, i, i, vp, sz]
+        ip = C.POINTER(C.c_int)
+        L.lf_workspace_bytes_widths.restype, L.lf_workspace_bytes_widths.argtypes = sz, [i, ip, i, i]
+        L.lf_create_widths.restype, L.lf_create_widths.argtypes = i, [vpp, i, ip, i, i, i, vp, sz]
         L.lf_set_params.restype, L.lf_set_params.argtypes = i, [vp, vpp, vpp]
         L.lf_set_grad_buffers.restype, L.lf_set_grad_buffers.argtypes = i, [vp, vpp, vpp]
         L.lf_set_schedule.restype, L.lf_set_schedule.argtypes = i, [vp, i]
@@ -72,6 +75,24 @@ def lf_create(L: int, N: int, B: int, dt: int, cost: int, workspace: int, worksp
     """Returns (status, handle); handle is None unless status == LF_OK."""
     h = C.c_void_p()
     st = lib().lf_create(C.byref(h), L, N, B, dt, cost, C.c_void_p(workspace), workspace_bytes)
+    return st, (h if st == LF_OK else None)
+
+
+def _int_array(values: Optional[Sequence[int]]):
+    if values is None:
+        return None
+    return (C.c_int * len(values))(*values)
+
+
+def lf_workspace_bytes_widths(L: int, n: Optional[Sequence[int]], B: int, dt: int) -> int:
+    return int(lib().lf_workspace_bytes_widths(L, _int_array(n), B, dt))
+
+
+def lf_create_widths(L: int, n: Optional[Sequence[int]], B: int, dt: int, cost: int, workspace: int,
+                     workspace_bytes: int):
+    """Returns (status, handle); handle is None unless status == LF_OK."""
+    h = C.c_void_p()
+    st = lib().lf_create_widths(C.byref(h), L, _int_array(n), B, dt, cost, C.c_void_p(workspace), workspace_bytes)
     return st, (h if st == LF_OK else None)
 
 
@@ -128,29 +149,41 @@ def lf_destroy(net) -> None:
 # ---- convenience owner ---------------------------------------------------------------------------
 class LeapfrogNet:
     """Holds the torch tensors (weights, biases, gradients, workspace) of one net on the GPU and the
-    library handle that works on them.  Layer indices are the paper's: 2..L."""
+    library handle that works on them.  Layer indices are the paper's: 2..L.  N is the number of neurons of
+    every layer, or a sequence of L widths (layer 1 first)."""
 
-    def __init__(self, L: int, N: int, B: int = 1, dtype: str = "f32", device: str = "cuda:0"):
+    def __init__(self, L: int, N, B: int = 1, dtype: str = "f32", device: str = "cuda:0"):
         import torch
         self.torch = torch
-        self.L, self.N, self.B, self.dtype = L, N, B, dtype
+        self.widths = [int(N)] * L if isinstance(N, int) else [int(v) for v in N]
+        if len(self.widths) != L:
+            raise LfError(LF_EINVAL, "need one width per layer")
+        self.L, self.N, self.B, self.dtype = L, max(self.widths), B, dtype
         self.device = torch.device(device)
         self.dt = {"f32": LF_F32, "bf16": LF_BF16}[dtype]
         self.tdtype = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
-        nbytes = lf_workspace_bytes(L, N, B, self.dt)
+        n = self.widths
+        if isinstance(N, int):
+            nbytes = lf_workspace_bytes(L, N, B, self.dt)
+        else:
+            nbytes = lf_workspace_bytes_widths(L, n, B, self.dt)
         if nbytes == 0:
             raise LfError(LF_EINVAL, "invalid shape")
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        st, self.handle = lf_create(L, N, B, self.dt, LF_COST_QUADRATIC, self.workspace.data_ptr(), nbytes)
+        if isinstance(N, int):
+            st, self.handle = lf_create(L, N, B, self.dt, LF_COST_QUADRATIC, self.workspace.data_ptr(), nbytes)
+        else:
+            st, self.handle = lf_create_widths(L, n, B, self.dt, LF_COST_QUADRATIC, self.workspace.data_ptr(),
+                                               nbytes)
         if st != LF_OK:
             raise LfError(st, lf_last_error(None))
-        M = L - 1
-        self.w = [torch.empty((N, N), dtype=self.tdtype, device=self.device) for _ in range(M)]
-        self.b = [torch.empty(N, dtype=torch.float32, device=self.device) for _ in range(M)]
-        self.nabla_w = [torch.empty((N, N), dtype=torch.float32, device=self.device) for _ in range(M)]
-        self.nabla_b = [torch.empty(N, dtype=torch.float32, device=self.device) for _ in range(M)]
-        self.x = torch.empty((B, N), dtype=self.tdtype, device=self.device)
-        self.y = torch.empty((B, N), dtype=self.tdtype, device=self.device)
+        dev, f32 = self.device, torch.float32
+        self.w = [torch.empty((n[l - 1], n[l - 2]), dtype=self.tdtype, device=dev) for l in range(2, L + 1)]
+        self.b = [torch.empty(n[l - 1], dtype=f32, device=dev) for l in range(2, L + 1)]
+        self.nabla_w = [torch.empty((n[l - 1], n[l - 2]), dtype=f32, device=dev) for l in range(2, L + 1)]
+        self.nabla_b = [torch.empty(n[l - 1], dtype=f32, device=dev) for l in range(2, L + 1)]
+        self.x = torch.empty((B, n[0]), dtype=self.tdtype, device=dev)
+        self.y = torch.empty((B, n[L - 1]), dtype=self.tdtype, device=dev)
         self._check(lf_set_params(self.handle, [t.data_ptr() for t in self.w], [t.data_ptr() for t in self.b]))
         self._check(lf_set_grad_buffers(self.handle, [t.data_ptr() for t in self.nabla_w],
                                         [t.data_ptr() for t in self.nabla_b]))
@@ -198,12 +231,12 @@ class LeapfrogNet:
             return self.x
         st, pa, _ = lf_activations(self.handle, l)
         self._check(st)
-        return self._view(pa, (self.B, self.N), self.tdtype)
+        return self._view(pa, (self.B, self.widths[l - 1]), self.tdtype)
 
     def delta(self, l: int):
         st, _, pd = lf_activations(self.handle, l)
         self._check(st)
-        return self._view(pd, (self.B, self.N), self.torch.float32)
+        return self._view(pd, (self.B, self.widths[l - 1]), self.torch.float32)
 
     def grads(self, l: int):
         st, pw, pb = lf_grads(self.handle, l)

@@ -14,7 +14,7 @@ constexpr int kWavesPerWg = kThreads / kWave;
 __host__ __device__ constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // ------------------------------------------------------------------------------------------------
-// eqs. (z),(a):  a_out[j] = sigma( sum_k W[j][k] a_in[k] + b[j] )
+// eqs. (z),(a):  a_out[j] = sigma( sum_k W[j][k] a_in[k] + b[j] ),  W is rows x cols
 // One wave owns R consecutive rows.  a_in is staged once per workgroup in LDS; a lane walks the row
 // in float4 steps of stride 64 lanes, keeps one accumulator per row, and the 64 lane sums are
 // combined in a fixed order (row rotations, then the four rows of 16 lanes).
@@ -22,22 +22,22 @@ template <int R>
 __global__ __launch_bounds__(kThreads) void k_fwd_gemv(const float* __restrict__ W,
                                                        const float* __restrict__ bias,
                                                        const float* __restrict__ a_in,
-                                                       float* __restrict__ a_out, int N) {
-    extern __shared__ v4f s_a[];   // N/4 float4
-    const int nvec = N >> 2;
+                                                       float* __restrict__ a_out, int rows, int cols) {
+    extern __shared__ v4f s_a[];   // cols/4 float4
+    const int nvec = cols >> 2;
     for (int v = threadIdx.x; v < nvec; v += kThreads) s_a[v] = reinterpret_cast<const v4f*>(a_in)[v];
     __syncthreads();
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int row0 = (blockIdx.x * kWavesPerWg + wave) * R;
-    if (row0 >= N) return;
+    if (row0 >= rows) return;
 
     const v4f* wrow[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int row = min(row0 + r, N - 1);   // rows past the end repeat the last one; not stored
-        wrow[r] = reinterpret_cast<const v4f*>(W + (size_t)row * N);
+        const int row = min(row0 + r, rows - 1);   // rows past the end repeat the last one; not stored
+        wrow[r] = reinterpret_cast<const v4f*>(W + (size_t)row * cols);
     }
     float acc[R];
 #pragma unroll
@@ -77,31 +77,32 @@ __global__ __launch_bounds__(kThreads) void k_fwd_gemv(const float* __restrict__
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const float z = wave_sum(acc[r]);
-        if (lane == 0 && row0 + r < N) a_out[row0 + r] = sigmoidf(z + bias[row0 + r]);
+        if (lane == 0 && row0 + r < rows) a_out[row0 + r] = sigmoidf(z + bias[row0 + r]);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// eq. (bp2), stage 1: partial[p][k] = sum over the rows j of block p of W[j][k] * delta[j].
+// eq. (bp2), stage 1: partial[p][k] = sum over the rows j of block p of W[j][k] * delta[j]; W is rows x cols.
 // A workgroup covers one strip of 256 columns (a lane owns 4 consecutive columns, so each row is read
 // as one contiguous 1 KiB segment) and RPW rows per wave; the four waves' sums are added in wave
 // order through LDS.
 template <int RPW>
 __global__ __launch_bounds__(kThreads) void k_chain_partial(const float* __restrict__ W,
                                                             const float* __restrict__ delta,
-                                                            float* __restrict__ partial, int N) {
+                                                            float* __restrict__ partial, int rows,
+                                                            int cols) {
     __shared__ v4f s_acc[kWavesPerWg][kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int col = blockIdx.x * (kWave * 4) + lane * 4;
     const int row_begin = (blockIdx.y * kWavesPerWg + wave) * RPW;
     v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (col < N) {
-        const float* wp = W + (size_t)row_begin * N + col;
-        if (row_begin + RPW <= N) {
+    if (col < cols) {
+        const float* wp = W + (size_t)row_begin * cols + col;
+        if (row_begin + RPW <= rows) {
             v4f w[RPW];
 #pragma unroll
-            for (int r = 0; r < RPW; ++r) w[r] = *reinterpret_cast<const v4f*>(wp + (size_t)r * N);
+            for (int r = 0; r < RPW; ++r) w[r] = *reinterpret_cast<const v4f*>(wp + (size_t)r * cols);
 #pragma unroll
             for (int r = 0; r < RPW; ++r) {
                 const float d = delta[row_begin + r];
@@ -111,8 +112,8 @@ __global__ __launch_bounds__(kThreads) void k_chain_partial(const float* __restr
                 acc.w = fmaf(w[r].w, d, acc.w);
             }
         } else {
-            for (int r = 0; r < RPW && row_begin + r < N; ++r) {
-                const v4f w = *reinterpret_cast<const v4f*>(wp + (size_t)r * N);
+            for (int r = 0; r < RPW && row_begin + r < rows; ++r) {
+                const v4f w = *reinterpret_cast<const v4f*>(wp + (size_t)r * cols);
                 const float d = delta[row_begin + r];
                 acc.x = fmaf(w.x, d, acc.x);
                 acc.y = fmaf(w.y, d, acc.y);
@@ -123,11 +124,11 @@ __global__ __launch_bounds__(kThreads) void k_chain_partial(const float* __restr
     }
     s_acc[wave][lane] = acc;
     __syncthreads();
-    if (wave == 0 && col < N) {
+    if (wave == 0 && col < cols) {
         v4f t = s_acc[0][lane];
 #pragma unroll
         for (int q = 1; q < kWavesPerWg; ++q) t += s_acc[q][lane];
-        *reinterpret_cast<v4f*>(partial + (size_t)blockIdx.y * N + col) = t;
+        *reinterpret_cast<v4f*>(partial + (size_t)blockIdx.y * cols + col) = t;
     }
 }
 
@@ -144,33 +145,33 @@ __global__ __launch_bounds__(kThreads) void k_chain_finish(const float* __restri
 }
 
 // ------------------------------------------------------------------------------------------------
-// eqs. (bp3),(bp4):  nabla_b[j] = delta[j];  nabla_w[j][k] = delta[j] * a_prev[k].
+// eqs. (bp3),(bp4):  nabla_b[j] = delta[j];  nabla_w[j][k] = delta[j] * a_prev[k]  (rows x cols).
 // Pure store stream.  A wave owns a strip of 256 columns (its a_prev values stay in registers) and
 // RW rows, and writes each row segment with one non-temporal 128-bit store per lane.
 template <int RW>
 __global__ __launch_bounds__(kThreads) void k_grad_outer(const float* __restrict__ delta,
                                                          const float* __restrict__ a_prev,
                                                          float* __restrict__ nabla_w,
-                                                         float* __restrict__ nabla_b, int N,
-                                                         int nstrips) {
+                                                         float* __restrict__ nabla_b, int rows,
+                                                         int cols, int nstrips) {
     const int lane = threadIdx.x & (kWave - 1);
     const int gw = blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);   // global wave index
     const int strip = gw % nstrips;
     const int row0 = (gw / nstrips) * RW;
-    if (row0 >= N) return;
+    if (row0 >= rows) return;
     const int col = strip * (kWave * 4) + lane * 4;
     if (strip == 0) {
-        for (int r = lane; r < RW && row0 + r < N; r += kWave) nabla_b[row0 + r] = delta[row0 + r];
+        for (int r = lane; r < RW && row0 + r < rows; r += kWave) nabla_b[row0 + r] = delta[row0 + r];
     }
-    if (col >= N) return;
+    if (col >= cols) return;
     const v4f a = *reinterpret_cast<const v4f*>(a_prev + col);
-    float* out = nabla_w + (size_t)row0 * N + col;
+    float* out = nabla_w + (size_t)row0 * cols + col;
 #pragma unroll 4
     for (int r = 0; r < RW; ++r) {
-        if (row0 + r >= N) break;
+        if (row0 + r >= rows) break;
         const float d = delta[row0 + r];
         const v4f g = {d * a.x, d * a.y, d * a.z, d * a.w};
-        __builtin_nontemporal_store(g, reinterpret_cast<v4f*>(out + (size_t)r * N));
+        __builtin_nontemporal_store(g, reinterpret_cast<v4f*>(out + (size_t)r * cols));
     }
 }
 
@@ -190,46 +191,47 @@ __global__ __launch_bounds__(kThreads) void k_output_error(const T* __restrict__
     if (delta_bf) delta_bf[i] = (__bf16)d;
 }
 
-int chain_rows_per_wave(int N) { return N >= 4096 ? 16 : (N >= 2048 ? 8 : 4); }
+int chain_rows_per_wave(int rows) { return rows >= 4096 ? 16 : (rows >= 2048 ? 8 : 4); }
 
 }  // namespace
 
-int chain_partial_blocks(int N) { return ceil_div(N, kWavesPerWg * chain_rows_per_wave(N)); }
+int chain_partial_blocks(int rows) { return ceil_div(rows, kWavesPerWg * chain_rows_per_wave(rows)); }
 
 hipError_t launch_fwd_gemv_f32(const float* W, const float* b, const float* a_in, float* a_out,
-                               int N, hipStream_t s) {
-    const size_t lds = (size_t)N * sizeof(float);
-    if (N >= 4096) {
-        k_fwd_gemv<4><<<ceil_div(N, kWavesPerWg * 4), kThreads, lds, s>>>(W, b, a_in, a_out, N);
-    } else if (N >= 2048) {
-        k_fwd_gemv<2><<<ceil_div(N, kWavesPerWg * 2), kThreads, lds, s>>>(W, b, a_in, a_out, N);
+                               int rows, int cols, hipStream_t s) {
+    const size_t lds = (size_t)cols * sizeof(float);
+    const size_t elems = (size_t)rows * cols;
+    if (elems >= (size_t)4096 * 4096) {
+        k_fwd_gemv<4><<<ceil_div(rows, kWavesPerWg * 4), kThreads, lds, s>>>(W, b, a_in, a_out, rows, cols);
+    } else if (elems >= (size_t)2048 * 2048) {
+        k_fwd_gemv<2><<<ceil_div(rows, kWavesPerWg * 2), kThreads, lds, s>>>(W, b, a_in, a_out, rows, cols);
     } else {
-        k_fwd_gemv<1><<<ceil_div(N, kWavesPerWg), kThreads, lds, s>>>(W, b, a_in, a_out, N);
+        k_fwd_gemv<1><<<ceil_div(rows, kWavesPerWg), kThreads, lds, s>>>(W, b, a_in, a_out, rows, cols);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_chain_gemvT_f32(const float* W_next, const float* delta_next, const float* a_l,
-                                  float* delta_l, float* partial, int N, hipStream_t s) {
-    const int rpw = chain_rows_per_wave(N);
-    const int P = chain_partial_blocks(N);
-    const dim3 grid(ceil_div(N, kWave * 4), P);
-    if (rpw == 16) k_chain_partial<16><<<grid, kThreads, 0, s>>>(W_next, delta_next, partial, N);
-    else if (rpw == 8) k_chain_partial<8><<<grid, kThreads, 0, s>>>(W_next, delta_next, partial, N);
-    else k_chain_partial<4><<<grid, kThreads, 0, s>>>(W_next, delta_next, partial, N);
+                                  float* delta_l, float* partial, int rows, int cols, hipStream_t s) {
+    const int rpw = chain_rows_per_wave(rows);
+    const int P = chain_partial_blocks(rows);
+    const dim3 grid(ceil_div(cols, kWave * 4), P);
+    if (rpw == 16) k_chain_partial<16><<<grid, kThreads, 0, s>>>(W_next, delta_next, partial, rows, cols);
+    else if (rpw == 8) k_chain_partial<8><<<grid, kThreads, 0, s>>>(W_next, delta_next, partial, rows, cols);
+    else k_chain_partial<4><<<grid, kThreads, 0, s>>>(W_next, delta_next, partial, rows, cols);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    k_chain_finish<<<ceil_div(N, kThreads), kThreads, 0, s>>>(partial, a_l, delta_l, N, P);
+    k_chain_finish<<<ceil_div(cols, kThreads), kThreads, 0, s>>>(partial, a_l, delta_l, cols, P);
     return hipGetLastError();
 }
 
 hipError_t launch_grad_outer_f32(const float* delta, const float* a_prev, float* nabla_w,
-                                 float* nabla_b, int N, hipStream_t s) {
-    const int nstrips = ceil_div(N, kWave * 4);
+                                 float* nabla_b, int rows, int cols, hipStream_t s) {
+    const int nstrips = ceil_div(cols, kWave * 4);
     constexpr int RW = 16;
-    const int waves = nstrips * ceil_div(N, RW);
+    const int waves = nstrips * ceil_div(rows, RW);
     k_grad_outer<RW><<<ceil_div(waves, kWavesPerWg), kThreads, 0, s>>>(delta, a_prev, nabla_w, nabla_b,
-                                                                      N, nstrips);
+                                                                      rows, cols, nstrips);
     return hipGetLastError();
 }
 

@@ -607,8 +607,8 @@ hipError_t run_big(GemmArgs g, int splits, hipStream_t s) {
 
 }  // namespace
 
-// Whether a net of this shape takes the 256 x 256 bf16 kernel: when the forward product has at least 64
-// such tiles.  LF_GEMM_BIG=0/1 forces the choice (tests, A/B runs); the caller decides once per net.
+// Whether a net whose widest layer has N neurons takes the 256 x 256 bf16 kernel: when the forward product of
+// such a layer has at least 64 such tiles.  LF_GEMM_BIG=0/1 forces the choice (tests, A/B runs); the caller decides once per net.
 bool gemm_use_big(int N, int B, bool bf16) {
     if (!bf16) return false;
     if (const char* e = getenv("LF_GEMM_BIG")) {
@@ -618,37 +618,38 @@ bool gemm_use_big(int N, int B, bool bf16) {
     return ceil_div(B, big::TM) * ceil_div(N, big::TN) >= 64;
 }
 
-// Number of K splits used for the two chain-side GEMMs (output B x N is small, so a single pass over
-// K would leave most compute units idle).  Depends on the shape (and the kernel chosen) alone.
-int chain_splits(int N, int B, bool bf16, bool big_tiles) {
+// Number of K splits used for the two chain-side GEMMs (their output, B x n_out, is small, so a single pass
+// over the contraction length K would leave most compute units idle).  Depends on the shape (and the kernel
+// chosen) alone.
+int chain_splits(int n_out, int K, int B, bool bf16, bool big_tiles) {
     if (big_tiles) {
-        const int tiles = ceil_div(N, big::TN) * ceil_div(B, big::TM);
-        const int kt = ceil_div(N, big::TK);
+        const int tiles = ceil_div(n_out, big::TN) * ceil_div(B, big::TM);
+        const int kt = ceil_div(K, big::TK);
         int s = 1;
         while (tiles * s < 256 && s < 16 && kt / (s * 2) >= 4) s *= 2;      // one workgroup per compute unit
         return s;
     }
-    const int tiles = ceil_div(N, BN) * ceil_div(B, BM);
-    const int kt = ceil_div(N, bf16 ? Tile<__bf16>::BK : Tile<float>::BK);
+    const int tiles = ceil_div(n_out, BN) * ceil_div(B, BM);
+    const int kt = ceil_div(K, bf16 ? Tile<__bf16>::BK : Tile<float>::BK);
     int s = 1;
     while (tiles * s < 512 && s < 16 && kt / (s * 2) >= 4) s *= 2;
     return s;
 }
 
-size_t split_workspace_floats(int N, int B, bool bf16) {      // enough for either kernel
-    int s = chain_splits(N, B, bf16, false);
-    if (bf16) s = max(s, chain_splits(N, B, true, true));
-    return s > 1 ? (size_t)s * B * N : 0;
+size_t split_workspace_floats(int n_out, int K, int B, bool bf16) {      // enough for either kernel
+    int s = chain_splits(n_out, K, B, bf16, false);
+    if (bf16) s = max(s, chain_splits(n_out, K, B, true, true));
+    return s > 1 ? (size_t)s * B * n_out : 0;
 }
 
 template <typename T>
 static hipError_t fwd_impl(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
-                           int N, int B, bool big_tiles, hipStream_t s) {
+                           int n_out, int n_in, int B, bool big_tiles, hipStream_t s) {
     constexpr bool bf = sizeof(T) == 2;
-    const int splits = chain_splits(N, B, bf, big_tiles);
+    const int splits = chain_splits(n_out, n_in, B, bf, big_tiles);
     GemmArgs g{};
-    g.P = A_in; g.ldp = N; g.Q = W; g.ldq = N; g.M = B; g.Nn = N; g.K = N;
-    g.k_tiles_per_split = ceil_div(ceil_div(N, Tile<T>::BK), splits);
+    g.P = A_in; g.ldp = n_in; g.Q = W; g.ldq = n_in; g.M = B; g.Nn = n_out; g.K = n_in;
+    g.k_tiles_per_split = ceil_div(ceil_div(n_in, Tile<T>::BK), splits);
     g.bias = bias; g.out = A_out; g.raw = raw;
     hipError_t e;
     if constexpr (bf) {
@@ -664,20 +665,21 @@ static hipError_t fwd_impl(const void* W, const float* bias, const void* A_in, v
         e = run<T, false, false, EPI_RAW>(g, splits, s);
     }
     if (e != hipSuccess) return e;
-    const size_t count = (size_t)B * N;
+    const size_t count = (size_t)B * n_out;
     k_split_finish<T, EPI_SIGMOID><<<(unsigned)((count + kThreads - 1) / kThreads), kThreads, 0, s>>>(
-        raw, splits, count, N, bias, nullptr, A_out, nullptr);
+        raw, splits, count, n_out, bias, nullptr, A_out, nullptr);
     return hipGetLastError();
 }
 
 template <typename T>
 static hipError_t chain_impl(const void* W_next, const void* D_next_op, const void* A_l, float* D_l,
-                             void* D_l_bf, float* raw, int N, int B, bool big_tiles, hipStream_t s) {
+                             void* D_l_bf, float* raw, int n_l, int n_next, int B, bool big_tiles,
+                             hipStream_t s) {
     constexpr bool bf = sizeof(T) == 2;
-    const int splits = chain_splits(N, B, bf, big_tiles);
+    const int splits = chain_splits(n_l, n_next, B, bf, big_tiles);
     GemmArgs g{};
-    g.P = D_next_op; g.ldp = N; g.Q = W_next; g.ldq = N; g.M = B; g.Nn = N; g.K = N;
-    g.k_tiles_per_split = ceil_div(ceil_div(N, Tile<T>::BK), splits);
+    g.P = D_next_op; g.ldp = n_next; g.Q = W_next; g.ldq = n_l; g.M = B; g.Nn = n_l; g.K = n_next;
+    g.k_tiles_per_split = ceil_div(ceil_div(n_next, Tile<T>::BK), splits);
     g.act = A_l; g.out = D_l; g.out_bf = D_l_bf; g.raw = raw;
     hipError_t e;
     if constexpr (bf) {
@@ -693,32 +695,33 @@ static hipError_t chain_impl(const void* W_next, const void* D_next_op, const vo
         e = run<T, false, true, EPI_RAW>(g, splits, s);
     }
     if (e != hipSuccess) return e;
-    const size_t count = (size_t)B * N;
+    const size_t count = (size_t)B * n_l;
     k_split_finish<T, EPI_SIGMA_PRIME><<<(unsigned)((count + kThreads - 1) / kThreads), kThreads, 0, s>>>(
-        raw, splits, count, N, nullptr, static_cast<const T*>(A_l), D_l, static_cast<__bf16*>(D_l_bf));
+        raw, splits, count, n_l, nullptr, static_cast<const T*>(A_l), D_l, static_cast<__bf16*>(D_l_bf));
     return hipGetLastError();
 }
 
 hipError_t launch_fwd_gemm(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
-                           int N, int B, bool bf16, bool big_tiles, hipStream_t s) {
-    return bf16 ? fwd_impl<__bf16>(W, bias, A_in, A_out, raw, N, B, big_tiles, s)
-                : fwd_impl<float>(W, bias, A_in, A_out, raw, N, B, false, s);
+                           int n_out, int n_in, int B, bool bf16, bool big_tiles, hipStream_t s) {
+    return bf16 ? fwd_impl<__bf16>(W, bias, A_in, A_out, raw, n_out, n_in, B, big_tiles, s)
+                : fwd_impl<float>(W, bias, A_in, A_out, raw, n_out, n_in, B, false, s);
 }
 
 hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void* D_next_bf,
-                             const void* A_l, float* D_l, void* D_l_bf, float* raw, int N, int B,
-                             bool bf16, bool big_tiles, hipStream_t s) {
-    return bf16 ? chain_impl<__bf16>(W_next, D_next_bf, A_l, D_l, D_l_bf, raw, N, B, big_tiles, s)
-                : chain_impl<float>(W_next, D_next, A_l, D_l, nullptr, raw, N, B, false, s);
+                             const void* A_l, float* D_l, void* D_l_bf, float* raw, int n_l, int n_next,
+                             int B, bool bf16, bool big_tiles, hipStream_t s) {
+    return bf16 ? chain_impl<__bf16>(W_next, D_next_bf, A_l, D_l, D_l_bf, raw, n_l, n_next, B, big_tiles, s)
+                : chain_impl<float>(W_next, D_next, A_l, D_l, nullptr, raw, n_l, n_next, B, false, s);
 }
 
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
-                            float* nabla_b, int N, int B, bool bf16, bool big_tiles, hipStream_t s) {
-    k_bias_grad<<<ceil_div(N, 32), kThreads, 0, s>>>(D, nabla_b, N, B);
+                            float* nabla_b, int n_l, int n_prev, int B, bool bf16, bool big_tiles,
+                            hipStream_t s) {
+    k_bias_grad<<<ceil_div(n_l, 32), kThreads, 0, s>>>(D, nabla_b, n_l, B);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     GemmArgs g{};
-    g.ldp = N; g.Q = A_prev; g.ldq = N; g.M = N; g.Nn = N; g.K = B;
+    g.ldp = n_l; g.Q = A_prev; g.ldq = n_prev; g.M = n_l; g.Nn = n_prev; g.K = B;
     g.out = nabla_w;
     if (bf16) {
         g.P = D_bf;

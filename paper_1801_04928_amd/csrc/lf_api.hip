@@ -41,11 +41,26 @@ struct Layout {
     size_t total;
 };
 
-bool valid_shape(int L, int N, int B, lf_dtype dt) {
-    if (L < 2 || L > kMaxL || N < 1 || B < 1) return false;
+// n[l-1] = neurons of layer l, l = 1..L
+bool valid_shape(int L, const int* n, int B, lf_dtype dt) {
+    if (L < 2 || L > kMaxL || !n || B < 1) return false;
     if (dt != LF_F32 && dt != LF_BF16) return false;
-    if (N % (dt == LF_BF16 ? 8 : 4) != 0) return false;
-    if ((size_t)N * (size_t)B > ((size_t)1 << 40)) return false;
+    for (int i = 0; i < L; ++i) {
+        if (n[i] < 1 || n[i] % (dt == LF_BF16 ? 8 : 4) != 0) return false;
+        if ((size_t)n[i] * (size_t)B > ((size_t)1 << 40)) return false;
+    }
+    return true;
+}
+
+int widest(int L, const int* n) {
+    int m = n[0];
+    for (int i = 1; i < L; ++i) m = std::max(m, n[i]);
+    return m;
+}
+
+bool all_equal(int L, const int* n) {
+    for (int i = 1; i < L; ++i)
+        if (n[i] != n[0]) return false;
     return true;
 }
 
@@ -62,21 +77,36 @@ int ll_spread_shift() {
     return shift;
 }
 
-Layout make_layout(int L, int N, int B, lf_dtype dt) {
+// Every layer's a^l and delta^l get a slot sized for the widest layer (N).
+Layout make_layout(int L, const int* n, int B, lf_dtype dt) {
     Layout y{};
+    const int N = widest(L, n);
     const size_t M = (size_t)(L - 1), bn = (size_t)B * N;
     const size_t es = dt == LF_BF16 ? 2 : 4;
     size_t off = 0;
     y.a_off = off;   y.a_stride = align_up(bn * es);   off += M * y.a_stride;
     y.d_off = off;   y.d_stride = align_up(bn * 4);    off += M * y.d_stride;
     y.dbf_off = off; y.dbf_stride = dt == LF_BF16 ? align_up(bn * 2) : 0; off += M * y.dbf_stride;
+    // scratch of the chain-side products, sized for the layer that needs most: the row-block partial sums
+    // of the single-sample chain step, the split-K partials of the minibatch products
+    size_t partial_floats = 0, raw_floats = 0;
+    for (int l = 2; l <= L; ++l) {
+        const int n_l = n[l - 1], n_prev = n[l - 2];
+        if (single_sample_path(N, B, dt)) {
+            if (l >= 3)   // the step delta^l -> delta^{l-1} reads w^l (n_l x n_prev)
+                partial_floats = std::max(partial_floats, (size_t)lf::chain_partial_blocks(n_l) * n_prev);
+        } else {
+            raw_floats = std::max(raw_floats, lf::split_workspace_floats(n_l, n_prev, B, dt == LF_BF16));
+            if (l >= 3) raw_floats = std::max(raw_floats, lf::split_workspace_floats(n_prev, n_l, B, dt == LF_BF16));
+        }
+    }
     y.partial_off = off;
-    y.partial_bytes = single_sample_path(N, B, dt) ? align_up((size_t)lf::chain_partial_blocks(N) * N * 4) : 0;
+    y.partial_bytes = align_up(partial_floats * 4);
     off += y.partial_bytes;
     y.raw_off = off;
-    y.raw_bytes = single_sample_path(N, B, dt) ? 0 : align_up(lf::split_workspace_floats(N, B, dt == LF_BF16) * 4);
+    y.raw_bytes = align_up(raw_floats * 4);
     off += y.raw_bytes;
-    if (single_sample_path(N, B, dt) && lf::persistent_supported(L, N)) {
+    if (all_equal(L, n) && single_sample_path(N, B, dt) && lf::persistent_supported(L, N)) {
         y.ll_shift = ll_spread_shift();
         y.ll_layer = lf::persistent_ll_layer_words(N, y.ll_shift);
         y.ll_words = M * y.ll_layer;
@@ -97,7 +127,10 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 }  // namespace
 
 struct lf_net {
-    int L, N, B;
+    int L, N, B;                       // N: the widest layer
+    std::vector<int> n;                // n[l-1] = neurons of layer l
+    bool uniform;                      // every layer has N neurons
+    int width(int l) const { return n[l - 1]; }
     lf_dtype dt;
     lf_cost cost;
     lf_sched sched;
@@ -170,7 +203,8 @@ lf_status ensure_workers(lf_net* net, int k) {
 }
 
 bool persistent_possible(const lf_net* net) {
-    return single_sample_path(net->N, net->B, net->dt) && lf::persistent_supported(net->L, net->N);
+    return net->uniform && single_sample_path(net->N, net->B, net->dt) &&
+           lf::persistent_supported(net->L, net->N);
 }
 
 bool use_persistent(const lf_net* net) {
@@ -307,10 +341,11 @@ lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
     const int i = l - 2;
     if (single_sample_path(net->N, net->B, net->dt)) {
         LF_HIP(net, lf::launch_grad_outer_f32(net->d_ptr(l), static_cast<const float*>(net->a_ptr(l - 1)),
-                                              net->gw[i], net->gb[i], net->N, s));
+                                              net->gw[i], net->gb[i], net->width(l), net->width(l - 1), s));
     } else {
         LF_HIP(net, lf::launch_grad_gemm(net->d_ptr(l), net->dbf_ptr(l), net->a_ptr(l - 1), net->gw[i],
-                                         net->gb[i], net->N, net->B, net->dt == LF_BF16, net->gemm_big, s));
+                                         net->gb[i], net->width(l), net->width(l - 1), net->B,
+                                         net->dt == LF_BF16, net->gemm_big, s));
     }
     return LF_OK;
 }
@@ -319,32 +354,40 @@ lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
 
 extern "C" {
 
-size_t lf_workspace_bytes(int L, int N, int B, lf_dtype dt) {
-    if (!valid_shape(L, N, B, dt)) return 0;
-    const size_t t = make_layout(L, N, B, dt).total;
+size_t lf_workspace_bytes_widths(int L, const int* n, int B, lf_dtype dt) {
+    if (!valid_shape(L, n, B, dt)) return 0;
+    const size_t t = make_layout(L, n, B, dt).total;
     return t ? t : kAlign;
 }
 
-lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost, void* workspace,
-                    size_t workspace_bytes) {
+size_t lf_workspace_bytes(int L, int N, int B, lf_dtype dt) {
+    if (L < 2 || L > kMaxL) return 0;
+    const std::vector<int> n((size_t)L, N);
+    return lf_workspace_bytes_widths(L, n.data(), B, dt);
+}
+
+lf_status lf_create_widths(lf_net** out, int L, const int* n, int B, lf_dtype dt, lf_cost cost, void* workspace,
+                           size_t workspace_bytes) {
     if (!out) return fail(nullptr, LF_EINVAL, "lf_create: out is NULL");
     *out = nullptr;
-    if (!valid_shape(L, N, B, dt))
+    if (!valid_shape(L, n, B, dt))
         return fail(nullptr, LF_EINVAL,
-                    "lf_create: need 2 <= L <= 4096, B >= 1, N a positive multiple of 4 (fp32) or 8 (bf16)");
+                    "lf_create: need 2 <= L <= 4096, B >= 1, every width a positive multiple of 4 (fp32) or 8 (bf16)");
     if (cost != LF_COST_QUADRATIC) return fail(nullptr, LF_EINVAL, "lf_create: unknown cost");
     if (!workspace) return fail(nullptr, LF_EINVAL, "lf_create: workspace is NULL");
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign)
         return fail(nullptr, LF_EINVAL, "lf_create: workspace must be 256-byte aligned");
-    if (workspace_bytes < lf_workspace_bytes(L, N, B, dt))
+    if (workspace_bytes < lf_workspace_bytes_widths(L, n, B, dt))
         return fail(nullptr, LF_EINVAL, "lf_create: workspace smaller than lf_workspace_bytes()");
     lf_net* net = new (std::nothrow) lf_net();
     if (!net) return fail(nullptr, LF_ENOMEM, "lf_create: out of host memory");
+    const int N = widest(L, n);
     net->L = L; net->N = N; net->B = B; net->dt = dt; net->cost = cost;
+    net->uniform = all_equal(L, n);
     net->sched = LF_SCHED_AUTO;
     net->cost_scale = 1.0f;
     net->ws = static_cast<char*>(workspace);
-    net->lay = make_layout(L, N, B, dt);
+    net->lay = make_layout(L, n, B, dt);
     net->x1 = nullptr;
     net->have_params = net->have_grads = net->fwd_done = net->bwd_done = false;
     net->gemm_big = lf::gemm_use_big(N, B, dt == LF_BF16);
@@ -352,6 +395,7 @@ lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost
     net->p_abort_host = nullptr; net->p_abort_dev_view = nullptr;
     net->err = "no error";
     try {
+        net->n.assign(n, n + L);
         net->w.assign(L - 1, nullptr); net->b.assign(L - 1, nullptr);
         net->gw.assign(L - 1, nullptr); net->gb.assign(L - 1, nullptr);
     } catch (...) {
@@ -360,6 +404,21 @@ lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost
     }
     *out = net;
     return LF_OK;
+}
+
+lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost, void* workspace,
+                    size_t workspace_bytes) {
+    if (out) *out = nullptr;
+    if (L < 2 || L > kMaxL)
+        return fail(nullptr, LF_EINVAL,
+                    "lf_create: need 2 <= L <= 4096, B >= 1, N a positive multiple of 4 (fp32) or 8 (bf16)");
+    std::vector<int> n;
+    try {
+        n.assign((size_t)L, N);
+    } catch (...) {
+        return fail(nullptr, LF_ENOMEM, "lf_create: out of host memory");
+    }
+    return lf_create_widths(out, L, n.data(), B, dt, cost, workspace, workspace_bytes);
 }
 
 lf_status lf_set_params(lf_net* net, const void* const* w, const void* const* b) {
@@ -402,7 +461,7 @@ lf_status lf_set_schedule(lf_net* net, lf_sched sched) {
         case LF_SCHED_PERSISTENT:
             if (!persistent_possible(net))
                 return fail(net, LF_EUNSUPPORTED,
-                            "lf_set_schedule: the persistent path needs B = 1, fp32, N <= 4096");
+                            "lf_set_schedule: the persistent path needs B = 1, fp32, equal widths N <= 4096");
             net->sched = sched;
             return LF_OK;
         default:
@@ -443,10 +502,12 @@ lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream) {
         if (single_sample_path(net->N, net->B, net->dt)) {
             LF_HIP(net, lf::launch_fwd_gemv_f32(static_cast<const float*>(net->w[l - 2]), net->b[l - 2],
                                                 static_cast<const float*>(net->a_ptr(l - 1)),
-                                                static_cast<float*>(net->a_ptr(l)), net->N, s));
+                                                static_cast<float*>(net->a_ptr(l)), net->width(l),
+                                                net->width(l - 1), s));
         } else {
             LF_HIP(net, lf::launch_fwd_gemm(net->w[l - 2], net->b[l - 2], net->a_ptr(l - 1), net->a_ptr(l),
-                                            net->raw(), net->N, net->B, bf, net->gemm_big, s));
+                                            net->raw(), net->width(l), net->width(l - 1), net->B, bf,
+                                            net->gemm_big, s));
         }
     }
     net->fwd_done = true;
@@ -486,14 +547,16 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
         // the chain: (bp1) at L, (bp2) below
         if (l == L) {
             LF_HIP(net, lf::launch_output_error(net->a_ptr(L), y, net->d_ptr(L), net->dbf_ptr(L),
-                                                (size_t)B * N, bf, net->cost_scale, s));
+                                                (size_t)B * net->width(L), bf, net->cost_scale, s));
         } else if (b1) {
+            // w^{l+1} has n_{l+1} rows and n_l columns
             LF_HIP(net, lf::launch_chain_gemvT_f32(static_cast<const float*>(net->w[l - 1]), net->d_ptr(l + 1),
                                                    static_cast<const float*>(net->a_ptr(l)), net->d_ptr(l),
-                                                   net->partial(), N, s));
+                                                   net->partial(), net->width(l + 1), net->width(l), s));
         } else {
             LF_HIP(net, lf::launch_chain_gemm(net->w[l - 1], net->d_ptr(l + 1), net->dbf_ptr(l + 1), net->a_ptr(l),
-                                              net->d_ptr(l), net->dbf_ptr(l), net->raw(), N, B, bf, net->gemm_big, s));
+                                              net->d_ptr(l), net->dbf_ptr(l), net->raw(), net->width(l),
+                                              net->width(l + 1), B, bf, net->gemm_big, s));
         }
         // (bp3),(bp4) of layer l, off the chain
         if (k == 1) {

@@ -10,19 +10,21 @@
 namespace lf {
 
 // ---- single-sample (B = 1) fp32 path: HBM-bound GEMV / outer-product kernels --------------------
+// Matrices are rows x cols, row-major: w^l has n_l rows and n_{l-1} columns.
 
-// Row blocks the transposed GEMV of eq. (bp2) is split into (size of its partial buffer, [P][N]).
-int chain_partial_blocks(int N);
+// Row blocks the transposed GEMV of eq. (bp2) is split into (its partial buffer is [P][cols]).
+int chain_partial_blocks(int rows);
 
 // eqs. (z),(a): a_out = sigma(W a_in + b)
 hipError_t launch_fwd_gemv_f32(const float* W, const float* b, const float* a_in, float* a_out,
-                               int N, hipStream_t s);
-// eq. (bp2): delta_l = (W_next^T delta_next) (.) a_l (1 - a_l); partial: [chain_partial_blocks(N)][N]
+                               int rows, int cols, hipStream_t s);
+// eq. (bp2): delta_l = (W_next^T delta_next) (.) a_l (1 - a_l); W_next is rows x cols, delta_next has rows
+// entries, delta_l and a_l cols; partial: [chain_partial_blocks(rows)][cols]
 hipError_t launch_chain_gemvT_f32(const float* W_next, const float* delta_next, const float* a_l,
-                                  float* delta_l, float* partial, int N, hipStream_t s);
-// eqs. (bp3),(bp4): nabla_b = delta; nabla_w[j][k] = delta[j] a_prev[k]
+                                  float* delta_l, float* partial, int rows, int cols, hipStream_t s);
+// eqs. (bp3),(bp4): nabla_b = delta (rows entries); nabla_w[j][k] = delta[j] a_prev[k] (rows x cols)
 hipError_t launch_grad_outer_f32(const float* delta, const float* a_prev, float* nabla_w,
-                                 float* nabla_b, int N, hipStream_t s);
+                                 float* nabla_b, int rows, int cols, hipStream_t s);
 
 // ---- any B, either storage type ----------------------------------------------------------------
 
@@ -34,23 +36,27 @@ hipError_t launch_output_error(const void* a_L, const void* y, float* delta_L, v
 
 // ---- minibatch path: MFMA contractions ----------------------------------------------------------
 
-// Floats of scratch the split-K stage of the forward / chain contractions needs (0 = no split).
-size_t split_workspace_floats(int N, int B, bool bf16);
-// Whether a net of this shape takes the 256 x 256-tile bf16 kernel (decided once per net; `big_tiles` below).
+// Floats of scratch the split-K stage of a forward / chain contraction with a B x n_out result and
+// contraction length K needs (0 = no split).
+size_t split_workspace_floats(int n_out, int K, int B, bool bf16);
+// Whether a net whose widest layer has N neurons takes the 256 x 256-tile bf16 kernel (decided once per net;
+// `big_tiles` below).
 bool gemm_use_big(int N, int B, bool bf16);
 
-// eqs. (z),(a) for a minibatch: A_out[b][j] = sigma(sum_k A_in[b][k] W[j][k] + bias[j])
-// `raw` is the split-K scratch, split_workspace_floats(N, B, bf16) floats (may be NULL when that is 0).
+// eqs. (z),(a) for a minibatch: A_out[b][j] = sigma(sum_k A_in[b][k] W[j][k] + bias[j]); W is n_out x n_in.
+// `raw` is the split-K scratch, split_workspace_floats(n_out, n_in, B, bf16) floats (may be NULL when that is 0).
 hipError_t launch_fwd_gemm(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
-                           int N, int B, bool bf16, bool big_tiles, hipStream_t s);
-// eq. (bp2) for a minibatch: D_l[b][k] = (sum_j D_next[b][j] W_next[j][k]) A_l[b][k] (1 - A_l[b][k]).
-// For bf16, D_next_bf / D_l_bf are the bfloat16 copies used as matrix operands.
+                           int n_out, int n_in, int B, bool bf16, bool big_tiles, hipStream_t s);
+// eq. (bp2) for a minibatch: D_l[b][k] = (sum_j D_next[b][j] W_next[j][k]) A_l[b][k] (1 - A_l[b][k]);
+// W_next is n_next x n_l.  For bf16, D_next_bf / D_l_bf are the bfloat16 copies used as matrix operands.
+// raw: split_workspace_floats(n_l, n_next, B, bf16) floats.
 hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void* D_next_bf,
                              const void* A_l, float* D_l, void* D_l_bf, float* raw,
-                             int N, int B, bool bf16, bool big_tiles, hipStream_t s);
-// eqs. (bp3),(bp4) for a minibatch: nabla_w[j][k] = sum_b D[b][j] A_prev[b][k];
+                             int n_l, int n_next, int B, bool bf16, bool big_tiles, hipStream_t s);
+// eqs. (bp3),(bp4) for a minibatch: nabla_w[j][k] = sum_b D[b][j] A_prev[b][k] (n_l x n_prev);
 // nabla_b[j] = sum_b D[b][j] (fixed summation order).
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
-                            float* nabla_b, int N, int B, bool bf16, bool big_tiles, hipStream_t s);
+                            float* nabla_b, int n_l, int n_prev, int B, bool bf16, bool big_tiles,
+                            hipStream_t s);
 
 }  // namespace lf

@@ -47,7 +47,7 @@ def run_gpu(net, k, sched=None, poison=True):
     import torch
     import paper_1801_04928_amd as P
     s = net.spec
-    g = P.LeapfrogNet(s.L, s.N, s.B, s.dtype)
+    g = P.LeapfrogNet(s.L, list(s.widths) if s.widths else s.N, s.B, s.dtype)
     g.load(net)
     if sched is not None:
         g.set_schedule(sched)
@@ -95,8 +95,8 @@ def check_against_oracle(net, g, tol=None, sample_tiles=None, rng=None):
             count, size = sample_tiles
             tiles = []
             for _ in range(count):
-                j0 = int(rng.integers(0, max(1, s.N - size + 1)))
-                k0 = int(rng.integers(0, max(1, s.N - size + 1)))
+                j0 = int(rng.integers(0, max(1, s.width(l) - size + 1)))
+                k0 = int(rng.integers(0, max(1, s.width(l - 1) - size + 1)))
                 want = delta[:, j0:j0 + size].T @ a[l - 1][:, k0:k0 + size]
                 got = to_np(gw[j0:j0 + size, k0:k0 + size])
                 tiles.append((got, want))

@@ -63,6 +63,40 @@ def test_create_rejects_bad_arguments():
         assert "lf_create" in P.lf_last_error(None)
 
 
+def test_unequal_widths_workspace_and_create():
+    """lf_workspace_bytes_widths / lf_create_widths: one width per layer, the same limits as N; equal widths
+    give lf_create's workspace; such a net has no persistent path."""
+    F = P.LF_F32
+    assert P.lf_workspace_bytes_widths(3, [8, 16, 4], 1, F) > 0
+    assert P.lf_workspace_bytes_widths(3, [8, 16, 4], 1, F) % 256 == 0
+    assert P.lf_workspace_bytes_widths(3, [8, 15, 4], 1, F) == 0       # not a multiple of 4
+    assert P.lf_workspace_bytes_widths(3, [8, 16, 4], 1, P.LF_BF16) == 0   # 4 is not a multiple of 8
+    assert P.lf_workspace_bytes_widths(3, [8, 0, 4], 1, F) == 0
+    assert P.lf_workspace_bytes_widths(1, [8], 1, F) == 0
+    assert P.lf_workspace_bytes_widths(3, None, 1, F) == 0
+    assert P.lf_workspace_bytes_widths(8, [256] * 8, 1, F) == P.lf_workspace_bytes(8, 256, 1, F)
+    assert P.lf_workspace_bytes_widths(4, [64, 256, 256, 32], 16, F) <= P.lf_workspace_bytes(4, 256, 16, F)
+    widths = [64, 256, 128, 32]
+    nbytes = P.lf_workspace_bytes_widths(4, widths, 1, F)
+    st, h = P.lf_create_widths(4, widths, 1, F, P.LF_COST_QUADRATIC, FAKE, nbytes)
+    assert st == P.LF_OK
+    assert P.lf_set_schedule(h, P.LF_SCHED_PERSISTENT) == P.LF_EUNSUPPORTED
+    assert "equal widths" in P.lf_last_error(h)
+    assert P.lf_set_schedule(h, P.LF_SCHED_STREAMS) == P.LF_OK
+    assert P.lf_set_schedule(h, P.LF_SCHED_AUTO) == P.LF_OK
+    P.lf_destroy(h)
+    st, h = P.lf_create_widths(4, widths, 1, F, P.LF_COST_QUADRATIC, FAKE, nbytes - 1)
+    assert st == P.LF_EINVAL and h is None
+    st, h = P.lf_create_widths(4, [64, 256, 130, 32], 1, F, P.LF_COST_QUADRATIC, FAKE, nbytes)
+    assert st == P.LF_EINVAL and "width" in P.lf_last_error(None)
+    st, h = P.lf_create_widths(4, None, 1, F, P.LF_COST_QUADRATIC, FAKE, nbytes)
+    assert st == P.LF_EINVAL
+    # equal widths through the general call: the persistent path is there
+    st, h = P.lf_create_widths(8, [256] * 8, 1, F, P.LF_COST_QUADRATIC, FAKE, P.lf_workspace_bytes(8, 256, 1, F))
+    assert st == P.LF_OK and P.lf_set_schedule(h, P.LF_SCHED_PERSISTENT) == P.LF_OK
+    P.lf_destroy(h)
+
+
 def test_call_order_and_argument_checks():
     h = _handle()
     M = 7

@@ -331,6 +331,56 @@ def test_minibatch_bf16_large_tile_kernel_matches_oracle(monkeypatch, L, N, B, k
 
 
 # ---------------------------------------------------------------- the five configurations, full size
+# ---------------------------------------------------------------- layers of unequal widths
+@pytest.mark.parametrize("widths,B,dtype,k,big", [
+    ((260, 1028, 516, 2052, 64), 1, "f32", 2, None),     # single sample: every matrix ragged, rows-per-wave 4 and 8
+    ((1000, 4100, 300, 4100), 1, "f32", 3, None),        # rows-per-wave 16 on a 4100 x 300 and a 300 x 4100 matrix
+    ((4100, 4100, 8), 1, "f32", 1, None),                # four rows per wave forward; an 8 x 4100 last layer
+    ((8, 4), 1, "f32", 1, None),                         # one tiny weight layer
+    ((264, 520, 136, 392), 70, "f32", 2, None),          # minibatch fp32 MFMA, ragged in every dimension
+    ((136, 1032, 264), 300, "f32", 1, None),             # several row tiles
+    ((264, 520, 136, 392), 70, "bf16", 3, "0"),          # bf16, 128 x 128 tiles
+    ((520, 264, 1032, 264), 260, "bf16", 2, "1"),        # bf16, 256 x 256 tiles, split K of unequal lengths
+])
+def test_unequal_layer_widths_match_oracle(monkeypatch, widths, B, dtype, k, big):
+    """Nets whose layers differ in width (w^l is n_l x n_{l-1}; x has n_1 and y has n_L entries): the stream
+    schedule's kernels against the oracle, and the same bits for another k."""
+    import torch
+    if big is not None:
+        monkeypatch.setenv("LF_GEMM_BIG", big)
+    L = len(widths)
+    net = make_net(L, widths, B, dtype=dtype, seed=sum(widths) + B)
+    g = run_gpu(net, k)
+    rep = check_against_oracle(net, g)
+    for l in range(2, L + 1):
+        gw, gb = g.grads(l)
+        assert tuple(gw.shape) == (widths[l - 1], widths[l - 2]) and tuple(gb.shape) == (widths[l - 1],)
+    if L > 2:
+        ref = [to_np(t).copy() for t in g.nabla_w] + [to_np(t).copy() for t in g.nabla_b]
+        g.forward()
+        g.backward(1 if k > 1 else 2)
+        torch.cuda.synchronize()
+        got = [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]
+        for a, b in zip(ref, got):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    log(f"widths {widths} B={B} {dtype} k={k}: worst normwise error {rep['worst']:.2e}")
+    _free(g)
+
+
+def test_unequal_layer_widths_outer_product_is_exact():
+    """Eq. (bp4) at B = 1 with a non-square w^l: nabla_w^l[j][k] = fl32(delta^l[j] * a^{l-1}[k]) bit for bit."""
+    widths = (772, 260, 1284, 516)
+    net = make_net(4, widths, 1, seed=9)
+    g = run_gpu(net, 2)
+    for l in range(2, 5):
+        d = to_np(g.delta(l))[0].astype(np.float32)
+        a = to_np(g.activation(l - 1))[0].astype(np.float32)
+        gw, gb = g.grads(l)
+        assert np.array_equal(to_np(gw), np.outer(d, a).astype(np.float32))
+        assert np.array_equal(to_np(gb), d)
+    _free(g)
+
+
 def test_config1_full():
     net = config_net("cfg1", cache=True)
     g = run_gpu(net, 2)

@@ -53,6 +53,57 @@ def test_gradients_match_central_finite_differences(L, N, B):
     assert worst < 2e-9, worst
 
 
+@pytest.mark.parametrize("widths,B", [((3, 5, 2), 1), ((4, 2, 6, 3), 2), ((2, 7), 3), ((5, 1, 4, 1, 3), 1)])
+def test_gradients_of_nets_with_unequal_widths_match_finite_differences(widths, B):
+    """Section 2 fixes N neurons per layer for its cost analysis only; the equations hold for any widths.
+    With w^l of shape n_l x n_{l-1} a transposed operand does not even have the right shape, and every
+    dC/dw^l_jk, dC/db^l_j must still equal a central difference of C."""
+    L = len(widths)
+    net = make_net(L, widths, B, seed=sum(widths), b_var=1.0)
+    w = {l: net.w(l).astype(np.float64) * 2.0 for l in range(2, L + 1)}
+    b = {l: net.b(l).astype(np.float64) for l in range(2, L + 1)}
+    x, y = net.x().astype(np.float64), net.y().astype(np.float64)
+    assert x.shape == (B, widths[0]) and y.shape == (B, widths[-1])
+    a, delta, nb, nw, _ = O.full_pass(w, b, x, y, L)
+    h = 1e-6
+    worst = 0.0
+    for l in range(2, L + 1):
+        assert w[l].shape == (widths[l - 1], widths[l - 2]) == nw[l].shape
+        assert a[l].shape == delta[l].shape == (B, widths[l - 1]) and nb[l].shape == (widths[l - 1],)
+        for j in range(widths[l - 1]):
+            for k in range(widths[l - 2]):
+                w0 = w[l][j, k]
+                w[l][j, k] = w0 + h
+                cp = _C(w, b, x, y, L)
+                w[l][j, k] = w0 - h
+                cm = _C(w, b, x, y, L)
+                w[l][j, k] = w0
+                worst = max(worst, abs((cp - cm) / (2 * h) - nw[l][j, k]))
+            b0 = b[l][j]
+            b[l][j] = b0 + h
+            cp = _C(w, b, x, y, L)
+            b[l][j] = b0 - h
+            cm = _C(w, b, x, y, L)
+            b[l][j] = b0
+            worst = max(worst, abs((cp - cm) / (2 * h) - nb[l][j]))
+    assert worst < 2e-9, worst
+
+
+def test_unequal_widths_algorithm1_equals_sequential():
+    """Theorem 1 does not depend on the widths: Algorithm 1 run literally gives the sequential pass's bits."""
+    widths = (6, 3, 8, 2, 5, 4, 7)
+    L = len(widths)
+    net = make_net(L, widths, 2, seed=11)
+    w, b = net.w_by_layer, net.b_by_layer
+    a = O.forward(w, b, net.x(), L)
+    _, nb, nw = O.backward_sequential(w, a, net.y(), L)
+    for k in range(1, L):
+        nb1, nw1, _, writes = O.backward_algorithm1(w, a, net.y(), L, k)
+        assert all(writes[l] == 1 for l in range(2, L + 1))
+        for l in range(2, L + 1):
+            assert np.array_equal(nb[l], nb1[l]) and np.array_equal(nw[l], nw1[l])
+
+
 def test_delta_is_dC_dz():
     """delta^l = dC/dz^l (the definition behind (bp1),(bp2)): perturb b^l, which
     enters z^l additively, one neuron and one layer at a time; B = 1."""
