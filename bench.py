@@ -26,15 +26,16 @@ def matrix_sizes(spec):
     return [spec.width(l) * spec.width(l - 1) for l in range(2, spec.L + 1)]
 
 
-def algorithmic_work(spec):
+def algorithmic_work(spec, sgd=False):
     """Per backward pass.  B = 1: bytes the method must move, 4 bytes per entry of a matrix read or written:
     the chain reads w^{l+1} for l = L-1..2, the workers write nabla_w^l for l = 2..L (vectors are O(N),
-    ignored).  Minibatch: 2 B flops per matrix entry for each chain and each gradient contraction."""
+    ignored).  Minibatch: 2 B flops per matrix entry for each chain and each gradient contraction.
+    sgd: the descent step fused into the workers reads and rewrites w^l instead of writing nabla_w^l."""
     sizes = matrix_sizes(spec)
     every, chain = sum(sizes), sum(sizes[1:])        # the chain never reads w^2
     if spec.B == 1:
         es = 4 if spec.dtype == "f32" else 2
-        return {"bound": "hbm", "bwd": es * chain + 4 * every,
+        return {"bound": "hbm", "bwd": es * chain + (8 if sgd else 4) * every,
                 "fwd": es * every, "unit": "GB/s", "peak": HBM_PEAK_GBS, "scale": 1e9}
     f = 2.0 * spec.B
     return {"bound": "mfma", "bwd": f * (chain + every), "fwd": f * every, "unit": "TFLOP/s",
@@ -123,6 +124,10 @@ def main():
                     help="instead of --config: neurons of layers 1..L, comma-separated (with --batch, --dtype)")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--sgd", type=float, default=0.0,
+                    help="eta > 0: every backward pass applies the descent step (fp32 nets, stream schedule)")
+    ap.add_argument("--sgd-unfused", action="store_true",
+                    help="with --sgd: store the gradients and apply the step with a separate plain torch update, for comparison")
     ap.add_argument("--k", type=int, default=0, help="workers (0 = the configuration's largest k)")
     ap.add_argument("--sched", default="auto", choices=["auto", "streams", "persistent"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -162,11 +167,20 @@ def main():
     g.load(net)
     g.set_schedule({"auto": P.LF_SCHED_AUTO, "streams": P.LF_SCHED_STREAMS,
                     "persistent": P.LF_SCHED_PERSISTENT}[args.sched])
+    fused = args.sgd > 0.0 and not args.sgd_unfused
+    if fused:
+        g.set_sgd(args.sgd)
     torch.cuda.synchronize()
+
+    def backward():
+        g.backward(k)
+        if args.sgd > 0.0 and not fused:      # the plain alternative: gradients through memory, then one update per tensor
+            torch._foreach_add_(g.w, g.nabla_w, alpha=-args.sgd)
+            torch._foreach_add_(g.b, g.nabla_b, alpha=-args.sgd)
 
     for _ in range(warmup):
         g.forward()
-        g.backward(k)
+        backward()
     torch.cuda.synchronize()
 
     # Timed region: exactly `steps` passes.  Events on the stream the passes are enqueued on
@@ -179,7 +193,7 @@ def main():
         ev[i][0].record()
         g.forward()
         ev[i][1].record()
-        g.backward(k)
+        backward()
         ev[i][2].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -195,7 +209,7 @@ def main():
         dst.copy_(src)          # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
 
-    work = algorithmic_work(s)
+    work = algorithmic_work(s, sgd=args.sgd > 0.0)
     achieved = work["bwd"] / (bwd_ms * 1e-3) / work["scale"]
     bwd_list = sorted(e[1].elapsed_time(e[2]) for e in ev)
 
@@ -226,7 +240,8 @@ def main():
             achievable = {"value": 2.0 * 8192 ** 3 / (best * 1e-3) / 1e12, "unit": "TFLOP/s",
                           "what": f"torch.matmul 8192^3 {s.dtype} (vendor library), best of 5"}
             del a_, b_, c_
-    persistent = s.B == 1 and s.dtype == "f32" and s.N <= 4096 and args.sched != "streams" and not s.widths
+    persistent = (s.B == 1 and s.dtype == "f32" and s.N <= 4096 and args.sched != "streams" and not s.widths
+                  and not fused)
     kernel = "k_bwd_persistent (one launch = the whole backward pass)" if persistent else \
         "backward pass (bp1)-(bp4), all kernels"
     out = {
@@ -243,7 +258,9 @@ def main():
         "dtype": s.dtype,
         "data": "synthetic",
         "config": {"workload": f"{s.name}: sigmoid MLP L={s.L} N={s.N} B={s.B} {s.dtype}, k={k}, seed {s.seed}",
-                   "k": k, "schedule": args.sched, "weight_matrices": s.L - 1},
+                   "k": k, "schedule": args.sched, "weight_matrices": s.L - 1,
+                   "descent_step": None if args.sgd <= 0.0 else
+                   {"eta": args.sgd, "how": "fused into the workers" if fused else "separate torch update after the pass"}},
         "fwd_ms": fwd_ms,
         "bwd_ms": bwd_ms,
         "bwd_ms_median": bwd_list[len(bwd_list) // 2],
@@ -260,7 +277,8 @@ def main():
                      "frac_of_achievable": None if achievable is None else achieved / achievable["value"]},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(net, g)
+        # (after descent steps the GPU's weights are no longer the oracle's: no parity figure then)
+        out["cpu_baseline"] = cpu_baseline(net, g if args.sgd <= 0.0 else None)
     print(json.dumps(out), flush=True)
 
 

@@ -116,6 +116,20 @@ lf_status lf_set_schedule(lf_net* net, lf_sched sched);
  * LF_EINVAL unless -126 <= log2_scale <= 127. */
 lf_status lf_set_cost_scale(lf_net* net, int log2_scale);
 
+/* Fuse a plain gradient-descent step into the workers.  The paper ends at the gradients of eqs. (bp3), (bp4);
+ * this is the step that consumes them, taken by the worker that has just formed them so that nabla_w^l is
+ * never written to memory and read back.  With eta > 0 every later lf_backward_leapfrog applies
+ *     w^l <- w^l - eta nabla_w^l,   b^l <- b^l - eta nabla_b^l     (l = 2..L)
+ * in place, in the buffers registered with lf_set_params (which must then be writable), and stores no
+ * gradients: lf_set_grad_buffers is not needed and lf_grads returns LF_ESTATE.  Each gradient entry is
+ * rounded to fp32 as it would have been stored, then applied with one fused multiply-add.  Layer l's step
+ * waits until the chain has read w^l for delta^{l-1}.  After such a pass the stored a^l, delta^l still belong
+ * to the old weights; the next backward pass needs a new lf_forward (else LF_ESTATE).
+ * eta = 0 (default) switches it off.  fp32 storage only (LF_EUNSUPPORTED for bf16).  Both schedules have it;
+ * they form delta^l with different (fixed) summation orders, so the stepped weights of the two agree to
+ * rounding, not bit for bit.  LF_EINVAL unless eta is finite and >= 0. */
+lf_status lf_set_sgd(lf_net* net, float eta);
+
 /* Forward pass, eqs. (x), (z), (a): a^1 = x^1; for l = 2..L
  * z^l = w^l a^{l-1} + b^l, a^l = sigma(z^l).  x1: [B][N] of type dt, aliased as
  * a^1 (it must stay valid and unchanged until the backward pass has finished).

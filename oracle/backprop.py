@@ -36,7 +36,8 @@ weight and bias of tiny nets; an fp64 autograd cross-check; the one-layer
 closed form; the all-zero-weights closed form; the rank-one symmetric net
 whose pass collapses to a scalar recurrence at any N; hand-computed values;
 Algorithm 1 run literally equals the sequential pass bit for bit for every k;
-finite differences and Algorithm 1 = sequential again for unequal widths.
+finite differences and Algorithm 1 = sequential again for unequal widths;
+the descent step by the first-order decrease of C it must produce.
 """
 from __future__ import annotations
 
@@ -194,6 +195,14 @@ def full_pass(w, b, x, y, L: int):
     a = forward(w, b, x, L)
     delta, nb, nw = backward_sequential(w, a, y, L)
     return a, delta, nb, nw, cost(a[L], y)
+
+
+def sgd_step(w, b, nabla_w, nabla_b, eta: float, L: int):
+    """Plain gradient descent, the step that consumes (bp3),(bp4) (the paper itself stops at the gradients):
+    w^l <- w^l - eta nabla_w^l,  b^l <- b^l - eta nabla_b^l  for l = 2..L.  Returns new dicts (w, b)."""
+    w1 = {l: _f64(w[l]) - eta * nabla_w[l] for l in range(2, L + 1)}
+    b1 = {l: _f64(b[l]) - eta * nabla_b[l] for l in range(2, L + 1)}
+    return w1, b1
 
 
 def normwise_error(got, want) -> float:

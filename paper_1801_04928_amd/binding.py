@@ -49,6 +49,7 @@ def lib() -> C.CDLL:
         L.lf_set_grad_buffers.restype, L.lf_set_grad_buffers.argtypes = i, [vp, vpp, vpp]
         L.lf_set_schedule.restype, L.lf_set_schedule.argtypes = i, [vp, i]
         L.lf_set_cost_scale.restype, L.lf_set_cost_scale.argtypes = i, [vp, i]
+        L.lf_set_sgd.restype, L.lf_set_sgd.argtypes = i, [vp, C.c_float]
         L.lf_forward.restype, L.lf_forward.argtypes = i, [vp, vp, vp]
         L.lf_backward_leapfrog.restype, L.lf_backward_leapfrog.argtypes = i, [vp, vp, i, vp]
         L.lf_grads.restype, L.lf_grads.argtypes = i, [vp, i, vpp, vpp]
@@ -110,6 +111,10 @@ def lf_set_schedule(net, sched: int) -> int:
 
 def lf_set_cost_scale(net, log2_scale: int) -> int:
     return lib().lf_set_cost_scale(net, log2_scale)
+
+
+def lf_set_sgd(net, eta: float) -> int:
+    return lib().lf_set_sgd(net, eta)
 
 
 def lf_forward(net, x1: int, hip_stream: int = 0) -> int:
@@ -209,6 +214,9 @@ class LeapfrogNet:
 
     def set_cost_scale(self, log2_scale: int) -> None:
         self._check(lf_set_cost_scale(self.handle, log2_scale))
+
+    def set_sgd(self, eta: float) -> None:
+        self._check(lf_set_sgd(self.handle, eta))
 
     def forward(self) -> None:
         self._check(lf_forward(self.handle, self.x.data_ptr(), self._stream()))

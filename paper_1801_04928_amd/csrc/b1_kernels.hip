@@ -148,12 +148,14 @@ __global__ __launch_bounds__(kThreads) void k_chain_finish(const float* __restri
 // eqs. (bp3),(bp4):  nabla_b[j] = delta[j];  nabla_w[j][k] = delta[j] * a_prev[k]  (rows x cols).
 // Pure store stream.  A wave owns a strip of 256 columns (its a_prev values stay in registers) and
 // RW rows, and writes each row segment with one non-temporal 128-bit store per lane.
-template <int RW>
+// SGD: the gradient-descent step fused into the worker -- `nabla_w` and `nabla_b` are then w^l and b^l
+// themselves and receive w - eta * nabla_w, b - eta * nabla_b (the gradient entry is rounded to fp32 exactly as
+// it would have been stored, then one fused multiply-add); the gradients are not stored.
+template <int RW, bool SGD>
 __global__ __launch_bounds__(kThreads) void k_grad_outer(const float* __restrict__ delta,
                                                          const float* __restrict__ a_prev,
-                                                         float* __restrict__ nabla_w,
-                                                         float* __restrict__ nabla_b, int rows,
-                                                         int cols, int nstrips) {
+                                                         float* nabla_w, float* nabla_b, int rows,
+                                                         int cols, int nstrips, float eta) {
     const int lane = threadIdx.x & (kWave - 1);
     const int gw = blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);   // global wave index
     const int strip = gw % nstrips;
@@ -161,17 +163,40 @@ __global__ __launch_bounds__(kThreads) void k_grad_outer(const float* __restrict
     if (row0 >= rows) return;
     const int col = strip * (kWave * 4) + lane * 4;
     if (strip == 0) {
-        for (int r = lane; r < RW && row0 + r < rows; r += kWave) nabla_b[row0 + r] = delta[row0 + r];
+        for (int r = lane; r < RW && row0 + r < rows; r += kWave) {
+            if constexpr (SGD) nabla_b[row0 + r] = fmaf(-eta, delta[row0 + r], nabla_b[row0 + r]);
+            else nabla_b[row0 + r] = delta[row0 + r];
+        }
     }
     if (col >= cols) return;
     const v4f a = *reinterpret_cast<const v4f*>(a_prev + col);
     float* out = nabla_w + (size_t)row0 * cols + col;
+    if constexpr (SGD) {
+        constexpr int U = 8;                          // rows read ahead
+#pragma unroll 1
+        for (int r0 = 0; r0 < RW; r0 += U) {
+            v4f w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)   // rows past the end re-read the last one; not stored
+                w[u] = *reinterpret_cast<const v4f*>(out + (size_t)(min(row0 + r0 + u, rows - 1) - row0) * cols);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (row0 + r0 + u >= rows) break;
+                const float d = delta[row0 + r0 + u];
+                const v4f g = {d * a.x, d * a.y, d * a.z, d * a.w};
+                const v4f o = {fmaf(-eta, g.x, w[u].x), fmaf(-eta, g.y, w[u].y), fmaf(-eta, g.z, w[u].z),
+                               fmaf(-eta, g.w, w[u].w)};
+                *reinterpret_cast<v4f*>(out + (size_t)(r0 + u) * cols) = o;
+            }
+        }
+    } else {
 #pragma unroll 4
-    for (int r = 0; r < RW; ++r) {
-        if (row0 + r >= rows) break;
-        const float d = delta[row0 + r];
-        const v4f g = {d * a.x, d * a.y, d * a.z, d * a.w};
-        __builtin_nontemporal_store(g, reinterpret_cast<v4f*>(out + (size_t)r * cols));
+        for (int r = 0; r < RW; ++r) {
+            if (row0 + r >= rows) break;
+            const float d = delta[row0 + r];
+            const v4f g = {d * a.x, d * a.y, d * a.z, d * a.w};
+            __builtin_nontemporal_store(g, reinterpret_cast<v4f*>(out + (size_t)r * cols));
+        }
     }
 }
 
@@ -226,12 +251,17 @@ hipError_t launch_chain_gemvT_f32(const float* W_next, const float* delta_next, 
 }
 
 hipError_t launch_grad_outer_f32(const float* delta, const float* a_prev, float* nabla_w,
-                                 float* nabla_b, int rows, int cols, hipStream_t s) {
+                                 float* nabla_b, int rows, int cols, float sgd_eta, hipStream_t s) {
     const int nstrips = ceil_div(cols, kWave * 4);
     constexpr int RW = 16;
     const int waves = nstrips * ceil_div(rows, RW);
-    k_grad_outer<RW><<<ceil_div(waves, kWavesPerWg), kThreads, 0, s>>>(delta, a_prev, nabla_w, nabla_b,
-                                                                      rows, cols, nstrips);
+    const int grid = ceil_div(waves, kWavesPerWg);
+    if (sgd_eta != 0.0f)
+        k_grad_outer<RW, true><<<grid, kThreads, 0, s>>>(delta, a_prev, nabla_w, nabla_b, rows, cols, nstrips,
+                                                         sgd_eta);
+    else
+        k_grad_outer<RW, false><<<grid, kThreads, 0, s>>>(delta, a_prev, nabla_w, nabla_b, rows, cols, nstrips,
+                                                          0.0f);
     return hipGetLastError();
 }
 

@@ -49,6 +49,7 @@ struct GemmArgs {
     const void* act;                       // EPI_SIGMA_PRIME: A_l [M][Nn], type T
     void* out;                             // EPI_SIGMOID: T [M][Nn]; EPI_SIGMA_PRIME / EPI_GRAD: float [M][Nn]
     void* out_bf;                          // EPI_SIGMA_PRIME with bf16: bfloat16 copy of out (or null)
+    float sgd_eta;                         // EPI_GRAD, fp32: != 0 = out is w^l itself and receives w - eta * C
 };
 
 // ---- global -> register staging ---------------------------------------------------------------
@@ -279,7 +280,17 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g) {
                 const int row = 4 * it + (lane >> 4), c4 = (lane & 15) * 4;
                 const v4f v = *reinterpret_cast<const v4f*>(&stage[row * LDE + c4]);
                 const int m = m0 + wm + i * 32 + row, n = n0 + wn + c4;
-                if (m < g.M && n < g.Nn) store_global_nt_v4f(out + (size_t)m * g.Nn + n, v);
+                if (m < g.M && n < g.Nn) {
+                    float* dst = out + (size_t)m * g.Nn + n;
+                    if (g.sgd_eta != 0.0f) {       // the descent step fused in: one more read of the same line
+                        const v4f w = *reinterpret_cast<const v4f*>(dst);
+                        const v4f o = {fmaf(-g.sgd_eta, v.x, w.x), fmaf(-g.sgd_eta, v.y, w.y),
+                                       fmaf(-g.sgd_eta, v.z, w.z), fmaf(-g.sgd_eta, v.w, w.w)};
+                        *reinterpret_cast<v4f*>(dst) = o;
+                    } else {
+                        store_global_nt_v4f(dst, v);
+                    }
+                }
             }
         }
         return;
@@ -552,8 +563,9 @@ __global__ __launch_bounds__(kThreads) void k_split_finish(const float* __restri
 
 // eq. (bp3) for a minibatch: nabla_b[j] = sum_b D[b][j].  A workgroup owns 32 columns; its 8 row groups
 // each add every 8th sample in ascending order, then the 8 partial sums are added in group order.
-__global__ __launch_bounds__(kThreads) void k_bias_grad(const float* __restrict__ D,
-                                                        float* __restrict__ nabla_b, int N, int B) {
+// sgd_eta != 0: nabla_b is b^l itself and receives b - eta * sum.
+__global__ __launch_bounds__(kThreads) void k_bias_grad(const float* __restrict__ D, float* nabla_b, int N,
+                                                        int B, float sgd_eta) {
     __shared__ float s_part[8][32];
     const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
     const int j = blockIdx.x * 32 + c;
@@ -576,7 +588,7 @@ __global__ __launch_bounds__(kThreads) void k_bias_grad(const float* __restrict_
         float t = s_part[0][c];
 #pragma unroll
         for (int q = 1; q < 8; ++q) t += s_part[q][c];
-        nabla_b[j] = t;
+        nabla_b[j] = sgd_eta != 0.0f ? fmaf(-sgd_eta, t, nabla_b[j]) : t;
     }
 }
 
@@ -716,13 +728,15 @@ hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void
 
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
                             float* nabla_b, int n_l, int n_prev, int B, bool bf16, bool big_tiles,
-                            hipStream_t s) {
-    k_bias_grad<<<ceil_div(n_l, 32), kThreads, 0, s>>>(D, nabla_b, n_l, B);
+                            float sgd_eta, hipStream_t s) {
+    if (bf16 && sgd_eta != 0.0f) return hipErrorInvalidValue;   // the fused step exists for fp32 storage only
+    k_bias_grad<<<ceil_div(n_l, 32), kThreads, 0, s>>>(D, nabla_b, n_l, B, sgd_eta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     GemmArgs g{};
     g.ldp = n_l; g.Q = A_prev; g.ldq = n_prev; g.M = n_l; g.Nn = n_prev; g.K = B;
     g.out = nabla_w;
+    g.sgd_eta = sgd_eta;
     if (bf16) {
         g.P = D_bf;
         g.k_tiles_per_split = ceil_div(B, Tile<__bf16>::BK);

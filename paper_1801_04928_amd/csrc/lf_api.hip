@@ -38,6 +38,7 @@ struct Layout {
     size_t tab_off, tab_bytes;       // w, b, nabla_w, nabla_b pointer tables, L-1 entries each
     size_t abort_off;
     size_t counts_off;               // per-workgroup launch counts: 3 x kMaxLaunchGroups words
+    size_t reads_off, reads_words;   // [L-1][kMaxGroups] tagged words: chain workgroup g has finished reading w^l
     size_t total;
 };
 
@@ -117,6 +118,8 @@ Layout make_layout(int L, const int* n, int B, lf_dtype dt) {
         y.tab_off = off; y.tab_bytes = 4 * M * sizeof(void*);         off += align_up(y.tab_bytes);
         y.abort_off = off; off += kAlign;
         y.counts_off = off; off += align_up(3 * lf::kMaxLaunchGroups * sizeof(unsigned));
+        y.reads_words = M * lf::kMaxGroups;
+        y.reads_off = off; off += align_up(y.reads_words * 8);
     }
     y.total = off;
     return y;
@@ -135,6 +138,7 @@ struct lf_net {
     lf_cost cost;
     lf_sched sched;
     float cost_scale;
+    float sgd_eta;                     // != 0: the workers apply the descent step instead of storing gradients
     bool gemm_big;                     // minibatch bf16: the 256 x 256-tile kernel (decided at creation)
     char* ws;
     Layout lay;
@@ -143,6 +147,7 @@ struct lf_net {
     std::vector<float*> gw, gb;
     const void* x1;
     bool have_params, have_grads, fwd_done, bwd_done;
+    bool stepped;                      // a fused descent step has changed the weights since the last forward pass
     std::vector<hipStream_t> workers;
     std::vector<hipEvent_t> ev_delta;  // index l-2
     std::vector<hipEvent_t> ev_done;   // per worker stream
@@ -211,6 +216,7 @@ bool use_persistent(const lf_net* net) {
     if (net->sched == LF_SCHED_STREAMS) return false;
     return persistent_possible(net);
 }
+
 
 // A persistent kernel whose wait gave up has raised the pinned abort word.
 lf_status check_abort(lf_net* net) {
@@ -281,6 +287,7 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.all_off, net->lay.ll_words, 0ull, s));
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.pll_off, net->lay.pll_words, 0ull, s));
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.abort_off, kAlign / 8, 0ull, s));
+        LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.reads_off, net->lay.reads_words, 0ull, s));
         // every workgroup's launch count starts at 1
         LF_HIP(net, lf::launch_fill_u64(net->ws + net->lay.counts_off, 3 * lf::kMaxLaunchGroups / 2,
                                         0x0000000100000001ull, s));
@@ -312,6 +319,9 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     A.GB = net->p_bgroups; A.TPR = net->p_tpr; A.RS = net->p_rs;
     A.GW = net->p_workers;
     A.k = k < net->p_workers ? k : net->p_workers;   // never more partitions than worker workgroups
+    A.sgd_eta = net->sgd_eta;
+    A.workers = (A.k > 1 || A.sgd_eta != 0.0f) ? 1 : 0;
+    A.reads_done = reinterpret_cast<unsigned long long*>(net->ws + net->lay.reads_off);
     A.epoch = 0;                                            // set by the kernel
     A.counts_fwd = reinterpret_cast<unsigned*>(net->ws + net->lay.counts_off);
     A.counts_bwd1 = A.counts_fwd + lf::kMaxLaunchGroups;
@@ -336,18 +346,30 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     return A;
 }
 
-// (bp3),(bp4) of layer l on stream s.
+// (bp3),(bp4) of layer l on stream s; with the descent step fused in, applied to w^l and b^l in place.
 lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
     const int i = l - 2;
+    const bool sgd = net->sgd_eta != 0.0f;
+    float* out_w = sgd ? static_cast<float*>(const_cast<void*>(net->w[i])) : net->gw[i];
+    float* out_b = sgd ? const_cast<float*>(net->b[i]) : net->gb[i];
     if (single_sample_path(net->N, net->B, net->dt)) {
         LF_HIP(net, lf::launch_grad_outer_f32(net->d_ptr(l), static_cast<const float*>(net->a_ptr(l - 1)),
-                                              net->gw[i], net->gb[i], net->width(l), net->width(l - 1), s));
+                                              out_w, out_b, net->width(l), net->width(l - 1), net->sgd_eta, s));
     } else {
-        LF_HIP(net, lf::launch_grad_gemm(net->d_ptr(l), net->dbf_ptr(l), net->a_ptr(l - 1), net->gw[i],
-                                         net->gb[i], net->width(l), net->width(l - 1), net->B,
-                                         net->dt == LF_BF16, net->gemm_big, s));
+        LF_HIP(net, lf::launch_grad_gemm(net->d_ptr(l), net->dbf_ptr(l), net->a_ptr(l - 1), out_w, out_b,
+                                         net->width(l), net->width(l - 1), net->B, net->dt == LF_BF16,
+                                         net->gemm_big, net->sgd_eta, s));
     }
     return LF_OK;
+}
+
+// The same on worker (L - l) mod k, once `ready` (an event recorded on the chain's stream) has passed.
+lf_status enqueue_grads_on_worker(lf_net* net, int l, int k, int nstreams, hipEvent_t ready,
+                                  std::vector<char>& used) {
+    const int j = lf_schedule_worker(net->L, k, l) % nstreams;
+    LF_HIP(net, hipStreamWaitEvent(net->workers[j], ready, 0));
+    used[j] = 1;
+    return enqueue_grads(net, l, net->workers[j]);
 }
 
 }  // namespace
@@ -386,10 +408,11 @@ lf_status lf_create_widths(lf_net** out, int L, const int* n, int B, lf_dtype dt
     net->uniform = all_equal(L, n);
     net->sched = LF_SCHED_AUTO;
     net->cost_scale = 1.0f;
+    net->sgd_eta = 0.0f;
     net->ws = static_cast<char*>(workspace);
     net->lay = make_layout(L, n, B, dt);
     net->x1 = nullptr;
-    net->have_params = net->have_grads = net->fwd_done = net->bwd_done = false;
+    net->have_params = net->have_grads = net->fwd_done = net->bwd_done = net->stepped = false;
     net->gemm_big = lf::gemm_use_big(N, B, dt == LF_BF16);
     net->p_ready = false; net->p_tables_dirty = true; net->p_groups = net->p_rpg = net->p_bgroups = net->p_tpr = 0; net->p_workers = 0;
     net->p_abort_host = nullptr; net->p_abort_dev_view = nullptr;
@@ -477,6 +500,16 @@ lf_status lf_set_cost_scale(lf_net* net, int log2_scale) {
     return LF_OK;
 }
 
+lf_status lf_set_sgd(lf_net* net, float eta) {
+    if (!net) return LF_EINVAL;
+    if (!(eta >= 0.0f) || !std::isfinite(eta)) return fail(net, LF_EINVAL, "lf_set_sgd: need a finite eta >= 0");
+    if (eta != 0.0f && net->dt != LF_F32)
+        return fail(net, LF_EUNSUPPORTED, "lf_set_sgd: the fused step exists for fp32 storage only");
+    net->sgd_eta = eta;
+    net->bwd_done = false;
+    return LF_OK;
+}
+
 lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream) {
     if (!net) return LF_EINVAL;
     if (!x1) return fail(net, LF_EINVAL, "lf_forward: x1 is NULL");
@@ -488,6 +521,7 @@ lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream) {
     net->x1 = x1;
     net->fwd_done = false;
     net->bwd_done = false;
+    net->stepped = false;
     const bool bf = net->dt == LF_BF16;
     if (use_persistent(net)) {
         st0 = prepare_persistent(net, s);
@@ -520,8 +554,11 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
     if (!aligned16(y)) return fail(net, LF_EINVAL, "lf_backward_leapfrog: y must be 16-byte aligned");
     if (k < 1 || k > net->L - 1) return fail(net, LF_EINVAL, "lf_backward_leapfrog: need 1 <= k <= L-1");
     if (!net->have_params) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_params first");
-    if (!net->have_grads) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_grad_buffers first");
+    if (!net->have_grads && net->sgd_eta == 0.0f)
+        return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_grad_buffers first");
     if (!net->fwd_done) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_forward first");
+    if (net->stepped)
+        return fail(net, LF_ESTATE, "lf_backward_leapfrog: the weights have been stepped since lf_forward; run it again");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const int L = net->L, N = net->N, B = net->B;
     const bool bf = net->dt == LF_BF16;
@@ -536,6 +573,7 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
         A.nap = net->p_nap_bwd;
         LF_HIP(net, lf::launch_bwd_persistent(A, s));
         net->bwd_done = true;
+        if (net->sgd_eta != 0.0f) net->stepped = true;
         return LF_OK;
     }
     st = ensure_workers(net, k);
@@ -558,17 +596,20 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
                                               net->d_ptr(l), net->dbf_ptr(l), net->raw(), net->width(l),
                                               net->width(l + 1), B, bf, net->gemm_big, s));
         }
-        // (bp3),(bp4) of layer l, off the chain
+        // (bp3),(bp4) of layer l, off the chain: as soon as delta^l is there.  With the descent step fused in
+        // the worker rewrites w^l, which the chain still reads on its way to delta^{l-1}: layer l's work then
+        // starts once delta^{l-1} is there (layer 2's, whose weights the chain never reads, with delta^2).
+        const bool sgd = net->sgd_eta != 0.0f;
         if (k == 1) {
-            st = enqueue_grads(net, l, s);
+            if (!sgd || l == 2) st = enqueue_grads(net, l, s);
+            if (st == LF_OK && sgd && l < L) st = enqueue_grads(net, l + 1, s);
             if (st != LF_OK) return st;
         } else {
-            const int j = lf_schedule_worker(L, k, l) % nstreams;
             LF_HIP(net, hipEventRecord(net->ev_delta[l - 2], s));
-            LF_HIP(net, hipStreamWaitEvent(net->workers[j], net->ev_delta[l - 2], 0));
-            st = enqueue_grads(net, l, net->workers[j]);
+            if (!sgd || l == 2) st = enqueue_grads_on_worker(net, l, k, nstreams, net->ev_delta[l - 2], used);
+            if (st == LF_OK && sgd && l < L)
+                st = enqueue_grads_on_worker(net, l + 1, k, nstreams, net->ev_delta[l - 2], used);
             if (st != LF_OK) return st;
-            used[j] = 1;
         }
     }
     if (k > 1) {   // join
@@ -579,6 +620,7 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
         }
     }
     net->bwd_done = true;
+    if (net->sgd_eta != 0.0f) net->stepped = true;     // the stored activations belong to the old weights
     return LF_OK;
 }
 
@@ -586,6 +628,8 @@ lf_status lf_grads(lf_net* net, int l, const float** nabla_w, const float** nabl
     if (!net) return LF_EINVAL;
     if (l < 2 || l > net->L) return fail(net, LF_EINVAL, "lf_grads: layer index must be in 2..L");
     if (!net->bwd_done) return fail(net, LF_ESTATE, "lf_grads: no backward pass has been enqueued");
+    if (net->sgd_eta != 0.0f)
+        return fail(net, LF_ESTATE, "lf_grads: with lf_set_sgd the gradients are applied, not stored");
     const lf_status st = check_abort(net);
     if (st != LF_OK) return st;
     if (nabla_w) *nabla_w = net->gw[l - 2];

@@ -22,9 +22,11 @@ hipError_t launch_fwd_gemv_f32(const float* W, const float* b, const float* a_in
 // entries, delta_l and a_l cols; partial: [chain_partial_blocks(rows)][cols]
 hipError_t launch_chain_gemvT_f32(const float* W_next, const float* delta_next, const float* a_l,
                                   float* delta_l, float* partial, int rows, int cols, hipStream_t s);
-// eqs. (bp3),(bp4): nabla_b = delta (rows entries); nabla_w[j][k] = delta[j] a_prev[k] (rows x cols)
+// eqs. (bp3),(bp4): nabla_b = delta (rows entries); nabla_w[j][k] = delta[j] a_prev[k] (rows x cols).
+// sgd_eta != 0: the descent step fused in -- nabla_w and nabla_b are then w^l and b^l themselves and receive
+// w - eta nabla_w, b - eta nabla_b; the gradients are not stored.
 hipError_t launch_grad_outer_f32(const float* delta, const float* a_prev, float* nabla_w,
-                                 float* nabla_b, int rows, int cols, hipStream_t s);
+                                 float* nabla_b, int rows, int cols, float sgd_eta, hipStream_t s);
 
 // ---- any B, either storage type ----------------------------------------------------------------
 
@@ -55,8 +57,10 @@ hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void
                              int n_l, int n_next, int B, bool bf16, bool big_tiles, hipStream_t s);
 // eqs. (bp3),(bp4) for a minibatch: nabla_w[j][k] = sum_b D[b][j] A_prev[b][k] (n_l x n_prev);
 // nabla_b[j] = sum_b D[b][j] (fixed summation order).
+// sgd_eta != 0 (fp32 storage only): the descent step fused into the epilogues -- nabla_w and nabla_b are then
+// w^l and b^l themselves and receive w - eta nabla_w, b - eta nabla_b; the gradients are not stored.
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
                             float* nabla_b, int n_l, int n_prev, int B, bool bf16, bool big_tiles,
-                            hipStream_t s);
+                            float sgd_eta, hipStream_t s);
 
 }  // namespace lf

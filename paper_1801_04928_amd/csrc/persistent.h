@@ -17,7 +17,12 @@ struct PersistArgs {
     int G, RPG;                          // forward: workgroups, rows per workgroup
     int GB, TPR;                         // backward chain: workgroups, float4 column groups per strip
     int RS;                              // backward chain: row blocks per strip (1 = a strip is one workgroup's)
-    int GW, k;                           // gradient worker workgroups (k >= 2), worker partitions
+    int GW, k;                           // gradient worker workgroups, worker partitions
+    int workers;                         // 1 = the grid has gradient worker workgroups (k >= 2, or the descent
+                                         // step is on); 0 = the chain workgroups form the gradients in line
+    float sgd_eta;                       // != 0: the workers apply w -= eta nabla_w, b -= eta nabla_b in place
+    unsigned long long* reads_done;      // [L-1][kMaxGroups] tagged words, row l-2: chain workgroup g has
+                                         // finished reading w^l (written only while the descent step is on)
     unsigned epoch;                      // tag of this launch's words (never 0): filled in by the kernel from its
                                          // workgroup's launch count (see launch_count)
     unsigned* counts_fwd;                // per-workgroup launch counts, kMaxLaunchGroups words each, all starting

@@ -318,7 +318,7 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& A) {
 // ================================================================================================
 constexpr int PG = kMaxPersistentN / 1024;   // float4 column groups a thread covers in a gradient row
 
-// Rows [jb, je) of nabla_w^layer and nabla_b^layer from delta values d[0..n) of rows row..row+n-1.
+// Rows row .. row+n-1 of nabla_w^layer and nabla_b^layer from their delta values d[0..n).
 __device__ __forceinline__ void store_gradient_rows(const PersistArgs& A, int layer, int row, int n,
                                                     const float d[4], const v4f (&ja)[PG]) {
     const int t = threadIdx.x, N = A.N, nvec = N >> 2;
@@ -336,6 +336,42 @@ __device__ __forceinline__ void store_gradient_rows(const PersistArgs& A, int la
                 }
             }
             if (t == 0) store_global_f32(A.gb[layer - 2] + row + c, d[c]);
+        }
+    }
+}
+
+// The same rows with the descent step fused in: w^layer and b^layer are read, stepped and written back in
+// place, the gradient entries (rounded to fp32 as they would have been stored) never reach memory.  The
+// results stay in the caches: the next forward pass reads them.
+__device__ __forceinline__ void step_weight_rows(const PersistArgs& A, int layer, int row, int n,
+                                                 const float d[4], const v4f (&ja)[PG]) {
+    const int t = threadIdx.x, N = A.N, nvec = N >> 2;
+    float* w = const_cast<float*>(A.w[layer - 2]);
+    float* b = const_cast<float*>(A.b[layer - 2]);
+    const float eta = A.sgd_eta;
+    v4f old[4][PG];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int p = 0; p < PG; ++p) {
+            const int v = min(t + kThreads * p, nvec - 1);           // rows and groups past the end re-read
+            old[c][p] = load_global_v4f(w + (size_t)(row + min(c, n - 1)) * N + 4 * v);   // valid ones
+        }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        if (c < n) {
+            float* out = w + (size_t)(row + c) * N;
+#pragma unroll
+            for (int p = 0; p < PG; ++p) {
+                const int v = t + kThreads * p;
+                if (v < nvec) {
+                    const v4f g = {d[c] * ja[p].x, d[c] * ja[p].y, d[c] * ja[p].z, d[c] * ja[p].w};
+                    const v4f o = {fmaf(-eta, g.x, old[c][p].x), fmaf(-eta, g.y, old[c][p].y),
+                                   fmaf(-eta, g.z, old[c][p].z), fmaf(-eta, g.w, old[c][p].w)};
+                    *reinterpret_cast<v4f*>(out + 4 * v) = o;
+                }
+            }
+            if (t == 0) b[row + c] = fmaf(-eta, d[c], b[row + c]);
         }
     }
 }
@@ -361,11 +397,14 @@ __device__ __forceinline__ float ll_wait1(const u64* p, unsigned tag, Abort& ab,
     return 0.0f;
 }
 
-// Gradient workgroup (k >= 2): member of worker partition `part`; streams out its share of rows of
+// Gradient workgroup: member of worker partition `part`; streams out its share of rows of
 // nabla_w^l, nabla_b^l for l = L - part, L - part - k, ... as soon as delta^l's words carry this
 // pass's tag.  It never feeds the chain, so the chain never waits for it.  Each of its rows' words is
 // polled by one thread only (the chain's own gathers read the same lines: every further poller slows
 // them down) and handed to the others through LDS.
+// With the descent step fused in it rewrites w^l, which the chain reads on its way to delta^{l-1}: it then also
+// waits until every chain workgroup has reported the end of its reads of w^l (one tagged word per chain
+// workgroup and layer, each polled by one thread).
 __device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, int nworkers, Abort& ab) {
     __shared__ float s_wd[kThreads];
     __shared__ int s_wdead;
@@ -376,13 +415,18 @@ __device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, i
     if (jb >= je) return;
     if (t == 0) s_wdead = 0;
     __syncthreads();
+    const bool sgd = A.sgd_eta != 0.0f;
     for (int layer = L - part; layer >= 2; layer -= k) {
         v4f ja[PG];
         load_activation_groups(A, layer - 1, ja);
         const u64* dl = A.DLL + (size_t)(layer - 2) * A.ll_layer;
+        bool wait_reads = sgd && layer >= 3;        // the chain never reads w^2
         for (int row0 = jb; row0 < je; row0 += kThreads) {
             const int nb = min(kThreads, je - row0);
             if (t < nb) s_wd[t] = ll_wait1(dl + ll_index(A, row0 + t), A.epoch, ab, abort_code(3, layer, (int)blockIdx.x));
+            if (wait_reads && t < A.GB)
+                ll_wait1(A.reads_done + (size_t)(layer - 2) * kMaxGroups + t, A.epoch, ab, abort_code(3, layer, (int)blockIdx.x));
+            wait_reads = false;
             if (ab.dead) s_wdead = 1;
             __syncthreads();
             if (s_wdead) return;                    // the same for every thread
@@ -390,7 +434,8 @@ __device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, i
                 float d[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c) d[c] = s_wd[min(r + c, nb - 1)];
-                store_gradient_rows(A, layer, row0 + r, min(4, nb - r), d, ja);
+                if (sgd) step_weight_rows(A, layer, row0 + r, min(4, nb - r), d, ja);
+                else store_gradient_rows(A, layer, row0 + r, min(4, nb - r), d, ja);
             }
             __syncthreads();                        // the next batch overwrites s_wd
         }
@@ -426,7 +471,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
     __shared__ const float* s_w[kTableLds];             // w^l pointers (see the forward kernel)
     float* s_delta = reinterpret_cast<float*>(s_delta4);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
-    const int N = A.N, L = A.L, GB = A.GB, k = A.k, nvec = N >> 2;
+    const int N = A.N, L = A.L, GB = A.GB, nvec = N >> 2;
     Abort ab{A.abort_dev, A.abort_host, false, A.spin_limit};
     if (g >= GB) {
         gradient_worker(A, g - GB, (int)gridDim.x - GB, ab);
@@ -568,7 +613,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
     // the time, also across the exchange, without any register copy.
     auto step = [&](v4f (&bufA)[CH], v4f (&bufB)[CH], int l) {
         const float a_l = a_next;
-        if (k == 1) inline_grads(l + 1);
+        if (!A.workers) inline_grads(l + 1);
         const float* W = wptr(l - 1);
         const float* Wn = l > 2 ? wptr(l - 2) : nullptr;
         v4f acc = {0.f, 0.f, 0.f, 0.f};
@@ -597,6 +642,8 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
         acc.w = row_class_sum<TPR>(acc.w);
         if ((lane & 15) < TPR) s_red[wave * 4 + (lane >> 4)][lane & 15] = acc;
         __syncthreads();
+        // every load of w^{l+1} by this workgroup has been used: tell the workers, who are about to rewrite it
+        if (A.sgd_eta != 0.0f && t == 0) ll_store(A.reads_done + (size_t)(l - 1) * kMaxGroups + g, 1.0f, A.epoch);
         if constexpr (SPLIT) {
             // my row block's partial sums of the strip go out; the partials of my share of its columns
             // come in, from every row block (mine included), and are added in row-block order
@@ -637,7 +684,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
     } else {
         for (int l = L - 1; l >= 2; --l) step(buf[0], buf[1], l);
     }
-    if (k == 1) inline_grads(2);
+    if (!A.workers) inline_grads(2);
 }
 
 template <int Q, int RF, bool SINGLE>
@@ -646,13 +693,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArg
     A.epoch = launch_count(args.counts_fwd);
     forward_pass<Q, RF, SINGLE>(A);
 }
-// The backward kernel runs with two grids: chain workgroups only (k = 1), or chain + gradient workers.  Each
-// grid has its own counts; odd tags belong to the first, even tags to the second, so the words of one can
-// never pass for the other's.
+// The backward kernel runs with two grids: chain workgroups only (k = 1 without the descent step), or chain +
+// gradient workers.  Each grid has its own counts; odd tags belong to the first, even tags to the second, so
+// the words of one can never pass for the other's.
 template <int TPR, int CH, bool SINGLE, bool SPLIT>
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArgs args) {
     PersistArgs A = args;
-    if (args.k == 1) A.epoch = 2u * launch_count(args.counts_bwd1) + 1u;
+    if (!args.workers) A.epoch = 2u * launch_count(args.counts_bwd1) + 1u;
     else A.epoch = 2u * launch_count(args.counts_bwdk);
     backward_pass<TPR, CH, SINGLE, SPLIT>(A);
 }
@@ -751,7 +798,9 @@ hipError_t launch_bwd_persistent(const PersistArgs& A, hipStream_t s) {
     if (A.GB > kMaxGroups * 2 || !persistent_supported(A.L, A.N)) return hipErrorInvalidValue;
     if (A.RS != 1 && A.RS != 2 && A.RS != 4) return hipErrorInvalidValue;
     if (A.GB % A.RS != 0 || (4 * A.TPR) % A.RS != 0) return hipErrorInvalidValue;
-    const int grid = A.GB + (A.k > 1 ? A.GW : 0);    // chain workgroups, then the gradient workers
+    if ((A.k > 1 || A.sgd_eta != 0.0f) != (A.workers != 0)) return hipErrorInvalidValue;
+    if (A.GB > kMaxGroups || kMaxGroups > kThreads) return hipErrorInvalidValue;   // one polling thread per chain workgroup
+    const int grid = A.GB + (A.workers ? A.GW : 0);  // chain workgroups, then the gradient workers
     if (grid > kMaxLaunchGroups) return hipErrorInvalidValue;
     switch (A.TPR) {
         case 1: return launch_bwd_tpr<1>(A, grid, s);

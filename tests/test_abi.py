@@ -97,6 +97,25 @@ def test_unequal_widths_workspace_and_create():
     P.lf_destroy(h)
 
 
+def test_sgd_argument_and_state_checks():
+    """lf_set_sgd: eta finite and >= 0; fp32 storage only; available in both schedules."""
+    h = _handle()
+    assert P.lf_set_sgd(h, -1.0) == P.LF_EINVAL
+    assert P.lf_set_sgd(h, float("nan")) == P.LF_EINVAL
+    assert P.lf_set_sgd(h, float("inf")) == P.LF_EINVAL
+    assert P.lf_set_sgd(h, 0.0) == P.LF_OK
+    assert P.lf_set_sgd(h, 0.5) == P.LF_OK
+    assert P.lf_set_schedule(h, P.LF_SCHED_PERSISTENT) == P.LF_OK
+    assert P.lf_set_sgd(h, 0.25) == P.LF_OK
+    assert P.lf_set_schedule(h, P.LF_SCHED_STREAMS) == P.LF_OK
+    assert P.lf_set_sgd(None, 0.5) == P.LF_EINVAL
+    P.lf_destroy(h)
+    hb = _handle(4, 256, 8, P.LF_BF16)
+    assert P.lf_set_sgd(hb, 0.5) == P.LF_EUNSUPPORTED and "fp32" in P.lf_last_error(hb)
+    assert P.lf_set_sgd(hb, 0.0) == P.LF_OK
+    P.lf_destroy(hb)
+
+
 def test_call_order_and_argument_checks():
     h = _handle()
     M = 7

@@ -381,6 +381,91 @@ def test_unequal_layer_widths_outer_product_is_exact():
     _free(g)
 
 
+# ---------------------------------------------------------------- descent step fused into the workers
+@pytest.mark.parametrize("shape,B,k,sched", [
+    ((5, 516), 1, 2, "streams"),                   # single sample, ragged strips
+    ((3, 4100), 1, 1, "streams"),                  # sequential pass; rows read ahead past a ragged end
+    ((260, 1028, 516, 64), 1, 3, "streams"),       # unequal widths
+    ((4, 520), 130, 2, "streams"),                 # minibatch fp32 MFMA epilogue
+    ((264, 520, 136, 392), 70, 1, "streams"),      # minibatch, unequal widths, sequential
+    ((5, 516), 1, 2, "persistent"),                # worker workgroups step the weights behind the chain
+    ((9, 1000), 1, 1, "persistent"),               # k = 1: one partition of workers does every layer
+    ((6, 1028), 1, 5, "persistent"),               # k = L-1
+    ((4, 3076), 1, 3, "persistent"),               # strips in row blocks, several float4 groups per thread
+    ((2, 256), 1, 1, "persistent"),                # no chain step: nothing to wait for
+    ((32, 1024), 1, 8, "persistent"),              # configuration 2's shape: 31 layers stepped behind the chain
+])
+def test_fused_descent_step(shape, B, k, sched):
+    """lf_set_sgd: the pass applies w <- w - eta nabla_w, b <- b - eta nabla_b in place.  Checked (i) against
+    the gradients the same library stores without it -- each entry must be the fp32 value nearest to
+    w - eta g, give or take the double rounding of the host's reference -- which isolates the step from the
+    chain; (ii) against the oracle's step; (iii) for the same bits with another k; (iv) for the call order."""
+    import torch
+    import paper_1801_04928_amd as P
+    from oracle import backprop as O
+    if len(shape) == 2:                            # (L, N); longer tuples are widths
+        L, N = shape
+        widths = [N] * L
+        net = make_net(L, N, B, seed=N + B)
+    else:
+        widths = list(shape)
+        L = len(widths)
+        net = make_net(L, widths, B, seed=sum(widths) + B)
+    g = run_gpu(net, k, sched=SCHEDS[sched])
+    check_against_oracle(net, g)
+    grads_w = [to_np(t).astype(np.float64) for t in g.nabla_w]
+    grads_b = [to_np(t).astype(np.float64) for t in g.nabla_b]
+    eta = float(np.float32(0.1 * np.max(np.abs(net.w(L))) / np.max(np.abs(grads_w[-1]))))
+    g.set_sgd(eta)
+    g.forward()
+    g.backward(k)
+    torch.cuda.synchronize()
+    new_w = [to_np(t).copy() for t in g.w]
+    new_b = [to_np(t).copy() for t in g.b]
+    # (i) the step itself
+    for i in range(L - 1):
+        for new, old, grad in ((new_w[i], net.w(i + 2), grads_w[i]), (new_b[i], net.b(i + 2), grads_b[i])):
+            want = old.astype(np.float64) - eta * grad
+            ulp = np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
+            assert np.all(np.abs(new.astype(np.float64) - want) <= 0.5000001 * ulp + 1e-300), f"layer {i + 2}"
+    # (ii) against the oracle: the applied step, in units of the gradient
+    w, b = net.w_by_layer, net.b_by_layer
+    a = O.forward(w, b, net.x(), L)
+    _, nb, nw = O.backward_sequential(w, a, net.y(), L)
+    w1, b1 = O.sgd_step(w, b, nw, nb, eta, L)
+    for l in range(2, L + 1):
+        for new, old, want, grad in ((new_w[l - 2], net.w(l), w1[l], nw[l]), (new_b[l - 2], net.b(l), b1[l], nb[l])):
+            applied = (old.astype(np.float64) - new.astype(np.float64)) / eta
+            floor = 2.0 ** -23 * float(np.max(np.abs(old))) / eta      # rounding of the stored result
+            assert np.max(np.abs(applied - grad)) <= 1e-5 * np.max(np.abs(grad)) + floor, f"layer {l}"
+            assert np.max(np.abs(new - want)) <= 1e-6 * np.max(np.abs(want))
+    # (iv) stale activations, gradients not stored
+    with pytest.raises(P.LfError) as e:
+        g.backward(k)
+    assert e.value.status == P.LF_ESTATE
+    with pytest.raises(P.LfError) as e:
+        g.grads(2)
+    assert e.value.status == P.LF_ESTATE
+    # the next forward pass runs on the stepped weights
+    c0 = O.cost(a[L], net.y())
+    g.forward()
+    torch.cuda.synchronize()
+    a1 = O.forward(w1, b1, net.x(), L)
+    assert O.normwise_error(to_np(g.activation(L)), a1[L]) <= 1e-5
+    c1 = O.cost(a1[L], net.y())
+    # (iii) another k from the same start gives the same bits
+    if L > 2:
+        g.load(net)
+        g.forward()
+        g.backward(1 if k > 1 else 2)
+        torch.cuda.synchronize()
+        for i in range(L - 1):
+            assert np.array_equal(to_np(g.w[i]).view(np.uint32), new_w[i].view(np.uint32))
+            assert np.array_equal(to_np(g.b[i]).view(np.uint32), new_b[i].view(np.uint32))
+    log(f"fused descent step {shape} B={B} k={k} {sched}: eta {eta:.3g}, cost {c0:.6g} -> {c1:.6g}")
+    _free(g)
+
+
 def test_config1_full():
     net = config_net("cfg1", cache=True)
     g = run_gpu(net, 2)

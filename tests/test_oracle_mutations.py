@@ -65,3 +65,31 @@ def test_unmutated_oracle_passes():
 def test_planted_mistake_is_caught(monkeypatch, name, mutant):
     monkeypatch.setattr(O, name, mutant)
     assert _fd_worst() > 1e-4
+
+
+def _first_order_defect(eta=1e-4, L=4, N=5, B=2, seed=8):
+    """|(C(theta) - C(theta')) / eta - ||g||^2| / ||g||^2 for theta' = the oracle's descent step."""
+    net = make_net(L, N, B, seed=seed, b_var=1.0)
+    w = {l: net.w(l).astype(np.float64) * 3.0 for l in range(2, L + 1)}
+    b = {l: net.b(l).astype(np.float64) for l in range(2, L + 1)}
+    x, y = net.x().astype(np.float64), net.y().astype(np.float64)
+    _, _, nb, nw, c0 = O.full_pass(w, b, x, y, L)
+    g2 = sum(float(np.sum(nw[l] ** 2)) + float(np.sum(nb[l] ** 2)) for l in range(2, L + 1))
+    w1, b1 = O.sgd_step(w, b, nw, nb, eta, L)
+    c1 = O.cost(O.forward(w1, b1, x, L)[L], y)
+    return abs((c0 - c1) / eta - g2) / g2
+
+
+def test_unmutated_descent_step_passes():
+    assert _first_order_defect() < 3e-3
+
+
+@pytest.mark.parametrize("mutant", [
+    lambda w, b, nw, nb, eta, L: ({l: w[l] + eta * nw[l] for l in w}, {l: b[l] - eta * nb[l] for l in b}),   # sign of the weight step
+    lambda w, b, nw, nb, eta, L: ({l: w[l] - eta * nw[l] for l in w}, {l: b[l] for l in b}),                # biases left alone
+    lambda w, b, nw, nb, eta, L: ({l: w[l] - 0.5 * eta * nw[l] for l in w}, {l: b[l] - eta * nb[l] for l in b}),  # a factor
+    lambda w, b, nw, nb, eta, L: ({l: w[l] - eta * nw[l].T for l in w}, {l: b[l] - eta * nb[l] for l in b}),    # transposed gradient
+])
+def test_planted_mistake_in_the_descent_step_is_caught(monkeypatch, mutant):
+    monkeypatch.setattr(O, "sgd_step", mutant)
+    assert _first_order_defect() > 2e-2

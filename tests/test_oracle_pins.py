@@ -349,6 +349,31 @@ def test_vanishing_gradient_rate_of_the_configs_init():
     assert 0.1 < np.exp(np.mean(np.log(ratios))) < 0.45
 
 
+def test_descent_step_decreases_the_cost_to_first_order():
+    """C(w - eta g, b - eta g_b) = C - eta ||g||^2 + O(eta^2): the sign, the pairing of each gradient with its
+    own parameter and the absence of any extra factor are all fixed by this limit."""
+    L, N, B = 4, 6, 3
+    w, b, x, y = _net(L, N, B, seed=3)
+    _, _, nb, nw, c0 = O.full_pass(w, b, x, y, L)
+    g2 = sum(float(np.sum(nw[l] ** 2)) + float(np.sum(nb[l] ** 2)) for l in range(2, L + 1))
+    prev = None
+    for eta in (1e-2, 1e-3, 1e-4):
+        w1, b1 = O.sgd_step(w, b, nw, nb, eta, L)
+        c1 = _C(w1, b1, x, y, L)
+        assert c1 < c0
+        rel = abs((c0 - c1) / eta - g2) / g2
+        assert rel < 30 * eta                      # the remainder is O(eta)
+        assert prev is None or rel < prev
+        prev = rel
+    # a swapped pairing (the bias step taken with the wrong layer's gradient) does not pass
+    nb_wrong = {l: nb[L + 2 - l] for l in range(2, L + 1)}
+    w1, b1 = O.sgd_step(w, b, nw, nb_wrong, 1e-4, L)
+    assert abs((c0 - _C(w1, b1, x, y, L)) / 1e-4 - g2) / g2 > 1e-2
+    # eta = 0 changes nothing; inputs are not modified
+    w0, b0 = O.sgd_step(w, b, nw, nb, 0.0, L)
+    assert all(np.array_equal(w0[l], w[l]) and np.array_equal(b0[l], b[l]) for l in range(2, L + 1))
+
+
 def test_normwise_error():
     assert O.normwise_error([1.0, 2.0], [1.0, 2.0]) == 0.0
     assert O.normwise_error([1.0, 2.5], [1.0, 2.0]) == 0.25
