@@ -137,7 +137,7 @@ def main():
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU only; --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -57,7 +57,7 @@ typedef enum {
     LF_ESTATE = 2,        /* call out of order: parameters/buffers not set, backward before forward */
     LF_ENOMEM = 3,        /* host allocation failed */
     LF_EHIP = 4,          /* a HIP call failed (no device, launch error, ...) */
-    LF_EUNSUPPORTED = 5   /* valid request this build cannot serve */
+    LF_EUNSUPPORTED = 5   /* valid request the library cannot serve */
 } lf_status;
 
 typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
