@@ -240,6 +240,32 @@ def main():
             achievable = {"value": 2.0 * 8192 ** 3 / (best * 1e-3) / 1e12, "unit": "TFLOP/s",
                           "what": f"torch.matmul 8192^3 {s.dtype} (vendor library), best of 5"}
             del a_, b_, c_
+            # the vendor library on this net's own two backward products (widest layer): the chain's
+            # D W (B x N x N) and the gradient's D^T A (N x N x B, fp32 result), one after the other
+            n_ = s.N
+            d_ = torch.randn(s.B, n_, device="cuda", dtype=dt)
+            w_ = torch.randn(n_, n_, device="cuda", dtype=dt)
+            x_ = torch.rand(s.B, n_, device="cuda", dtype=dt)
+
+            def both():
+                d_ @ w_
+                if dt == torch.float32:
+                    d_.t() @ x_
+                else:
+                    torch.mm(d_.t(), x_, out_dtype=torch.float32)
+            try:
+                both()
+                best = 1e9
+                for _ in range(5):
+                    e0.record(); both(); e1.record(); torch.cuda.synchronize()
+                    best = min(best, e0.elapsed_time(e1))
+                achievable["same_shapes"] = {
+                    "value": 4.0 * s.B * n_ * n_ / (best * 1e-3) / 1e12, "unit": "TFLOP/s",
+                    "what": f"torch: (B x N)(N x N) then (N x B)(B x N) -> fp32, B={s.B} N={n_} {s.dtype}, "
+                            "the two products of one backward layer without their epilogues, best of 5"}
+            except Exception as ex:      # an older torch without out_dtype
+                achievable["same_shapes"] = {"value": None, "what": f"not measured: {str(ex)[:80]}"}
+            del d_, w_, x_
     persistent = (s.B == 1 and s.dtype == "f32" and s.N <= 4096 and args.sched != "streams" and not s.widths
                   and not fused)
     kernel = "k_bwd_persistent (one launch = the whole backward pass)" if persistent else \
