@@ -172,10 +172,16 @@ def main():
         g.set_sgd(args.sgd)
     torch.cuda.synchronize()
 
+    masters = [t.float() for t in g.w] if (args.sgd > 0.0 and not fused and s.dtype == "bf16") else None
+
     def backward():
         g.backward(k)
         if args.sgd > 0.0 and not fused:      # the plain alternative: gradients through memory, then one update per tensor
-            torch._foreach_add_(g.w, g.nabla_w, alpha=-args.sgd)
+            if masters is None:
+                torch._foreach_add_(g.w, g.nabla_w, alpha=-args.sgd)
+            else:                             # bf16 storage: fp32 masters stepped, the bf16 weights rewritten from them
+                torch._foreach_add_(masters, g.nabla_w, alpha=-args.sgd)
+                torch._foreach_copy_(g.w, masters)
             torch._foreach_add_(g.b, g.nabla_b, alpha=-args.sgd)
 
     for _ in range(warmup):

@@ -125,10 +125,18 @@ lf_status lf_set_cost_scale(lf_net* net, int log2_scale);
  * rounded to fp32 as it would have been stored, then applied with one fused multiply-add.  Layer l's step
  * waits until the chain has read w^l for delta^{l-1}.  After such a pass the stored a^l, delta^l still belong
  * to the old weights; the next backward pass needs a new lf_forward (else LF_ESTATE).
- * eta = 0 (default) switches it off.  fp32 storage only (LF_EUNSUPPORTED for bf16).  Both schedules have it;
- * they form delta^l with different (fixed) summation orders, so the stepped weights of the two agree to
- * rounding, not bit for bit.  LF_EINVAL unless eta is finite and >= 0. */
+ * eta = 0 (default) switches it off.  Both schedules have it; they form delta^l with different (fixed)
+ * summation orders, so the stepped weights of the two agree to rounding, not bit for bit.
+ * bfloat16 storage: a step of eta nabla_w is mostly below half a unit of a bfloat16 weight, so the step is
+ * taken on fp32 master copies (lf_set_master_weights; LF_ESTATE at the backward pass without them):
+ * master <- master - eta nabla_w in fp32, and w^l is rewritten as the master rounded to nearest even.
+ * LF_EINVAL unless eta is finite and >= 0. */
 lf_status lf_set_sgd(lf_net* net, float eta);
+
+/* Register fp32 master copies of the weights of a bfloat16 net (w32[i]: n_l x n_{l-1} floats for layer i+2,
+ * device memory, caller-owned and caller-initialised, normally with the values w^l was rounded from).  Only
+ * the fused descent step reads and writes them.  LF_EINVAL for an fp32 net, NULL or misaligned pointers. */
+lf_status lf_set_master_weights(lf_net* net, float* const* w32);
 
 /* Forward pass, eqs. (x), (z), (a): a^1 = x^1; for l = 2..L
  * z^l = w^l a^{l-1} + b^l, a^l = sigma(z^l).  x1: [B][N] of type dt, aliased as

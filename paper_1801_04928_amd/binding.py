@@ -50,6 +50,7 @@ def lib() -> C.CDLL:
         L.lf_set_schedule.restype, L.lf_set_schedule.argtypes = i, [vp, i]
         L.lf_set_cost_scale.restype, L.lf_set_cost_scale.argtypes = i, [vp, i]
         L.lf_set_sgd.restype, L.lf_set_sgd.argtypes = i, [vp, C.c_float]
+        L.lf_set_master_weights.restype, L.lf_set_master_weights.argtypes = i, [vp, vpp]
         L.lf_forward.restype, L.lf_forward.argtypes = i, [vp, vp, vp]
         L.lf_backward_leapfrog.restype, L.lf_backward_leapfrog.argtypes = i, [vp, vp, i, vp]
         L.lf_grads.restype, L.lf_grads.argtypes = i, [vp, i, vpp, vpp]
@@ -115,6 +116,10 @@ def lf_set_cost_scale(net, log2_scale: int) -> int:
 
 def lf_set_sgd(net, eta: float) -> int:
     return lib().lf_set_sgd(net, eta)
+
+
+def lf_set_master_weights(net, w32: Optional[Sequence[int]]) -> int:
+    return lib().lf_set_master_weights(net, _ptr_array(w32))
 
 
 def lf_forward(net, x1: int, hip_stream: int = 0) -> int:
@@ -189,6 +194,7 @@ class LeapfrogNet:
         self.nabla_b = [torch.empty(n[l - 1], dtype=f32, device=dev) for l in range(2, L + 1)]
         self.x = torch.empty((B, n[0]), dtype=self.tdtype, device=dev)
         self.y = torch.empty((B, n[L - 1]), dtype=self.tdtype, device=dev)
+        self.master_w = None
         self._check(lf_set_params(self.handle, [t.data_ptr() for t in self.w], [t.data_ptr() for t in self.b]))
         self._check(lf_set_grad_buffers(self.handle, [t.data_ptr() for t in self.nabla_w],
                                         [t.data_ptr() for t in self.nabla_b]))
@@ -206,6 +212,8 @@ class LeapfrogNet:
         for l in range(2, self.L + 1):
             self.w[l - 2].copy_(t.from_numpy(net.w(l)))
             self.b[l - 2].copy_(t.from_numpy(net.b(l)))
+            if self.master_w is not None:
+                self.master_w[l - 2].copy_(t.from_numpy(net.w(l)))
         self.x.copy_(t.from_numpy(net.x()))
         self.y.copy_(t.from_numpy(net.y()))
 
@@ -216,6 +224,11 @@ class LeapfrogNet:
         self._check(lf_set_cost_scale(self.handle, log2_scale))
 
     def set_sgd(self, eta: float) -> None:
+        """Fuse the descent step into later backward passes.  A bf16 net gets fp32 master weights on first
+        use, initialised from the current bf16 weights."""
+        if eta != 0.0 and self.dtype == "bf16" and self.master_w is None:
+            self.master_w = [t.float() for t in self.w]
+            self._check(lf_set_master_weights(self.handle, [t.data_ptr() for t in self.master_w]))
         self._check(lf_set_sgd(self.handle, eta))
 
     def forward(self) -> None:

@@ -48,8 +48,9 @@ struct GemmArgs {
     const float* bias;                     // EPI_SIGMOID: [Nn]
     const void* act;                       // EPI_SIGMA_PRIME: A_l [M][Nn], type T
     void* out;                             // EPI_SIGMOID: T [M][Nn]; EPI_SIGMA_PRIME / EPI_GRAD: float [M][Nn]
-    void* out_bf;                          // EPI_SIGMA_PRIME with bf16: bfloat16 copy of out (or null)
-    float sgd_eta;                         // EPI_GRAD, fp32: != 0 = out is w^l itself and receives w - eta * C
+    void* out_bf;                          // EPI_SIGMA_PRIME with bf16: bfloat16 copy of out (or null);
+                                           // EPI_GRAD with sgd_eta: the bfloat16 weights to rewrite (or null)
+    float sgd_eta;                         // EPI_GRAD: != 0 = out holds w^l in fp32 and receives w - eta * C
 };
 
 // ---- global -> register staging ---------------------------------------------------------------
@@ -287,6 +288,10 @@ __global__ __launch_bounds__(kThreads) void k_gemm(const GemmArgs g) {
                         const v4f o = {fmaf(-g.sgd_eta, v.x, w.x), fmaf(-g.sgd_eta, v.y, w.y),
                                        fmaf(-g.sgd_eta, v.z, w.z), fmaf(-g.sgd_eta, v.w, w.w)};
                         *reinterpret_cast<v4f*>(dst) = o;
+                        if (g.out_bf) {            // bfloat16 storage: the weights the next pass multiplies with
+                            const v4bf ob = {(__bf16)o.x, (__bf16)o.y, (__bf16)o.z, (__bf16)o.w};
+                            *reinterpret_cast<v4bf*>(static_cast<__bf16*>(g.out_bf) + (size_t)m * g.Nn + n) = ob;
+                        }
                     } else {
                         store_global_nt_v4f(dst, v);
                     }
@@ -511,7 +516,17 @@ __global__ __launch_bounds__(kThreadsBig) void k_gemm_big(const GemmArgs g) {
             if (m >= g.M || n >= g.Nn) continue;              // Nn is a multiple of 4
             const size_t o = (size_t)m * g.Nn + n;
             if constexpr (EPI == EPI_GRAD) {
-                store_global_nt_v4f(static_cast<float*>(g.out) + o, v);
+                float* dst = static_cast<float*>(g.out) + o;
+                if (g.sgd_eta != 0.0f) {           // the descent step fused in: fp32 master weights stepped in
+                    const v4f w = *reinterpret_cast<const v4f*>(dst);     // place, the bfloat16 weights rewritten
+                    const v4f s = {fmaf(-g.sgd_eta, v.x, w.x), fmaf(-g.sgd_eta, v.y, w.y),
+                                   fmaf(-g.sgd_eta, v.z, w.z), fmaf(-g.sgd_eta, v.w, w.w)};
+                    *reinterpret_cast<v4f*>(dst) = s;
+                    const v4bf sb = {(__bf16)s.x, (__bf16)s.y, (__bf16)s.z, (__bf16)s.w};
+                    *reinterpret_cast<v4bf*>(static_cast<__bf16*>(g.out_bf) + o) = sb;
+                } else {
+                    store_global_nt_v4f(dst, v);
+                }
             } else if constexpr (EPI == EPI_RAW) {
                 *reinterpret_cast<v4f*>(g.raw + (size_t)blockIdx.z * g.M * g.Nn + o) = v;
             } else if constexpr (EPI == EPI_SIGMOID) {
@@ -728,8 +743,8 @@ hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void
 
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
                             float* nabla_b, int n_l, int n_prev, int B, bool bf16, bool big_tiles,
-                            float sgd_eta, hipStream_t s) {
-    if (bf16 && sgd_eta != 0.0f) return hipErrorInvalidValue;   // the fused step exists for fp32 storage only
+                            float sgd_eta, void* w_bf, hipStream_t s) {
+    if (sgd_eta != 0.0f && bf16 != (w_bf != nullptr)) return hipErrorInvalidValue;
     k_bias_grad<<<ceil_div(n_l, 32), kThreads, 0, s>>>(D, nabla_b, n_l, B, sgd_eta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -737,6 +752,7 @@ hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev
     g.ldp = n_l; g.Q = A_prev; g.ldq = n_prev; g.M = n_l; g.Nn = n_prev; g.K = B;
     g.out = nabla_w;
     g.sgd_eta = sgd_eta;
+    g.out_bf = sgd_eta != 0.0f ? w_bf : nullptr;
     if (bf16) {
         g.P = D_bf;
         g.k_tiles_per_split = ceil_div(B, Tile<__bf16>::BK);

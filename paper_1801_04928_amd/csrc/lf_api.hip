@@ -145,6 +145,8 @@ struct lf_net {
     std::vector<const void*> w;       // index l-2
     std::vector<const float*> b;
     std::vector<float*> gw, gb;
+    std::vector<float*> w32;           // bfloat16 nets: fp32 master copies of w^l for the fused descent step
+    bool have_master;
     const void* x1;
     bool have_params, have_grads, fwd_done, bwd_done;
     bool stepped;                      // a fused descent step has changed the weights since the last forward pass
@@ -349,16 +351,17 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
 // (bp3),(bp4) of layer l on stream s; with the descent step fused in, applied to w^l and b^l in place.
 lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
     const int i = l - 2;
-    const bool sgd = net->sgd_eta != 0.0f;
-    float* out_w = sgd ? static_cast<float*>(const_cast<void*>(net->w[i])) : net->gw[i];
+    const bool sgd = net->sgd_eta != 0.0f, bf = net->dt == LF_BF16;
+    float* out_w = !sgd ? net->gw[i] : (bf ? net->w32[i] : static_cast<float*>(const_cast<void*>(net->w[i])));
     float* out_b = sgd ? const_cast<float*>(net->b[i]) : net->gb[i];
+    void* w_bf = (sgd && bf) ? const_cast<void*>(net->w[i]) : nullptr;
     if (single_sample_path(net->N, net->B, net->dt)) {
         LF_HIP(net, lf::launch_grad_outer_f32(net->d_ptr(l), static_cast<const float*>(net->a_ptr(l - 1)),
                                               out_w, out_b, net->width(l), net->width(l - 1), net->sgd_eta, s));
     } else {
         LF_HIP(net, lf::launch_grad_gemm(net->d_ptr(l), net->dbf_ptr(l), net->a_ptr(l - 1), out_w, out_b,
-                                         net->width(l), net->width(l - 1), net->B, net->dt == LF_BF16,
-                                         net->gemm_big, net->sgd_eta, s));
+                                         net->width(l), net->width(l - 1), net->B, bf, net->gemm_big,
+                                         net->sgd_eta, w_bf, s));
     }
     return LF_OK;
 }
@@ -413,6 +416,7 @@ lf_status lf_create_widths(lf_net** out, int L, const int* n, int B, lf_dtype dt
     net->lay = make_layout(L, n, B, dt);
     net->x1 = nullptr;
     net->have_params = net->have_grads = net->fwd_done = net->bwd_done = net->stepped = false;
+    net->have_master = false;
     net->gemm_big = lf::gemm_use_big(N, B, dt == LF_BF16);
     net->p_ready = false; net->p_tables_dirty = true; net->p_groups = net->p_rpg = net->p_bgroups = net->p_tpr = 0; net->p_workers = 0;
     net->p_abort_host = nullptr; net->p_abort_dev_view = nullptr;
@@ -421,6 +425,7 @@ lf_status lf_create_widths(lf_net** out, int L, const int* n, int B, lf_dtype dt
         net->n.assign(n, n + L);
         net->w.assign(L - 1, nullptr); net->b.assign(L - 1, nullptr);
         net->gw.assign(L - 1, nullptr); net->gb.assign(L - 1, nullptr);
+        net->w32.assign(L - 1, nullptr);
     } catch (...) {
         delete net;
         return fail(nullptr, LF_ENOMEM, "lf_create: out of host memory");
@@ -500,11 +505,23 @@ lf_status lf_set_cost_scale(lf_net* net, int log2_scale) {
     return LF_OK;
 }
 
+lf_status lf_set_master_weights(lf_net* net, float* const* w32) {
+    if (!net) return LF_EINVAL;
+    if (net->dt != LF_BF16)
+        return fail(net, LF_EINVAL, "lf_set_master_weights: fp32 weights are stepped in place; masters belong to bf16 nets");
+    if (!w32) return fail(net, LF_EINVAL, "lf_set_master_weights: NULL pointer array");
+    for (int i = 0; i < net->L - 1; ++i) {
+        if (!w32[i]) return fail(net, LF_EINVAL, "lf_set_master_weights: NULL layer pointer");
+        if (!aligned16(w32[i])) return fail(net, LF_EINVAL, "lf_set_master_weights: pointers must be 16-byte aligned");
+    }
+    for (int i = 0; i < net->L - 1; ++i) net->w32[i] = w32[i];
+    net->have_master = true;
+    return LF_OK;
+}
+
 lf_status lf_set_sgd(lf_net* net, float eta) {
     if (!net) return LF_EINVAL;
     if (!(eta >= 0.0f) || !std::isfinite(eta)) return fail(net, LF_EINVAL, "lf_set_sgd: need a finite eta >= 0");
-    if (eta != 0.0f && net->dt != LF_F32)
-        return fail(net, LF_EUNSUPPORTED, "lf_set_sgd: the fused step exists for fp32 storage only");
     net->sgd_eta = eta;
     net->bwd_done = false;
     return LF_OK;
@@ -556,6 +573,8 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
     if (!net->have_params) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_params first");
     if (!net->have_grads && net->sgd_eta == 0.0f)
         return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_grad_buffers first");
+    if (net->sgd_eta != 0.0f && net->dt == LF_BF16 && !net->have_master)
+        return fail(net, LF_ESTATE, "lf_backward_leapfrog: lf_set_sgd on a bf16 net needs lf_set_master_weights");
     if (!net->fwd_done) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_forward first");
     if (net->stepped)
         return fail(net, LF_ESTATE, "lf_backward_leapfrog: the weights have been stepped since lf_forward; run it again");

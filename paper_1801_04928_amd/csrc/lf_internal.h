@@ -57,10 +57,12 @@ hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void
                              int n_l, int n_next, int B, bool bf16, bool big_tiles, hipStream_t s);
 // eqs. (bp3),(bp4) for a minibatch: nabla_w[j][k] = sum_b D[b][j] A_prev[b][k] (n_l x n_prev);
 // nabla_b[j] = sum_b D[b][j] (fixed summation order).
-// sgd_eta != 0 (fp32 storage only): the descent step fused into the epilogues -- nabla_w and nabla_b are then
-// w^l and b^l themselves and receive w - eta nabla_w, b - eta nabla_b; the gradients are not stored.
+// sgd_eta != 0: the descent step fused into the epilogues -- nabla_w and nabla_b are then w^l (in fp32) and b^l
+// themselves and receive w - eta nabla_w, b - eta nabla_b; the gradients are not stored.  With bfloat16 storage
+// nabla_w is the fp32 master copy of w^l, and w_bf, the bfloat16 weights, are rewritten as its rounding (w_bf
+// is NULL exactly when the storage is fp32).
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
                             float* nabla_b, int n_l, int n_prev, int B, bool bf16, bool big_tiles,
-                            float sgd_eta, hipStream_t s);
+                            float sgd_eta, void* w_bf, hipStream_t s);
 
 }  // namespace lf

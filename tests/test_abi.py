@@ -109,10 +109,16 @@ def test_sgd_argument_and_state_checks():
     assert P.lf_set_sgd(h, 0.25) == P.LF_OK
     assert P.lf_set_schedule(h, P.LF_SCHED_STREAMS) == P.LF_OK
     assert P.lf_set_sgd(None, 0.5) == P.LF_EINVAL
+    # bf16 storage: the step is taken on fp32 master copies, which only such a net may register
+    assert P.lf_set_master_weights(h, [FAKE] * 7) == P.LF_EINVAL and "bf16" in P.lf_last_error(h)
     P.lf_destroy(h)
     hb = _handle(4, 256, 8, P.LF_BF16)
-    assert P.lf_set_sgd(hb, 0.5) == P.LF_EUNSUPPORTED and "fp32" in P.lf_last_error(hb)
-    assert P.lf_set_sgd(hb, 0.0) == P.LF_OK
+    assert P.lf_set_sgd(hb, 0.5) == P.LF_OK
+    assert P.lf_set_master_weights(hb, None) == P.LF_EINVAL
+    assert P.lf_set_master_weights(hb, [FAKE, 0, FAKE]) == P.LF_EINVAL
+    assert P.lf_set_master_weights(hb, [FAKE, FAKE + 4, FAKE]) == P.LF_EINVAL
+    assert P.lf_set_master_weights(hb, [FAKE] * 3) == P.LF_OK
+    assert P.lf_set_master_weights(None, [FAKE] * 3) == P.LF_EINVAL
     P.lf_destroy(hb)
 
 

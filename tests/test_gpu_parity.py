@@ -466,6 +466,55 @@ def test_fused_descent_step(shape, B, k, sched):
     _free(g)
 
 
+@pytest.mark.parametrize("L,N,B,k,big", [(4, 264, 70, 2, "0"), (3, 520, 260, 1, "1")])
+def test_fused_descent_step_bf16_master_weights(monkeypatch, L, N, B, k, big):
+    """bfloat16 storage: the step is taken on fp32 master copies and the bf16 weights are rewritten as their
+    rounding.  Checked against the gradients the library stores without the step (master' is the fp32 value
+    nearest to master - eta g), against the oracle's step within the bf16 tolerance, for w = rne(master')
+    bit for bit, and for the order of calls."""
+    import torch
+    import paper_1801_04928_amd as P
+    from lf_inputs import round_to_bf16
+    from oracle import backprop as O
+    monkeypatch.setenv("LF_GEMM_BIG", big)
+    net = make_net(L, N, B, dtype="bf16", seed=N + B)
+    g = run_gpu(net, k)
+    check_against_oracle(net, g)
+    grads_w = [to_np(t).astype(np.float64) for t in g.nabla_w]
+    grads_b = [to_np(t).astype(np.float64) for t in g.nabla_b]
+    eta = float(np.float32(0.05 * np.max(np.abs(net.w(L))) / np.max(np.abs(grads_w[-1]))))
+    # without master weights the pass refuses
+    st = P.lf_set_sgd(g.handle, eta)
+    assert st == P.LF_OK
+    g.forward()
+    with pytest.raises(P.LfError) as e:
+        g.backward(k)
+    assert e.value.status == P.LF_ESTATE and "master" in str(e.value)
+    g.set_sgd(eta)                       # the binding creates the masters from the bf16 weights
+    g.forward()
+    g.backward(k)
+    torch.cuda.synchronize()
+    w, b = net.w_by_layer, net.b_by_layer
+    a = O.forward(w, b, net.x(), L)
+    _, nb, nw = O.backward_sequential(w, a, net.y(), L)
+    for l in range(2, L + 1):
+        master = to_np(g.master_w[l - 2])
+        want = net.w(l).astype(np.float64) - eta * grads_w[l - 2]
+        ulp = np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
+        assert np.all(np.abs(master.astype(np.float64) - want) <= 0.5000001 * ulp + 1e-300), f"layer {l}"
+        assert np.array_equal(to_np(g.w[l - 2]).view(np.uint32), round_to_bf16(master).view(np.uint32)), f"layer {l}"
+        applied = (net.w(l).astype(np.float64) - master.astype(np.float64)) / eta
+        floor = 2.0 ** -23 * float(np.max(np.abs(net.w(l)))) / eta
+        assert np.max(np.abs(applied - nw[l])) <= 2e-2 * np.max(np.abs(nw[l])) + floor, f"layer {l}"
+        bias = to_np(g.b[l - 2]).astype(np.float64)
+        want_b = net.b(l).astype(np.float64) - eta * grads_b[l - 2]
+        assert np.all(np.abs(bias - want_b) <= 0.5000001 * np.spacing(np.abs(want_b).astype(np.float32)) + 1e-300)
+    with pytest.raises(P.LfError) as e:
+        g.backward(k)
+    assert e.value.status == P.LF_ESTATE
+    _free(g)
+
+
 def test_config1_full():
     net = config_net("cfg1", cache=True)
     g = run_gpu(net, 2)
