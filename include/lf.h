@@ -28,9 +28,10 @@
  *     lf_forward and lf_backward_leapfrog only enqueue work and return; the work
  *     is ordered on that stream: anything enqueued on it afterwards sees the
  *     finished results (the "join" of Algorithm 1).
- *     After the first pass of a handle (which sets the handle up and may synchronise), lf_forward and
- *     lf_backward_leapfrog with LF_SCHED_PERSISTENT consist of kernel launches only and may be recorded in
- *     a HIP graph; a replay gives the same results as the recorded calls would.
+ *     After the first pass of a handle with the same k (which sets the handle up, creates worker streams and
+ *     may synchronise), lf_forward and lf_backward_leapfrog consist of kernel launches, event records and
+ *     event waits only and may be recorded in a HIP graph, with either schedule (the worker streams fork
+ *     from and join hip_stream through events); a replay gives the same results as the recorded calls would.
  *   - Every function returns an lf_status; nothing throws, nothing aborts.
  *     After a non-OK status lf_last_error() describes it.  A handle is not
  *     thread-safe; different handles are independent.

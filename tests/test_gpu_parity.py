@@ -264,6 +264,40 @@ def test_persistent_pass_replays_from_a_hip_graph():
     _free(g)
 
 
+@pytest.mark.parametrize("L,N,B,dtype,k", [(5, 520, 130, "f32", 3), (4, 516, 1, "f32", 2), (4, 520, 260, "bf16", 2)])
+def test_stream_schedule_pass_replays_from_a_hip_graph(L, N, B, dtype, k):
+    """The stream schedule recorded in a HIP graph: the worker streams fork from and join the capturing stream
+    through events, so the whole leapfrogged pass becomes one graph; every replay, with eager passes of the
+    same handle in between, must give the bits of the eager pass."""
+    import paper_1801_04928_amd as P
+    import torch
+    net = make_net(L, N, B, dtype=dtype, seed=5)
+    g = P.LeapfrogNet(L, N, B, dtype)
+    g.load(net)
+    g.set_schedule(P.LF_SCHED_STREAMS)
+    g.forward()
+    g.backward(k)
+    torch.cuda.synchronize()
+    check_against_oracle(net, g)
+    want = [to_np(t).copy() for t in g.nabla_w] + [to_np(t).copy() for t in g.nabla_b]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        g.forward()
+        g.backward(k)
+    for replay in range(3):
+        for t in g.nabla_w + g.nabla_b:
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]
+        for a, b in zip(want, got):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), f"replay {replay} differs"
+        g.forward()
+        g.backward(1 + replay % 2)
+        torch.cuda.synchronize()
+    _free(g)
+
+
 def test_persistent_wait_that_gives_up_is_reported(monkeypatch):
     """Failure handling of the persistent path, forced from the host: with a spin limit of one poll the
     first wait that does not find its data at once gives up.  Every kernel still exits normally; the next
