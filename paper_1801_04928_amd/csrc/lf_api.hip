@@ -9,6 +9,7 @@
 #include "lf_internal.h"
 #include "persistent.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <new>
