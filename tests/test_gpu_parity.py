@@ -549,6 +549,53 @@ def test_fused_descent_step_bf16_master_weights(monkeypatch, L, N, B, k, big):
     _free(g)
 
 
+# ---------------------------------------------------------------- the limits of the shape
+def test_widest_single_sample_net():
+    """N = 16384, the widest net of the single-sample kernels (a 1 GiB matrix per layer; the forward kernel keeps
+    all of a^{l-1} in 64 KiB of LDS)."""
+    net = make_net(3, 16384, 1, seed=16384, cache=False)
+    g = run_gpu(net, 2)
+    rep = check_against_oracle(net, g, sample_tiles=(24, 96), rng=np.random.default_rng(1))
+    log(f"B=1 L=3 N=16384: worst normwise error {rep['worst']:.2e}")
+    _free(g)
+
+
+def test_single_sample_wider_than_the_gemv_kernels_takes_the_matrix_kernels():
+    """Past N = 16384 a single sample runs as a minibatch of one through the MFMA kernels."""
+    net = make_net(2, 16392, 1, seed=3, cache=False)
+    g = run_gpu(net, 1)
+    rep = check_against_oracle(net, g, sample_tiles=(24, 96), rng=np.random.default_rng(2))
+    log(f"B=1 L=2 N=16392: worst normwise error {rep['worst']:.2e}")
+    _free(g)
+
+
+@pytest.mark.parametrize("L,sched", [(1025, "persistent"), (1030, "auto")])
+def test_deepest_nets(L, sched):
+    """L = 1025 is the deepest net of the persistent kernels (their per-layer pointer tables live in LDS); deeper
+    nets take the stream schedule.  delta vanishes by about 4x per layer, so below the top 60 layers the
+    gradients are subnormal or zero and are compared absolutely; the activations are compared at every layer."""
+    import paper_1801_04928_amd as P
+    N = 16
+    net = make_net(L, N, 1, seed=L)
+    g = P.LeapfrogNet(L, N, 1, "f32")
+    g.load(net)
+    if sched == "persistent":
+        g.set_schedule(P.LF_SCHED_PERSISTENT)
+    else:
+        with pytest.raises(P.LfError) as e:
+            g.set_schedule(P.LF_SCHED_PERSISTENT)
+        assert e.value.status == P.LF_EUNSUPPORTED
+    poison_buffers(g)
+    g.forward()
+    g.backward(8)
+    import torch
+    torch.cuda.synchronize()
+    rep = check_against_oracle(net, g)
+    assert len(rep.get("subnormal", [])) < 3 * (L - 1)      # the top layers met the relative bound
+    log(f"L={L} N={N} {sched}: worst {rep['worst']:.2e}, {len(rep.get('subnormal', []))} tensors compared absolutely")
+    _free(g)
+
+
 def test_config1_full():
     net = config_net("cfg1", cache=True)
     g = run_gpu(net, 2)
