@@ -129,7 +129,8 @@ def main():
     ap.add_argument("--sgd-unfused", action="store_true",
                     help="with --sgd: store the gradients and apply the step with a separate plain torch update, for comparison")
     ap.add_argument("--k", type=int, default=0, help="workers (0 = the configuration's largest k)")
-    ap.add_argument("--sched", default="auto", choices=["auto", "streams", "persistent"])
+    ap.add_argument("--sched", default="auto", choices=["auto", "streams", "persistent", "redundant"],
+                    help="redundant = Algorithm 1 as printed: every worker recomputes its own delta chain (B = 1, k <= 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-achievable", action="store_true",
                     help="skip the measurement of the rate plain library kernels reach on this machine")
@@ -166,7 +167,7 @@ def main():
     g = P.LeapfrogNet(s.L, list(s.widths) if s.widths else s.N, s.B, s.dtype)
     g.load(net)
     g.set_schedule({"auto": P.LF_SCHED_AUTO, "streams": P.LF_SCHED_STREAMS,
-                    "persistent": P.LF_SCHED_PERSISTENT}[args.sched])
+                    "persistent": P.LF_SCHED_PERSISTENT, "redundant": P.LF_SCHED_REDUNDANT}[args.sched])
     fused = args.sgd > 0.0 and not args.sgd_unfused
     if fused:
         g.set_sgd(args.sgd)
@@ -272,8 +273,8 @@ def main():
             except Exception as ex:      # an older torch without out_dtype
                 achievable["same_shapes"] = {"value": None, "what": f"not measured: {str(ex)[:80]}"}
             del d_, w_, x_
-    persistent = (s.B == 1 and s.dtype == "f32" and s.N <= 4096 and args.sched != "streams" and not s.widths
-                  and not fused)
+    persistent = (s.B == 1 and s.dtype == "f32" and s.N <= 4096 and args.sched in ("auto", "persistent")
+                  and not s.widths)
     kernel = "k_bwd_persistent (one launch = the whole backward pass)" if persistent else \
         "backward pass (bp1)-(bp4), all kernels"
     out = {

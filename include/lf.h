@@ -71,7 +71,12 @@ typedef enum { LF_COST_QUADRATIC = 0 } lf_cost;
 typedef enum {
     LF_SCHED_AUTO = 0,        /* the library picks (persistent where supported) */
     LF_SCHED_STREAMS = 1,     /* chain on the caller's stream, k worker streams fed by per-layer events */
-    LF_SCHED_PERSISTENT = 2   /* one persistent kernel, k workgroup partitions fed by per-layer ready flags */
+    LF_SCHED_PERSISTENT = 2,  /* one persistent kernel, k workgroup partitions fed by per-layer ready flags */
+    LF_SCHED_REDUNDANT = 3    /* Algorithm 1 as printed, for comparison: the parent (the caller's stream) walks
+                                 the top k layers, then each of k worker streams walks its OWN delta chain down
+                                 from delta^{L-j}, recomputing every delta^l, and forms the gradients of every
+                                 k-th layer.  Single sample, fp32, k <= 8; same results, bit for bit, as
+                                 LF_SCHED_STREAMS (the same kernels); k times the chain's work */
 } lf_sched;
 
 typedef struct lf_net lf_net;   /* opaque handle */
@@ -106,7 +111,8 @@ lf_status lf_set_params(lf_net* net, const void* const* w, const void* const* b)
 lf_status lf_set_grad_buffers(lf_net* net, float* const* nabla_w, float* const* nabla_b);
 
 /* Select the worker realisation for later lf_backward_leapfrog calls.
- * LF_EUNSUPPORTED if the shape/type has no such path. */
+ * LF_EUNSUPPORTED if the shape/type has no such path.  With LF_SCHED_REDUNDANT, lf_backward_leapfrog returns
+ * LF_EUNSUPPORTED for k > 8 or while lf_set_sgd is on. */
 lf_status lf_set_schedule(lf_net* net, lf_sched sched);
 
 /* Multiply the cost by 2^log2_scale (default 0).  Eq. (bp1) then yields 2^log2_scale * delta^L and, since
@@ -168,6 +174,11 @@ lf_status lf_activations(lf_net* net, int l, const void** a_l, const float** del
  * rule of Algorithm 1 extended to the top k layers.  -1 on invalid arguments.
  * Pure host function. */
 int lf_schedule_worker(int L, int k, int l);
+
+/* Who saves layer l's gradients in Algorithm 1 as printed (LF_SCHED_REDUNDANT): the parent for the top k
+ * layers L..L-k+1 (returned as k), thread (L - l) mod k below them.  -1 on invalid arguments.  Pure host
+ * function. */
+int lf_algorithm1_owner(int L, int k, int l);
 
 /* Description of the last failure on this handle (or of the last failed
  * lf_create when net is NULL).  Owned by the library; never NULL. */

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LF_OK, LF_EINVAL, LF_ESTATE, LF_ENOMEM, LF_EHIP, LF_EUNSUPPORTED = range(6)
 LF_F32, LF_BF16 = 0, 1
 LF_COST_QUADRATIC = 0
-LF_SCHED_AUTO, LF_SCHED_STREAMS, LF_SCHED_PERSISTENT = 0, 1, 2
+LF_SCHED_AUTO, LF_SCHED_STREAMS, LF_SCHED_PERSISTENT, LF_SCHED_REDUNDANT = 0, 1, 2, 3
 
 _STATUS_NAMES = {0: "LF_OK", 1: "LF_EINVAL", 2: "LF_ESTATE", 3: "LF_ENOMEM", 4: "LF_EHIP", 5: "LF_EUNSUPPORTED"}
 
@@ -56,6 +56,7 @@ def lib() -> C.CDLL:
         L.lf_grads.restype, L.lf_grads.argtypes = i, [vp, i, vpp, vpp]
         L.lf_activations.restype, L.lf_activations.argtypes = i, [vp, i, vpp, vpp]
         L.lf_schedule_worker.restype, L.lf_schedule_worker.argtypes = i, [i, i, i]
+        L.lf_algorithm1_owner.restype, L.lf_algorithm1_owner.argtypes = i, [i, i, i]
         L.lf_last_error.restype, L.lf_last_error.argtypes = C.c_char_p, [vp]
         L.lf_destroy.restype, L.lf_destroy.argtypes = None, [vp]
         _lib = L
@@ -146,6 +147,10 @@ def lf_activations(net, l: int):
 
 def lf_schedule_worker(L: int, k: int, l: int) -> int:
     return lib().lf_schedule_worker(L, k, l)
+
+
+def lf_algorithm1_owner(L: int, k: int, l: int) -> int:
+    return lib().lf_algorithm1_owner(L, k, l)
 
 
 def lf_last_error(net=None) -> str:

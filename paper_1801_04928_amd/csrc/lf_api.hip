@@ -21,6 +21,7 @@ namespace {
 constexpr size_t kAlign = 256;
 constexpr int kMaxL = 4096;
 constexpr int kMaxWorkerStreams = 32;   // workers beyond this share streams (worker j -> stream j mod 32)
+constexpr int kMaxRedundantWorkers = 8; // LF_SCHED_REDUNDANT: each worker has a delta chain (and scratch) of its own
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -31,6 +32,9 @@ struct Layout {
     size_t d_off, d_stride;          // delta^2..delta^L (fp32)
     size_t dbf_off, dbf_stride;      // bfloat16 copies of delta (bf16 nets only)
     size_t partial_off, partial_bytes;
+    // LF_SCHED_REDUNDANT (single sample): per worker two delta vectors (one layer's and the next's) and a
+    // partial buffer of its own
+    size_t red_off, red_vec_bytes, red_stride;
     size_t raw_off, raw_bytes;
     // persistent single-sample path: tagged-word exchange buffers, pointer tables, abort word
     size_t dll_off, all_off, ll_words;   // [L-1][ll_layer] each
@@ -108,6 +112,12 @@ Layout make_layout(int L, const int* n, int B, lf_dtype dt) {
     y.raw_off = off;
     y.raw_bytes = align_up(raw_floats * 4);
     off += y.raw_bytes;
+    if (single_sample_path(N, B, dt)) {
+        y.red_vec_bytes = align_up((size_t)N * 4);
+        y.red_stride = 2 * y.red_vec_bytes + y.partial_bytes;
+        y.red_off = off;
+        off += kMaxRedundantWorkers * y.red_stride;
+    }
     if (all_equal(L, n) && single_sample_path(N, B, dt) && lf::persistent_supported(L, N)) {
         y.ll_shift = ll_spread_shift();
         y.ll_layer = lf::persistent_ll_layer_words(N, y.ll_shift);
@@ -191,14 +201,14 @@ lf_status fail_hip(lf_net* net, hipError_t e, const char* what) {
         if (e_ != hipSuccess) return fail_hip(net, e_, #call);    \
     } while (0)
 
-lf_status ensure_workers(lf_net* net, int k) {
+// Per-layer events, and `want` worker streams with an end-of-work event each.
+lf_status ensure_worker_streams(lf_net* net, size_t want) {
     const size_t M = (size_t)net->L - 1;
     while (net->ev_delta.size() < M) {
         hipEvent_t e;
         LF_HIP(net, hipEventCreateWithFlags(&e, hipEventDisableTiming));
         net->ev_delta.push_back(e);
     }
-    const size_t want = k > 1 ? (size_t)(k < kMaxWorkerStreams ? k : kMaxWorkerStreams) : 0;
     while (net->workers.size() < want) {
         hipStream_t s;
         LF_HIP(net, hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
@@ -210,13 +220,18 @@ lf_status ensure_workers(lf_net* net, int k) {
     return LF_OK;
 }
 
+// The stream schedule's workers: k streams (none for the sequential pass, which runs on the caller's).
+lf_status ensure_workers(lf_net* net, int k) {
+    return ensure_worker_streams(net, k > 1 ? (size_t)(k < kMaxWorkerStreams ? k : kMaxWorkerStreams) : 0);
+}
+
 bool persistent_possible(const lf_net* net) {
     return net->uniform && single_sample_path(net->N, net->B, net->dt) &&
            lf::persistent_supported(net->L, net->N);
 }
 
 bool use_persistent(const lf_net* net) {
-    if (net->sched == LF_SCHED_STREAMS) return false;
+    if (net->sched == LF_SCHED_STREAMS || net->sched == LF_SCHED_REDUNDANT) return false;
     return persistent_possible(net);
 }
 
@@ -376,6 +391,65 @@ lf_status enqueue_grads_on_worker(lf_net* net, int l, int k, int nstreams, hipEv
     return enqueue_grads(net, l, net->workers[j]);
 }
 
+// Algorithm 1 as printed (single sample).  The parent -- the caller's stream -- applies (bp1) and then
+// (bp2),(bp3),(bp4) down to layer L-k+1; thread j, a stream of its own, starts from delta^{L-j}, walks the rest of
+// the chain by itself and applies (bp3),(bp4) at layers L-k-j, L-2k-j, ...  A thread's delta^l goes to the
+// net's delta^l slot when the thread owns layer l (nobody else writes that slot) and to one of the thread's two
+// private vectors otherwise, so no two streams ever write the same memory.
+lf_status backward_redundant(lf_net* net, const void* y, int k, hipStream_t s) {
+    const int L = net->L;
+    if (k > kMaxRedundantWorkers)
+        return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog: LF_SCHED_REDUNDANT has chains for at most 8 workers");
+    if (net->sgd_eta != 0.0f)
+        return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog: LF_SCHED_REDUNDANT does not take the descent step");
+    lf_status st = ensure_worker_streams(net, (size_t)k);       // a stream per thread, also for k = 1
+    if (st != LF_OK) return st;
+    auto chain = [&](int l, const float* d_next, float* d_l, float* partial, hipStream_t q) -> hipError_t {
+        return lf::launch_chain_gemvT_f32(static_cast<const float*>(net->w[l - 1]), d_next,
+                                          static_cast<const float*>(net->a_ptr(l)), d_l, partial,
+                                          net->width(l + 1), net->width(l), q);
+    };
+    // parent
+    LF_HIP(net, lf::launch_output_error(net->a_ptr(L), y, net->d_ptr(L), nullptr, (size_t)net->width(L), false,
+                                        net->cost_scale, s));
+    st = enqueue_grads(net, L, s);
+    if (st != LF_OK) return st;
+    const int parent_low = L - k + 1 > 2 ? L - k + 1 : 2;        // the parent's lowest layer
+    for (int l = L - 1; l >= parent_low; --l) {
+        LF_HIP(net, chain(l, net->d_ptr(l + 1), net->d_ptr(l), net->partial(), s));
+        st = enqueue_grads(net, l, s);
+        if (st != LF_OK) return st;
+    }
+    if (parent_low == 2) return LF_OK;                           // k = L-1: nothing is left for the threads
+    // fork: the threads' seeds delta^L .. delta^{L-k+1} are all there once the parent is
+    LF_HIP(net, hipEventRecord(net->ev_delta[0], s));
+    for (int j = 0; j < k; ++j) {
+        // thread j's layers are those below the parent's with (L - l) mod k = j; it walks down to the lowest
+        // of them and no further (whole blocks of k layers, as in the algorithm's inner loop)
+        const int lowest = 2 + ((L - j - 2) % k + k) % k;
+        if (lowest > L - k) continue;                             // no layer of its own: the thread does nothing
+        hipStream_t q = net->workers[j];
+        LF_HIP(net, hipStreamWaitEvent(q, net->ev_delta[0], 0));
+        char* mine = net->ws + net->lay.red_off + (size_t)j * net->lay.red_stride;
+        float* vec[2] = {reinterpret_cast<float*>(mine), reinterpret_cast<float*>(mine + net->lay.red_vec_bytes)};
+        float* partial = reinterpret_cast<float*>(mine + 2 * net->lay.red_vec_bytes);
+        const float* cur = net->d_ptr(L - j);
+        for (int l = L - j - 1; l >= lowest; --l) {
+            const bool owned = lf_algorithm1_owner(L, k, l) == j;
+            float* out = owned ? net->d_ptr(l) : vec[l & 1];
+            LF_HIP(net, chain(l, cur, out, partial, q));
+            if (owned) {
+                st = enqueue_grads(net, l, q);
+                if (st != LF_OK) return st;
+            }
+            cur = out;
+        }
+        LF_HIP(net, hipEventRecord(net->ev_done[j], q));
+        LF_HIP(net, hipStreamWaitEvent(s, net->ev_done[j], 0));   // the join
+    }
+    return LF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -487,6 +561,11 @@ lf_status lf_set_schedule(lf_net* net, lf_sched sched) {
         case LF_SCHED_STREAMS:
             net->sched = sched;
             return LF_OK;
+        case LF_SCHED_REDUNDANT:
+            if (!single_sample_path(net->N, net->B, net->dt))
+                return fail(net, LF_EUNSUPPORTED, "lf_set_schedule: Algorithm 1 as printed runs for B = 1, fp32, N <= 16384");
+            net->sched = sched;
+            return LF_OK;
         case LF_SCHED_PERSISTENT:
             if (!persistent_possible(net))
                 return fail(net, LF_EUNSUPPORTED,
@@ -596,6 +675,11 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
         if (net->sgd_eta != 0.0f) net->stepped = true;
         return LF_OK;
     }
+    if (net->sched == LF_SCHED_REDUNDANT) {
+        st = backward_redundant(net, y, k, s);
+        if (st == LF_OK) net->bwd_done = true;
+        return st;
+    }
     st = ensure_workers(net, k);
     if (st != LF_OK) return st;
     const int nstreams = (int)net->workers.size() < k ? (int)net->workers.size() : k;
@@ -669,6 +753,11 @@ lf_status lf_activations(lf_net* net, int l, const void** a_l, const float** del
 int lf_schedule_worker(int L, int k, int l) {
     if (L < 2 || k < 1 || k > L - 1 || l < 2 || l > L) return -1;
     return (L - l) % k;
+}
+
+int lf_algorithm1_owner(int L, int k, int l) {
+    if (L < 2 || k < 1 || k > L - 1 || l < 2 || l > L) return -1;
+    return l > L - k ? k : (L - l) % k;
 }
 
 const char* lf_last_error(const lf_net* net) { return net ? net->err.c_str() : g_create_error.c_str(); }

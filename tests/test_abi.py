@@ -181,6 +181,30 @@ def test_schedule_matches_algorithm1(L):
     assert P.lf_schedule_worker(L, 1, L + 1) == -1
 
 
+@pytest.mark.parametrize("L", [2, 3, 5, 8, 13, 21])
+def test_algorithm1_owner_matches_the_algorithm_run_literally(L):
+    """lf_algorithm1_owner (who saves a layer's gradients under LF_SCHED_REDUNDANT) against the owners recorded
+    by the oracle's literal run of Algorithm 1; LF_SCHED_REDUNDANT exists for single-sample fp32 nets only."""
+    import numpy as np
+    N = 2
+    w = {l: np.zeros((N, N)) for l in range(2, L + 1)}
+    a = {l: np.full((1, N), 0.5) for l in range(1, L + 1)}
+    for k in range(1, L):
+        _, _, owner, writes = O.backward_algorithm1(w, a, np.zeros((1, N)), L, k)
+        assert all(v == 1 for v in writes.values())
+        for l in range(2, L + 1):
+            got = P.lf_algorithm1_owner(L, k, l)
+            assert (got == k and owner[l] == "parent") or got == owner[l], (L, k, l, got, owner[l])
+    assert P.lf_algorithm1_owner(L, 0, 2) == -1 and P.lf_algorithm1_owner(L, L, 2) == -1
+    assert P.lf_algorithm1_owner(L, 1, 1) == -1 and P.lf_algorithm1_owner(L, 1, L + 1) == -1
+    h = _handle()
+    assert P.lf_set_schedule(h, P.LF_SCHED_REDUNDANT) == P.LF_OK
+    P.lf_destroy(h)
+    hb = _handle(4, 256, 8, P.LF_F32)
+    assert P.lf_set_schedule(hb, P.LF_SCHED_REDUNDANT) == P.LF_EUNSUPPORTED
+    P.lf_destroy(hb)
+
+
 def test_forward_without_a_gpu_fails_loudly():
     """No CPU fallback: on a machine without a GPU the pass reports LF_EHIP."""
     import torch

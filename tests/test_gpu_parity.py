@@ -596,6 +596,50 @@ def test_deepest_nets(L, sched):
     _free(g)
 
 
+# ---------------------------------------------------------------- Algorithm 1 as printed
+@pytest.mark.parametrize("shape,k", [
+    ((9, 516), 1),                  # one thread walks everything
+    ((9, 516), 3),
+    ((9, 516), 8),                  # k = L-1: the parent does every layer
+    ((12, 1028), 5),                # some threads stop above layer 2
+    ((260, 1028, 516, 64, 132, 8), 2),   # unequal widths
+    ((4, 4100), 2),
+])
+def test_algorithm1_as_printed(shape, k):
+    """LF_SCHED_REDUNDANT: every worker stream recomputes the delta chain it needs (Algorithm 1).  Theorem 1:
+    the same gradients as the sequential pass -- here the same bits as the stream schedule, whose kernels
+    it uses -- and the oracle's within the fp32 tolerance."""
+    import torch
+    import paper_1801_04928_amd as P
+    if len(shape) == 2:
+        L, N = shape
+        net = make_net(L, N, 1, seed=N + k)
+    else:
+        L = len(shape)
+        net = make_net(L, list(shape), 1, seed=sum(shape) + k)
+    ref = run_gpu(net, min(2, L - 1), sched=P.LF_SCHED_STREAMS)
+    want = [to_np(t).copy() for t in ref.nabla_w] + [to_np(t).copy() for t in ref.nabla_b]
+    _free(ref)
+    g = run_gpu(net, k, sched=P.LF_SCHED_REDUNDANT)
+    rep = check_against_oracle(net, g)
+    got = [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]
+    for a, b in zip(want, got):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    # a second pass (the threads' private vectors are reused), then the limits
+    poison_buffers(g, whole_workspace=False)
+    g.forward()
+    g.backward(k)
+    torch.cuda.synchronize()
+    for a, b in zip(want, [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    if L - 1 > 8:
+        with pytest.raises(P.LfError) as e:
+            g.backward(9)
+        assert e.value.status == P.LF_EUNSUPPORTED
+    log(f"Algorithm 1 as printed {shape} k={k}: worst {rep['worst']:.2e}")
+    _free(g)
+
+
 def test_config1_full():
     net = config_net("cfg1", cache=True)
     g = run_gpu(net, 2)
