@@ -669,6 +669,45 @@ def test_config3_full():
         _free(g)
 
 
+def test_config3_fused_descent_step():
+    """Configuration 3's shape with the descent step on, in the launch configuration the benchmark times
+    (256 chain workgroups in row blocks, 256 worker workgroups, k = 8): the workers rewrite 63 matrices of
+    64 MiB behind the chain.  Layer by layer, every stepped entry must be the fp32 value nearest to
+    w - eta g for the g the library stores without the step (a worker that overwrote w^l before the chain had
+    read it would change delta^{l-1} and with it every layer below)."""
+    import torch
+    import paper_1801_04928_amd as P
+    net = config_net("cfg3", cache=False)
+    s = net.spec
+    g = P.LeapfrogNet(s.L, s.N, 1, "f32")
+    g.load(net)
+    g.set_cost_scale(60)                 # keeps the bottom layers' gradients in the normal range
+    g.forward()
+    g.backward(8)
+    torch.cuda.synchronize()
+    top = float(torch.max(torch.abs(g.nabla_w[-1])))
+    eta = float(np.float32(0.05 * float(torch.max(torch.abs(g.w[-1]))) / top))
+    grads = [t.clone() for t in g.nabla_w]
+    old = [t.clone() for t in g.w]
+    old_b = [to_np(t).copy() for t in g.b]
+    grads_b = [to_np(t).astype(np.float64) for t in g.nabla_b]
+    g.set_sgd(eta)
+    g.forward()
+    g.backward(8)
+    torch.cuda.synchronize()
+    for i in range(s.L - 1):
+        want = to_np(old[i]).astype(np.float64) - eta * to_np(grads[i]).astype(np.float64)
+        ulp = np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
+        bad = np.abs(to_np(g.w[i]).astype(np.float64) - want) > 0.5000001 * ulp + 1e-300
+        assert not bad.any(), f"layer {i + 2}: {int(bad.sum())} entries off"
+        want_b = old_b[i].astype(np.float64) - eta * grads_b[i]
+        assert np.all(np.abs(to_np(g.b[i]).astype(np.float64) - want_b)
+                      <= 0.5000001 * np.spacing(np.abs(want_b).astype(np.float32)) + 1e-300)
+        if (i + 2) % 16 == 0:
+            log(f"  cfg3 fused step: layer {i + 2} checked")
+    _free(g)
+
+
 def test_config4_full_sampled():
     net = config_net("cfg4", cache=True)
     g = run_gpu(net, 4)
