@@ -131,6 +131,8 @@ def main():
     ap.add_argument("--k", type=int, default=0, help="workers (0 = the configuration's largest k)")
     ap.add_argument("--sched", default="auto", choices=["auto", "streams", "persistent", "redundant"],
                     help="redundant = Algorithm 1 as printed: every worker recomputes its own delta chain (B = 1, k <= 8)")
+    ap.add_argument("--event-every", type=int, default=8,
+                    help="small nets: bracket every n-th timed step with HIP events (phase times, roofline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-achievable", action="store_true",
                     help="skip the measurement of the rate plain library kernels reach on this machine")
@@ -190,23 +192,32 @@ def main():
         backward()
     torch.cuda.synchronize()
 
-    # Timed region: exactly `steps` passes.  Events on the stream the passes are enqueued on
-    # (torch's current stream, handed to the library) bracket each backward pass.
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
-           torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    # Timed region: exactly `steps` passes.  Events on the stream the passes are enqueued on (torch's current
+    # stream, handed to the library) bracket the forward and the backward pass of every `every`-th step: an
+    # event record costs a few microseconds of stream time, which is 7 % of a pass of the small nets, so only
+    # a sample of the steps carries them (all steps of the large nets, where they cost nothing).
+    every = max(1, args.event_every) if small else 1
+    marked = [i for i in range(steps) if i % every == every - 1] or [steps - 1]
+    ev = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
+              torch.cuda.Event(enable_timing=True)) for i in marked}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        ev[i][0].record()
-        g.forward()
-        ev[i][1].record()
-        backward()
-        ev[i][2].record()
+        e = ev.get(i)
+        if e is None:
+            g.forward()
+            backward()
+        else:
+            e[0].record()
+            g.forward()
+            e[1].record()
+            backward()
+            e[2].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall = t1 - t0
-    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
-    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev.values()) / len(ev)
+    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev.values()) / len(ev)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
@@ -218,7 +229,7 @@ def main():
 
     work = algorithmic_work(s, sgd=args.sgd > 0.0)
     achieved = work["bwd"] / (bwd_ms * 1e-3) / work["scale"]
-    bwd_list = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    bwd_list = sorted(e[1].elapsed_time(e[2]) for e in ev.values())
 
     # What plain library kernels reach on this machine, for scale (outside the timed region): a 1 GiB
     # device copy for the HBM-bound nets, an 8192^3 torch.matmul in the net's type for the MFMA-bound ones.
@@ -299,6 +310,7 @@ def main():
         "bwd_ms_median": bwd_list[len(bwd_list) // 2],
         "bwd_ms_min": bwd_list[0],
         "bwd_passes_per_s": 1e3 / bwd_ms,
+        "steps_with_events": len(ev),
         "weights_cache_warm": bool(4 * sum(matrix_sizes(s)) * (1 if s.dtype == "f32" else 0.5) < 256e6),
         "roofline": {"bound": work["bound"], "kernel": kernel, "achieved": achieved,
                      "peak": work["peak"], "unit": work["unit"], "frac": achieved / work["peak"],
