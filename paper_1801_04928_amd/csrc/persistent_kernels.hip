@@ -25,6 +25,9 @@
 //                     the gradient out with non-temporal stores while the chain moves on; the chain
 //                     never waits for them.  With k = 1 (the sequential pass) the chain workgroups
 //                     form the gradients in line, before stepping to the next layer.
+//   descent step:     when it is fused in, the workers (present for every k then) read, step and rewrite
+//                     w^l and b^l instead of storing the gradients, once every chain workgroup has
+//                     reported the end of its reads of w^l.
 //
 // Every wait is bounded: a poll that exceeds its spin limit raises an abort word that all loops
 // observe, the kernel drains, and the host reports LF_EHIP with the place of the failed wait.
