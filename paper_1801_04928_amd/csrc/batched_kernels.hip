@@ -555,24 +555,38 @@ static_assert(TK == Tile<__bf16>::BK, "both bf16 kernels count k-tiles of the sa
 static_assert(2 * 2 * ELEMS * 2 <= 160 * 1024, "LDS of one compute unit");
 }  // namespace big
 
-// Split-K second stage: sum the raw partials in split order, then the layer's epilogue.
+// Split-K second stage: sum the raw partials in split order, then the layer's epilogue.  A thread takes four
+// consecutive outputs (one row: every width is a multiple of 4), 16 bytes per load.
 template <typename T, int EPI>
 __global__ __launch_bounds__(kThreads) void k_split_finish(const float* __restrict__ raw, int splits,
                                                            size_t count, int Nn,
                                                            const float* __restrict__ bias,
                                                            const T* __restrict__ act, void* out,
                                                            __bf16* out_bf) {
-    const size_t o = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t o = ((size_t)blockIdx.x * kThreads + threadIdx.x) * 4;
     if (o >= count) return;
-    float v = 0.0f;
-    for (int z = 0; z < splits; ++z) v += raw[(size_t)z * count + o];
+    v4f v = *reinterpret_cast<const v4f*>(raw + o);
+    for (int z = 1; z < splits; ++z) v += *reinterpret_cast<const v4f*>(raw + (size_t)z * count + o);
     if constexpr (EPI == EPI_SIGMOID) {
-        static_cast<T*>(out)[o] = (T)sigmoidf(v + bias[o % Nn]);
+        const v4f bs = *reinterpret_cast<const v4f*>(bias + o % Nn);
+        typedef T v4t __attribute__((ext_vector_type(4)));
+        const v4t r = {(T)sigmoidf(v[0] + bs[0]), (T)sigmoidf(v[1] + bs[1]), (T)sigmoidf(v[2] + bs[2]),
+                       (T)sigmoidf(v[3] + bs[3])};
+        *reinterpret_cast<v4t*>(static_cast<T*>(out) + o) = r;
     } else {
-        const float a = (float)act[o];
-        const float d = v * (a * (1.0f - a));
-        static_cast<float*>(out)[o] = d;
-        if constexpr (sizeof(T) == 2) out_bf[o] = (__bf16)d;
+        typedef T v4t __attribute__((ext_vector_type(4)));
+        const v4t av = *reinterpret_cast<const v4t*>(act + o);
+        v4f d;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float a = (float)av[c];
+            d[c] = v[c] * (a * (1.0f - a));
+        }
+        *reinterpret_cast<v4f*>(static_cast<float*>(out) + o) = d;
+        if constexpr (sizeof(T) == 2) {
+            const v4bf db = {(__bf16)d[0], (__bf16)d[1], (__bf16)d[2], (__bf16)d[3]};
+            *reinterpret_cast<v4bf*>(out_bf + o) = db;
+        }
     }
 }
 
@@ -693,7 +707,7 @@ static hipError_t fwd_impl(const void* W, const float* bias, const void* A_in, v
     }
     if (e != hipSuccess) return e;
     const size_t count = (size_t)B * n_out;
-    k_split_finish<T, EPI_SIGMOID><<<(unsigned)((count + kThreads - 1) / kThreads), kThreads, 0, s>>>(
+    k_split_finish<T, EPI_SIGMOID><<<(unsigned)((count / 4 + kThreads - 1) / kThreads), kThreads, 0, s>>>(
         raw, splits, count, n_out, bias, nullptr, A_out, nullptr);
     return hipGetLastError();
 }
@@ -723,7 +737,7 @@ static hipError_t chain_impl(const void* W_next, const void* D_next_op, const vo
     }
     if (e != hipSuccess) return e;
     const size_t count = (size_t)B * n_l;
-    k_split_finish<T, EPI_SIGMA_PRIME><<<(unsigned)((count + kThreads - 1) / kThreads), kThreads, 0, s>>>(
+    k_split_finish<T, EPI_SIGMA_PRIME><<<(unsigned)((count / 4 + kThreads - 1) / kThreads), kThreads, 0, s>>>(
         raw, splits, count, n_l, nullptr, static_cast<const T*>(A_l), D_l, static_cast<__bf16*>(D_l_bf));
     return hipGetLastError();
 }
