@@ -208,6 +208,19 @@ def test_persistent_row_split_strips_match_oracle(monkeypatch, L, N, k, split):
     _free(g)
 
 
+@pytest.mark.parametrize("L,N,k,groups", [(5, 1024, 2, 16), (4, 2048, 3, 32), (6, 520, 1, 8), (4, 1000, 2, 4)])
+def test_persistent_with_few_workgroups(monkeypatch, L, N, k, groups):
+    """The launch shapes a device with few compute units would get (many rows per forward workgroup, several
+    chunks per wave and layer; wide backward strips), forced through the workgroup-count override."""
+    import paper_1801_04928_amd as P
+    monkeypatch.setenv("LF_PERSISTENT_GROUPS", str(groups))
+    net = make_net(L, N, 1, seed=N + groups)
+    g = run_gpu(net, k, sched=P.LF_SCHED_PERSISTENT)
+    rep = check_against_oracle(net, g)
+    log(f"{groups} workgroups: L={L} N={N} k={k}: worst {rep['worst']:.2e}")
+    _free(g)
+
+
 @pytest.mark.parametrize("stride,nap", [("1024", "0"), ("256", "3")])
 def test_persistent_exchange_layout_and_pause_knobs(monkeypatch, stride, nap):
     """The tuning knobs that change where the exchanged words lie and when they are first polled change
