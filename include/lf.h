@@ -61,22 +61,25 @@ typedef enum {
     LF_EUNSUPPORTED = 5   /* valid request the library cannot serve */
 } lf_status;
 
-typedef enum { LF_F32 = 0, LF_BF16 = 1 } lf_dtype;
+/* (The last enumerator of each input enum only widens its range to that of int, so that a caller's
+ * out-of-range value reaches the library's argument check as a value and not as undefined behaviour.) */
+typedef enum { LF_F32 = 0, LF_BF16 = 1, LF_DTYPE_INT_RANGE = 0x7fffffff } lf_dtype;
 
 /* Cost function C.  The paper leaves C open ("let C be the cost function");
  * quadratic: C = 1/2 sum_b ||a^L_b - y_b||^2, hence nabla_a^L C = a^L - y. */
-typedef enum { LF_COST_QUADRATIC = 0 } lf_cost;
+typedef enum { LF_COST_QUADRATIC = 0, LF_COST_INT_RANGE = 0x7fffffff } lf_cost;
 
 /* How the k workers of section 3 are realised on the one GPU. */
 typedef enum {
     LF_SCHED_AUTO = 0,        /* the library picks (persistent where supported) */
     LF_SCHED_STREAMS = 1,     /* chain on the caller's stream, k worker streams fed by per-layer events */
     LF_SCHED_PERSISTENT = 2,  /* one persistent kernel, k workgroup partitions fed by per-layer ready flags */
-    LF_SCHED_REDUNDANT = 3    /* Algorithm 1 as printed, for comparison: the parent (the caller's stream) walks
+    LF_SCHED_REDUNDANT = 3,   /* Algorithm 1 as printed, for comparison: the parent (the caller's stream) walks
                                  the top k layers, then each of k worker streams walks its OWN delta chain down
                                  from delta^{L-j}, recomputing every delta^l, and forms the gradients of every
                                  k-th layer.  Single sample, fp32, k <= 8; same results, bit for bit, as
                                  LF_SCHED_STREAMS (the same kernels); k times the chain's work */
+    LF_SCHED_INT_RANGE = 0x7fffffff
 } lf_sched;
 
 typedef struct lf_net lf_net;   /* opaque handle */
