@@ -284,6 +284,32 @@ def main():
             except Exception as ex:      # an older torch without out_dtype
                 achievable["same_shapes"] = {"value": None, "what": f"not measured: {str(ex)[:80]}"}
             del d_, w_, x_
+            # and what the matrix cores sustain when nothing else limits them: a loop of matrix instructions
+            # that never leaves the registers, two waves per SIMD on every compute unit
+            try:
+                import ctypes
+                probe = ctypes.CDLL(os.path.join(ROOT, "paper_1801_04928_amd", "libprobe.so"))
+                probe.probe_mfma_loop.restype = ctypes.c_double
+                probe.probe_mfma_loop.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                                  ctypes.c_void_p]
+                sink = torch.zeros(1, device="cuda")
+                cus = torch.cuda.get_device_properties(0).multi_processor_count
+                stream = torch.cuda.current_stream().cuda_stream
+                is_bf = 1 if s.dtype == "bf16" else 0
+                probe.probe_mfma_loop(is_bf, 2 * cus, 2000, sink.data_ptr(), stream)
+                torch.cuda.synchronize()
+                best, flops = 1e9, 0.0
+                for _ in range(3):
+                    e0.record()
+                    flops = probe.probe_mfma_loop(is_bf, 2 * cus, 10000, sink.data_ptr(), stream)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    best = min(best, e0.elapsed_time(e1))
+                achievable["mfma_loop"] = {
+                    "value": flops / (best * 1e-3) / 1e12 if flops > 0 else None, "unit": "TFLOP/s",
+                    "what": f"register-resident loop of 32x32 {s.dtype} matrix instructions on {cus} compute units, best of 3"}
+            except OSError as ex:
+                achievable["mfma_loop"] = {"value": None, "what": f"not measured: {str(ex)[:80]}"}
     persistent = (s.B == 1 and s.dtype == "f32" and s.N <= 4096 and args.sched in ("auto", "persistent")
                   and not s.widths)
     kernel = "k_bwd_persistent (one launch = the whole backward pass)" if persistent else \

@@ -1,5 +1,6 @@
 """Compile the HIP sources into paper_1801_04928_amd/liblf.so for gfx950 (hipcc cross-compiles
-without a GPU).  Run as `python -m paper_1801_04928_amd.build`."""
+without a GPU), and the benchmark's matrix-core probe into libprobe.so.  Run as
+`python -m paper_1801_04928_amd.build`."""
 from __future__ import annotations
 
 import os
@@ -11,6 +12,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblf.so")
 SOURCES = ["lf_api.hip", "b1_kernels.hip", "batched_kernels.hip", "persistent_kernels.hip"]
+PROBE_LIB = os.path.join(HERE, "libprobe.so")      # measurement aid of bench.py, not part of the library
+PROBE_SOURCES = ["peak_probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -27,9 +30,9 @@ def hipcc() -> str:
     return exe
 
 
-def build(verbose: bool = True) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [hipcc(), *FLAGS, "-o", LIB, *srcs]
+def _compile(lib: str, sources, verbose: bool) -> None:
+    srcs = [os.path.join(CSRC, s) for s in sources]
+    cmd = [hipcc(), *FLAGS, "-o", lib, *srcs]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -39,6 +42,11 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose: bool = True) -> str:
+    _compile(LIB, SOURCES, verbose)
+    _compile(PROBE_LIB, PROBE_SOURCES, verbose)
     return LIB
 
 

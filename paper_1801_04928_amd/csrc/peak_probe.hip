@@ -1,0 +1,77 @@
+// Measurement aid for bench.py, not part of the backpropagation library: a loop of matrix instructions that
+// never leaves the registers, on every compute unit, to show what the matrix cores sustain on this machine
+// at the clock they hold under that load (the published peaks are quoted at the maximum clock).
+#include <hip/hip_runtime.h>
+
+namespace {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+constexpr int kThreads = 256;            // 4 waves, one per SIMD
+constexpr int kChains = 4;               // independent accumulators per wave
+
+// Each wave keeps kChains independent chains of 32 x 32 x 16 bfloat16 products going.
+__global__ __launch_bounds__(kThreads) void k_mfma_loop_bf16(int iters, float* sink) {
+    v16f acc[kChains];
+#pragma unroll
+    for (int c = 0; c < kChains; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[c][e] = 0.0f;
+    v8bf a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(0.001f * (float)((threadIdx.x + e) & 7));
+        b[e] = (__bf16)(0.002f * (float)((threadIdx.x + 3 * e) & 7));
+    }
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int c = 0; c < kChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kChains; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[c][e];
+    if (s == 12345.678f) sink[0] = s;     // keeps the loop alive; never true
+}
+
+// The same with 32 x 32 x 2 fp32 products.
+__global__ __launch_bounds__(kThreads) void k_mfma_loop_f32(int iters, float* sink) {
+    v16f acc[kChains];
+#pragma unroll
+    for (int c = 0; c < kChains; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[c][e] = 0.0f;
+    const float a = 0.001f * (float)(threadIdx.x & 7), b = 0.002f * (float)(threadIdx.x & 5);
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int c = 0; c < kChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[c], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kChains; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[c][e];
+    if (s == 12345.678f) sink[0] = s;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Enqueue the loop on `hip_stream`: `groups` workgroups of four waves, each wave issuing 4 * iters matrix
+// instructions.  bf16 != 0: 32 x 32 x 16 bfloat16 (32768 flops each), else 32 x 32 x 2 fp32 (4096 flops each).
+// sink: one float of device memory (never written).  Returns the flops the launch performs, 0 on a bad
+// argument or a failed launch.
+double probe_mfma_loop(int bf16, int groups, int iters, float* sink, void* hip_stream) {
+    if (groups < 1 || groups > 65536 || iters < 1 || !sink) return 0.0;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (bf16) k_mfma_loop_bf16<<<groups, kThreads, 0, s>>>(iters, sink);
+    else k_mfma_loop_f32<<<groups, kThreads, 0, s>>>(iters, sink);
+    if (hipGetLastError() != hipSuccess) return 0.0;
+    const double per = bf16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2;
+    return per * kChains * (double)iters * 4.0 * (double)groups;
+}
+
+}  // extern "C"
