@@ -245,6 +245,33 @@ def main():
                 best = min(best, e0.elapsed_time(e1))
             achievable = {"value": 2.0 * src.numel() * 4 / (best * 1e-3) / 1e9, "unit": "GB/s",
                           "what": "1 GiB device copy (torch), bytes read + written, best of 5"}
+            # plain streaming kernels of this repository (csrc/peak_probe.hip): read only, write only, both at once
+            try:
+                import ctypes
+                probe = ctypes.CDLL(os.path.join(ROOT, "paper_1801_04928_amd", "libprobe.so"))
+                probe.probe_stream.restype = ctypes.c_double
+                probe.probe_stream.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+                src.zero_()
+                sink = torch.zeros(1, device="cuda")
+                cus = torch.cuda.get_device_properties(0).multi_processor_count
+                stream = torch.cuda.current_stream().cuda_stream
+                nbytes = src.numel() * 4
+                for mode, name in ((0, "read"), (1, "write"), (2, "read_and_write")):
+                    best, moved = 1e9, 0.0
+                    for per_cu in (2, 4, 8, 16, 32):            # workgroups per compute unit: the best is reported
+                        for _ in range(3):
+                            e0.record()
+                            moved = probe.probe_stream(mode, per_cu * cus, src.data_ptr(), dst.data_ptr(), nbytes,
+                                                       sink.data_ptr(), stream)
+                            e1.record()
+                            torch.cuda.synchronize()
+                            best = min(best, e0.elapsed_time(e1))
+                    achievable["stream_" + name] = {
+                        "value": moved / (best * 1e-3) / 1e9 if moved > 0 else None, "unit": "GB/s",
+                        "what": "plain 128-bit streaming kernel over 1 GiB per buffer, best launch shape of 5, best of 3"}
+            except OSError as ex:
+                achievable["stream_read"] = {"value": None, "what": f"not measured: {str(ex)[:80]}"}
             del src, dst
         else:
             dt = torch.bfloat16 if s.dtype == "bf16" else torch.float32

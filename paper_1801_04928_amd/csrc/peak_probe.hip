@@ -56,9 +56,69 @@ __global__ __launch_bounds__(kThreads) void k_mfma_loop_f32(int iters, float* si
     if (s == 12345.678f) sink[0] = s;
 }
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// Plain streaming kernels over n float4 vectors, grid-stride, 128-bit accesses: what HBM delivers to kernels
+// that only read, only write (non-temporal stores), or do both at once (even workgroups read the first
+// buffer, odd workgroups write the second).
+__global__ __launch_bounds__(kThreads) void k_stream_read(const v4f* __restrict__ src, size_t n, float* sink) {
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    for (; i + 3 * stride < n; i += 4 * stride) {       // four loads in flight per thread
+        const v4f a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc += (a + b) + (c + d);
+    }
+    for (; i < n; i += stride) acc += src[i];
+    if (acc.x + acc.y + acc.z + acc.w == 12345.678f) sink[0] = acc.x;   // never true for the zero-filled buffer
+}
+
+__global__ __launch_bounds__(kThreads) void k_stream_write(v4f* __restrict__ dst, size_t n) {
+    const v4f v = {1.0f, 2.0f, 3.0f, 4.0f};
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride)
+        __builtin_nontemporal_store(v, dst + i);
+}
+
+__global__ __launch_bounds__(kThreads) void k_stream_read_write(const v4f* __restrict__ src, v4f* __restrict__ dst,
+                                                               size_t n, float* sink) {
+    const size_t stride = (size_t)(gridDim.x / 2) * kThreads;
+    size_t i = (size_t)(blockIdx.x / 2) * kThreads + threadIdx.x;
+    if (blockIdx.x & 1) {
+        const v4f v = {1.0f, 2.0f, 3.0f, 4.0f};
+        for (; i < n; i += stride) __builtin_nontemporal_store(v, dst + i);
+    } else {
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+        for (; i + 3 * stride < n; i += 4 * stride) {
+            const v4f a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+            acc += (a + b) + (c + d);
+        }
+        for (; i < n; i += stride) acc += src[i];
+        if (acc.x + acc.y + acc.z + acc.w == 12345.678f) sink[0] = acc.x;
+    }
+}
+
 }  // namespace
 
 extern "C" {
+
+// Enqueue one streaming kernel over `bytes` bytes (a multiple of 16) of each buffer it uses.  mode 0: read src;
+// 1: write dst; 2: read src and write dst at once.  groups: workgroups of 256 threads (even for mode 2).
+// Returns the bytes the launch moves, 0 on a bad argument or a failed launch.
+double probe_stream(int mode, int groups, const void* src, void* dst, size_t bytes, float* sink, void* hip_stream) {
+    if (groups < 2 || groups > (1 << 20) || bytes < 16 || bytes % 16 != 0 || !sink) return 0.0;
+    if ((mode == 0 || mode == 2) && !src) return 0.0;
+    if ((mode == 1 || mode == 2) && !dst) return 0.0;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const size_t n = bytes / 16;
+    if (mode == 0) k_stream_read<<<groups, kThreads, 0, s>>>(static_cast<const v4f*>(src), n, sink);
+    else if (mode == 1) k_stream_write<<<groups, kThreads, 0, s>>>(static_cast<v4f*>(dst), n);
+    else if (mode == 2) k_stream_read_write<<<groups & ~1, kThreads, 0, s>>>(static_cast<const v4f*>(src),
+                                                                             static_cast<v4f*>(dst), n, sink);
+    else return 0.0;
+    if (hipGetLastError() != hipSuccess) return 0.0;
+    return mode == 2 ? 2.0 * (double)bytes : (double)bytes;
+}
 
 // Enqueue the loop on `hip_stream`: `groups` workgroups of four waves, each wave issuing 4 * iters matrix
 // instructions.  bf16 != 0: 32 x 32 x 16 bfloat16 (32768 flops each), else 32 x 32 x 2 fp32 (4096 flops each).
