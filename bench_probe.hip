@@ -1,4 +1,4 @@
-// Measurement aid for bench.py, not part of the backpropagation library: a loop of matrix instructions that
+// Measurement aid for bench.py, not part of the backpropagation library: plain streaming kernels, and a loop of matrix instructions that
 // never leaves the registers, on every compute unit, to show what the matrix cores sustain on this machine
 // at the clock they hold under that load (the published peaks are quoted at the maximum clock).
 #include <hip/hip_runtime.h>

@@ -34,7 +34,18 @@
  *     from and join hip_stream through events); a replay gives the same results as the recorded calls would.
  *   - Every function returns an lf_status; nothing throws, nothing aborts.
  *     After a non-OK status lf_last_error() describes it.  A handle is not
- *     thread-safe; different handles are independent.
+ *     thread-safe.  Different handles share nothing, with one restriction: the persistent
+ *     kernels (LF_SCHED_PERSISTENT, LF_SCHED_FUSED, and LF_SCHED_AUTO where it picks them: B = 1,
+ *     fp32, equal widths N <= 4096) need every workgroup of a launch resident at once, because the
+ *     workgroups wait for each other.  The library checks at set-up that the idle device holds them
+ *     (the runtime's occupancy figure for the kernel); it cannot see what else runs.  So do not let
+ *     such a pass overlap on the device with another kernel that holds compute units for long
+ *     (another handle's persistent pass on a second stream, other libraries' kernels): enqueue them
+ *     on one stream or order them with events.  If the workgroups starve anyway, every wait is
+ *     bounded: the kernel drains, and the next call on the handle returns LF_EHIP with the place of
+ *     the wait (after seconds, not a hang).  An LF_SCHED_AUTO handle then moves to the stream
+ *     schedule for good and works again from the next lf_forward; a handle set to
+ *     LF_SCHED_PERSISTENT or LF_SCHED_FUSED stays failed (destroy it).
  *   - Shape limits: N a multiple of 4 (fp32) or 8 (bf16) so rows stay 16-byte
  *     aligned; 2 <= L <= 4096; 1 <= B; 1 <= k <= L-1.
  *   - Layers of different widths (lf_create_widths): section 2 fixes N neurons per
@@ -65,8 +76,8 @@ typedef enum {
  * out-of-range value reaches the library's argument check as a value and not as undefined behaviour.) */
 typedef enum { LF_F32 = 0, LF_BF16 = 1, LF_DTYPE_INT_RANGE = 0x7fffffff } lf_dtype;
 
-/* Cost function C.  The paper leaves C open ("let C be the cost function");
- * quadratic: C = 1/2 sum_b ||a^L_b - y_b||^2, hence nabla_a^L C = a^L - y. */
+/* Cost function C.  Section 2 names a cost function without fixing one; the library offers the
+ * quadratic cost C = 1/2 sum_b ||a^L_b - y_b||^2, hence nabla_a^L C = a^L - y. */
 typedef enum { LF_COST_QUADRATIC = 0, LF_COST_INT_RANGE = 0x7fffffff } lf_cost;
 
 /* How the k workers of section 3 are realised on the one GPU. */
@@ -79,8 +90,23 @@ typedef enum {
                                  from delta^{L-j}, recomputing every delta^l, and forms the gradients of every
                                  k-th layer.  Single sample, fp32, k <= 8; same results, bit for bit, as
                                  LF_SCHED_STREAMS (the same kernels); k times the chain's work */
+    LF_SCHED_FUSED = 4,       /* no workers at all, for comparison with leapfrogging (eqs. (bp2), (bp4) and the
+                                 cost analysis of section 4): the persistent chain kernel's thread that
+                                 multiplies an entry of w^{l+1} into delta^l also stores the same entry of
+                                 nabla_w^{l+1} = delta^{l+1} (a^l)^T in the same loop, so reads and writes
+                                 alternate on the chain and f3 is paid there in full.  k is checked and
+                                 otherwise ignored.  Same shapes as LF_SCHED_PERSISTENT; same results, bit for
+                                 bit; not with lf_set_sgd */
     LF_SCHED_INT_RANGE = 0x7fffffff
 } lf_sched;
+
+/* Flags of lf_set_debug_flags. */
+typedef enum {
+    LF_DEBUG_CHAIN_ONLY = 1   /* lf_backward_leapfrog computes the delta chain (bp1), (bp2) alone: no worker runs,
+                                 no nabla_b^l or nabla_w^l is formed, the gradient buffers keep what they held and
+                                 lf_grads returns LF_ESTATE.  A timing aid: this is the term f2 of section 4,
+                                 against which "the gradients are hidden behind the chain" is judged */
+} lf_debug_flag;
 
 typedef struct lf_net lf_net;   /* opaque handle */
 
@@ -115,8 +141,13 @@ lf_status lf_set_grad_buffers(lf_net* net, float* const* nabla_w, float* const* 
 
 /* Select the worker realisation for later lf_backward_leapfrog calls.
  * LF_EUNSUPPORTED if the shape/type has no such path.  With LF_SCHED_REDUNDANT, lf_backward_leapfrog returns
- * LF_EUNSUPPORTED for k > 8 or while lf_set_sgd is on. */
+ * LF_EUNSUPPORTED for k > 8 or while lf_set_sgd is on; with LF_SCHED_FUSED while lf_set_sgd is on. */
 lf_status lf_set_schedule(lf_net* net, lf_sched sched);
+
+/* Set the debug flags (an OR of lf_debug_flag values; 0, the default, clears them).  LF_EINVAL for unknown
+ * bits.  With LF_DEBUG_CHAIN_ONLY a later lf_backward_leapfrog is LF_EUNSUPPORTED while lf_set_sgd is on or
+ * the schedule is LF_SCHED_REDUNDANT. */
+lf_status lf_set_debug_flags(lf_net* net, unsigned flags);
 
 /* Multiply the cost by 2^log2_scale (default 0).  Eq. (bp1) then yields 2^log2_scale * delta^L and, since
  * eqs. (bp2)-(bp4) are linear in delta, every delta^l, nabla_b^l and nabla_w^l comes out multiplied by

@@ -13,7 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LF_OK, LF_EINVAL, LF_ESTATE, LF_ENOMEM, LF_EHIP, LF_EUNSUPPORTED = range(6)
 LF_F32, LF_BF16 = 0, 1
 LF_COST_QUADRATIC = 0
-LF_SCHED_AUTO, LF_SCHED_STREAMS, LF_SCHED_PERSISTENT, LF_SCHED_REDUNDANT = 0, 1, 2, 3
+LF_SCHED_AUTO, LF_SCHED_STREAMS, LF_SCHED_PERSISTENT, LF_SCHED_REDUNDANT, LF_SCHED_FUSED = 0, 1, 2, 3, 4
+LF_DEBUG_CHAIN_ONLY = 1
 
 _STATUS_NAMES = {0: "LF_OK", 1: "LF_EINVAL", 2: "LF_ESTATE", 3: "LF_ENOMEM", 4: "LF_EHIP", 5: "LF_EUNSUPPORTED"}
 
@@ -48,6 +49,7 @@ def lib() -> C.CDLL:
         L.lf_set_params.restype, L.lf_set_params.argtypes = i, [vp, vpp, vpp]
         L.lf_set_grad_buffers.restype, L.lf_set_grad_buffers.argtypes = i, [vp, vpp, vpp]
         L.lf_set_schedule.restype, L.lf_set_schedule.argtypes = i, [vp, i]
+        L.lf_set_debug_flags.restype, L.lf_set_debug_flags.argtypes = i, [vp, C.c_uint]
         L.lf_set_cost_scale.restype, L.lf_set_cost_scale.argtypes = i, [vp, i]
         L.lf_set_sgd.restype, L.lf_set_sgd.argtypes = i, [vp, C.c_float]
         L.lf_set_master_weights.restype, L.lf_set_master_weights.argtypes = i, [vp, vpp]
@@ -109,6 +111,10 @@ def lf_set_grad_buffers(net, nabla_w: Optional[Sequence[int]], nabla_b: Optional
 
 def lf_set_schedule(net, sched: int) -> int:
     return lib().lf_set_schedule(net, sched)
+
+
+def lf_set_debug_flags(net, flags: int) -> int:
+    return lib().lf_set_debug_flags(net, flags)
 
 
 def lf_set_cost_scale(net, log2_scale: int) -> int:
@@ -224,6 +230,9 @@ class LeapfrogNet:
 
     def set_schedule(self, sched: int) -> None:
         self._check(lf_set_schedule(self.handle, sched))
+
+    def set_debug_flags(self, flags: int) -> None:
+        self._check(lf_set_debug_flags(self.handle, flags))
 
     def set_cost_scale(self, log2_scale: int) -> None:
         self._check(lf_set_cost_scale(self.handle, log2_scale))

@@ -1,5 +1,6 @@
 """Compile the HIP sources into paper_1801_04928_amd/liblf.so for gfx950 (hipcc cross-compiles
-without a GPU), and the benchmark's matrix-core probe into libprobe.so.  Run as
+without a GPU), and the benchmark's measurement aid (bench_probe.hip beside bench.py: plain streaming
+kernels and a matrix-instruction loop, no part of the library) into libbench_probe.so.  Run as
 `python -m paper_1801_04928_amd.build`."""
 from __future__ import annotations
 
@@ -12,8 +13,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblf.so")
 SOURCES = ["lf_api.hip", "b1_kernels.hip", "batched_kernels.hip", "persistent_kernels.hip"]
-PROBE_LIB = os.path.join(HERE, "libprobe.so")      # measurement aid of bench.py, not part of the library
-PROBE_SOURCES = ["peak_probe.hip"]
+OBJ_DIR = os.path.join(HERE, "_build")              # object files (not committed)
+ROOT = os.path.dirname(HERE)
+PROBE_LIB = os.path.join(ROOT, "libbench_probe.so")      # measurement aid of bench.py, not part of the library
+PROBE_SOURCES = [os.path.join(ROOT, "bench_probe.hip")]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -30,9 +33,7 @@ def hipcc() -> str:
     return exe
 
 
-def _compile(lib: str, sources, verbose: bool) -> None:
-    srcs = [os.path.join(CSRC, s) for s in sources]
-    cmd = [hipcc(), *FLAGS, "-o", lib, *srcs]
+def _run(cmd, verbose: bool) -> None:
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -42,6 +43,20 @@ def _compile(lib: str, sources, verbose: bool) -> None:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def _compile(lib: str, sources, verbose: bool) -> None:
+    """One object per source file, compiled side by side, then one link."""
+    from concurrent.futures import ThreadPoolExecutor
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    flags = [f for f in FLAGS if f != "-shared"]
+    jobs = []
+    for s in sources:
+        obj = os.path.join(OBJ_DIR, os.path.splitext(os.path.basename(s))[0] + ".o")
+        jobs.append((obj, [hipcc(), *flags, "-c", "-o", obj, os.path.join(CSRC, s)]))
+    with ThreadPoolExecutor(max_workers=min(4, len(jobs))) as pool:
+        list(pool.map(lambda j: _run(j[1], verbose), jobs))
+    _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *[j[0] for j in jobs]], verbose)
 
 
 def build(verbose: bool = True) -> str:

@@ -14,6 +14,9 @@
 namespace lf {
 namespace {
 
+#define LF_CHAIN_HALF_DEFAULT 1
+#define LF_GRAD_HALF_DEFAULT 1
+
 constexpr int kThreads = 256;
 constexpr int BM = 128, BN = 128;          // output tile of a workgroup; 2 x 2 waves of 64 x 64
 
@@ -555,6 +558,212 @@ static_assert(TK == Tile<__bf16>::BK, "both bf16 kernels count k-tiles of the sa
 static_assert(2 * 2 * ELEMS * 2 <= 160 * 1024, "LDS of one compute unit");
 }  // namespace big
 
+// ================================================================================================
+// bf16, large shapes: 128 x 256 tile, 256 threads, two workgroups per compute unit
+// ================================================================================================
+// The leapfrog schedule runs the chain product of one layer beside the gradient products of the layers
+// above it.  The two are complementary -- the chain product is bound by the matrix cores, the gradient
+// product by its N x N fp32 store stream -- but kernels whose workgroups fill a compute unit (the
+// 256 x 256 kernel above: 512 threads, 147 KB of LDS) cannot share one: they take turns.  This kernel is
+// sized for half a compute unit (256 threads, 60 KB of LDS, 256 registers), so that a workgroup of the
+// chain product and one of a gradient product -- or two of one product in different phases -- are
+// resident together: one multiplies while the other stores, loads or waits at a barrier.
+// Same wave tile (64 x 128: 8 matrix instructions per 6 operand fragments), 2 x 2 waves, k-tiles of 32,
+// LDS double-buffered, one barrier per k-tile; tile t is multiplied while tile t+1 goes from registers to
+// the other buffer and tile t+2 is requested.  The epilogues store straight from the accumulators: for a
+// fixed accumulator element the 32 lanes of a half wave hold 32 consecutive columns of one row, a whole
+// 128-byte line of fp32 output.
+namespace half {
+constexpr int kThreadsHalf = 256;
+constexpr int TM = 128, TN = 256, TK = 32;
+constexpr int LDA = TK + 8;                // QC operand in LDS: [i][q]; 80-byte rows: 16 lanes' 16-byte reads
+                                           // fall on 16 different bank groups
+constexpr int LDI_P = TM + 32;             // IC operand in LDS: [q][i], rows 16 banks past a multiple of 64
+constexpr int LDI_Q = TN + 32;
+constexpr int P_ELEMS = TM * LDA > TK * LDI_P ? TM * LDA : TK * LDI_P;
+constexpr int Q_ELEMS = TN * LDA > TK * LDI_Q ? TN * LDA : TK * LDI_Q;
+
+// 16-byte pieces of one operand tile of I rows (of its own index), I / 64 per thread
+template <int I, bool IC> struct StageHalf;
+template <int I> struct StageHalf<I, false> {     // [i][q]: 4 threads cover the 32 q of one row
+    v4f r[I / 64];
+    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int Imax, int Kq, bool live) {
+        const int t = threadIdx.x, qv = (t & 3) * 8;
+#pragma unroll
+        for (int u = 0; u < I / 64; ++u) {
+            const int i = (t >> 2) + 64 * u;
+            const bool ok = live && (i0 + i < Imax) && (q0 + qv < Kq);
+            const unsigned off = ((unsigned)(i0 + i) * (unsigned)ld + (unsigned)(q0 + qv)) * 2u;
+            r[u] = buffer_load_v4f(buf, ok ? off : kOutside);
+        }
+    }
+    __device__ void store(__bf16* s) const {
+        const int t = threadIdx.x, qv = (t & 3) * 8;
+#pragma unroll
+        for (int u = 0; u < I / 64; ++u) *reinterpret_cast<v4f*>(s + ((t >> 2) + 64 * u) * LDA + qv) = r[u];
+    }
+};
+template <int I> struct StageHalf<I, true> {      // [q][i]: I / 8 threads cover the I entries of one q
+    static constexpr int TPQ = I / 8, QPP = kThreadsHalf / TPQ, LDI = I + 32;
+    v4f r[I / 64];
+    __device__ void load(__amdgpu_buffer_rsrc_t buf, int ld, int i0, int q0, int Imax, int Kq, bool live) {
+        const int t = threadIdx.x, iv = (t % TPQ) * 8;
+#pragma unroll
+        for (int u = 0; u < I / 64; ++u) {
+            const int q = t / TPQ + QPP * u;
+            const bool ok = live && (q0 + q < Kq) && (i0 + iv < Imax);
+            const unsigned off = ((unsigned)(q0 + q) * (unsigned)ld + (unsigned)(i0 + iv)) * 2u;
+            r[u] = buffer_load_v4f(buf, ok ? off : kOutside);
+        }
+    }
+    __device__ void store(__bf16* s) const {
+        const int t = threadIdx.x, iv = (t % TPQ) * 8;
+#pragma unroll
+        for (int u = 0; u < I / 64; ++u) *reinterpret_cast<v4f*>(s + (t / TPQ + QPP * u) * LDI + iv) = r[u];
+    }
+};
+
+// Issue order of one k-tile's block (see big::interleave_from): 16 matrix instructions in two k = 16 steps;
+// the second step's operands are read from LDS during the first; each of the six staged vectors is written
+// to LDS and requested again back to back, one LDS write or one request after every matrix instruction.
+template <int R, int I>
+__device__ __forceinline__ void interleave_from() {
+    if constexpr (I < 16) {
+        constexpr int step = I / 8, m = I % 8, per = (R + 7) / 8;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if constexpr (step < 1 && m * per < R) __builtin_amdgcn_sched_group_barrier(0x100, per, 0);
+        if constexpr (I >= 1 && I <= 12 && I % 2 == 1) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        if constexpr (I >= 1 && I <= 12 && I % 2 == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        interleave_from<R, I + 1>();
+    }
+}
+template <bool P_IC, bool Q_IC>
+__device__ __forceinline__ void interleave() {
+    constexpr int R = (P_IC ? 4 : 2) + (Q_IC ? 8 : 4);
+    __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
+    interleave_from<R, 0>();
+}
+
+template <bool P_IC, bool Q_IC, int EPI>
+__global__ __launch_bounds__(kThreadsHalf, 2) void k_gemm_half(const GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) __bf16 s_p0[P_ELEMS];
+    __shared__ __attribute__((aligned(16))) __bf16 s_q0[Q_ELEMS];
+    __shared__ __attribute__((aligned(16))) __bf16 s_p1[P_ELEMS];
+    __shared__ __attribute__((aligned(16))) __bf16 s_q1[Q_ELEMS];
+
+    // (Workgroups are dealt to the 8 XCDs, each with an L2 of its own, round-robin by linear index, x fastest.
+    // With a multiple of 8 tile columns an XCD therefore owns every 8th tile column and walks it row by row:
+    // the workgroups resident on it together share a few operand tiles of either kind, which its L2 holds.)
+    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
+    const int r32 = lane & 31, half = lane >> 5;
+
+    const int kt_total = ceil_div(g.K, TK);
+    const int kt_begin = blockIdx.z * g.k_tiles_per_split;
+    const int kt_end = min(kt_total, kt_begin + g.k_tiles_per_split);
+    const int T = kt_end - kt_begin;
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    StageHalf<TM, P_IC> sp;
+    StageHalf<TN, Q_IC> sq;
+    const __amdgpu_buffer_rsrc_t P = make_buffer(g.P, g.p_bytes);
+    const __amdgpu_buffer_rsrc_t Q = make_buffer(g.Q, g.q_bytes);
+    auto request = [&](int t) {       // tiles past the end load zeros: no branch around a request
+        sp.load(P, g.ldp, m0, (kt_begin + t) * TK, g.M, g.K, t < T);
+        sq.load(Q, g.ldq, n0, (kt_begin + t) * TK, g.Nn, g.K, t < T);
+    };
+    auto multiply = [&](const __bf16* tp, const __bf16* tq) {
+#pragma unroll
+        for (int kk = 0; kk < TK; kk += 16) {
+            v8bf a[2], b[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                if constexpr (P_IC) a[i] = lds_operand_transposed(tp, LDI_P, wm + i * 32, kk);
+                else a[i] = *reinterpret_cast<const v8bf*>(&tp[(wm + i * 32 + r32) * LDA + kk + half * 8]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (Q_IC) b[j] = lds_operand_transposed(tq, LDI_Q, wn + j * 32, kk);
+                else b[j] = *reinterpret_cast<const v8bf*>(&tq[(wn + j * 32 + r32) * LDA + kk + half * 8]);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    };
+    auto tile_block = [&](const __bf16* cur_p, const __bf16* cur_q, __bf16* nxt_p, __bf16* nxt_q, int t) {
+        sp.store(nxt_p);
+        sq.store(nxt_q);
+        request(t + 2);
+        multiply(cur_p, cur_q);
+        interleave<P_IC, Q_IC>();
+        __syncthreads();
+    };
+    if (T > 0) {
+        request(0);
+        sp.store(s_p0);
+        sq.store(s_q0);
+        request(1);
+        __syncthreads();
+        for (int t = 0; t < T; t += 2) {
+            tile_block(s_p0, s_q0, s_p1, s_q1, t);
+            if (t + 1 < T) tile_block(s_p1, s_q1, s_p0, s_q0, t + 1);
+        }
+    }
+
+    // Accumulator element e of lane (r32, half) in tile (i, j) is
+    // C[m0 + wm + 32 i + 8 (e/4) + 4 half + e%4][n0 + wn + 32 j + r32]: for a fixed e a half wave holds 32
+    // consecutive columns of one row, so every store instruction writes two whole 128-byte lines of fp32.
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + wn + j * 32 + r32;
+            if (n >= g.Nn) continue;
+            float bias = 0.0f;
+            if constexpr (EPI == EPI_SIGMOID) bias = g.bias[n];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m0 + wm + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+                if (m >= g.M) continue;
+                const size_t o = (size_t)m * g.Nn + n;
+                const float v = acc[i][j][e];
+                if constexpr (EPI == EPI_GRAD) {
+                    float* dst = static_cast<float*>(g.out) + o;
+                    if (g.sgd_eta != 0.0f) {       // the descent step fused in: fp32 master weights stepped in
+                        const float w = fmaf(-g.sgd_eta, v, *dst);       // place, the bfloat16 weights rewritten
+                        *dst = w;
+                        static_cast<__bf16*>(g.out_bf)[o] = (__bf16)w;
+                    } else {
+                        __builtin_nontemporal_store(v, (__attribute__((address_space(1))) float*)dst);
+                    }
+                } else if constexpr (EPI == EPI_RAW) {
+                    g.raw[(size_t)blockIdx.z * g.M * g.Nn + o] = v;
+                } else if constexpr (EPI == EPI_SIGMOID) {
+                    static_cast<__bf16*>(g.out)[o] = (__bf16)sigmoidf(v + bias);
+                } else {
+                    const float a = (float)static_cast<const __bf16*>(g.act)[o];
+                    const float d = v * (a * (1.0f - a));
+                    static_cast<float*>(g.out)[o] = d;
+                    static_cast<__bf16*>(g.out_bf)[o] = (__bf16)d;
+                }
+            }
+        }
+}
+
+static_assert(2 * (P_ELEMS + Q_ELEMS) * 2 <= 80 * 1024, "two workgroups' LDS fit one compute unit");
+}  // namespace half
+
 // Split-K second stage: sum the raw partials in split order, then the layer's epilogue.  A thread takes four
 // consecutive outputs (one row: every width is a multiple of 4), 16 bytes per load.
 template <typename T, int EPI>
@@ -646,6 +855,35 @@ hipError_t run_big(GemmArgs g, int splits, hipStream_t s) {
     return hipGetLastError();
 }
 
+template <bool P_IC, bool Q_IC, int EPI>
+hipError_t run_half(GemmArgs g, int splits, hipStream_t s) {
+    const unsigned long long pb = (unsigned long long)(P_IC ? g.K : g.M) * g.ldp * 2ull;
+    const unsigned long long qb = (unsigned long long)(Q_IC ? g.K : g.Nn) * g.ldq * 2ull;
+    if (pb >= 0xFFFFFFF0ull || qb >= 0xFFFFFFF0ull) return hipErrorInvalidValue;
+    g.p_bytes = (unsigned)pb;
+    g.q_bytes = (unsigned)qb;
+    const dim3 grid(ceil_div(g.Nn, half::TN), ceil_div(g.M, half::TM), splits);
+    half::k_gemm_half<P_IC, Q_IC, EPI><<<grid, half::kThreadsHalf, 0, s>>>(g);
+    return hipGetLastError();
+}
+
+// Which of the two wide-net bf16 kernels a product takes: the 128 x 256 one that shares a compute unit (default),
+// or the 256 x 256 one.  LF_GEMM_CHAIN_TILE / LF_GEMM_GRAD_TILE = "big" or "half" override it (A/B runs, tests);
+// read once.
+bool chain_uses_half() {
+    static const int v = [] { const char* e = getenv("LF_GEMM_CHAIN_TILE"); return e ? (e[0] == 'h') : LF_CHAIN_HALF_DEFAULT; }();
+    return v != 0;
+}
+bool grad_uses_half() {
+    static const int v = [] { const char* e = getenv("LF_GEMM_GRAD_TILE"); return e ? (e[0] == 'h') : LF_GRAD_HALF_DEFAULT; }();
+    return v != 0;
+}
+// Workgroups the split of a chain-side product aims at (LF_GEMM_SPLIT_TARGET overrides; read once).
+int half_split_target() {
+    static const int v = [] { const char* e = getenv("LF_GEMM_SPLIT_TARGET"); const int t = e ? atoi(e) : 0; return t >= 64 && t <= 2048 ? t : 256; }();
+    return v;
+}
+
 }  // namespace
 
 // Whether a net whose widest layer has N neurons takes the 256 x 256 bf16 kernel: when the forward product of
@@ -663,6 +901,13 @@ bool gemm_use_big(int N, int B, bool bf16) {
 // over the contraction length K would leave most compute units idle).  Depends on the shape (and the kernel
 // chosen) alone.
 int chain_splits(int n_out, int K, int B, bool bf16, bool big_tiles) {
+    if (big_tiles && chain_uses_half()) {
+        const int tiles = ceil_div(n_out, half::TN) * ceil_div(B, half::TM);
+        const int kt = ceil_div(K, half::TK);
+        int s = 1;
+        while (tiles * s < half_split_target() && s < 16 && kt / (s * 2) >= 8) s *= 2;
+        return s;
+    }
     if (big_tiles) {
         const int tiles = ceil_div(n_out, big::TN) * ceil_div(B, big::TM);
         const int kt = ceil_div(K, big::TK);
@@ -677,9 +922,9 @@ int chain_splits(int n_out, int K, int B, bool bf16, bool big_tiles) {
     return s;
 }
 
-size_t split_workspace_floats(int n_out, int K, int B, bool bf16) {      // enough for either kernel
+size_t split_workspace_floats(int n_out, int K, int B, bool bf16) {      // enough for any of the kernels
     int s = chain_splits(n_out, K, B, bf16, false);
-    if (bf16) s = max(s, chain_splits(n_out, K, B, true, true));
+    if (bf16) s = max(s, 16);
     return s > 1 ? (size_t)s * B * n_out : 0;
 }
 
@@ -694,7 +939,11 @@ static hipError_t fwd_impl(const void* W, const float* bias, const void* A_in, v
     g.bias = bias; g.out = A_out; g.raw = raw;
     hipError_t e;
     if constexpr (bf) {
-        if (big_tiles) {
+        if (big_tiles && chain_uses_half()) {
+            g.k_tiles_per_split = ceil_div(ceil_div(n_in, half::TK), splits);
+            if (splits == 1) return run_half<false, false, EPI_SIGMOID>(g, 1, s);
+            e = run_half<false, false, EPI_RAW>(g, splits, s);
+        } else if (big_tiles) {
             if (splits == 1) return run_big<false, false, EPI_SIGMOID>(g, 1, s);
             e = run_big<false, false, EPI_RAW>(g, splits, s);
         } else {
@@ -724,7 +973,11 @@ static hipError_t chain_impl(const void* W_next, const void* D_next_op, const vo
     g.act = A_l; g.out = D_l; g.out_bf = D_l_bf; g.raw = raw;
     hipError_t e;
     if constexpr (bf) {
-        if (big_tiles) {
+        if (big_tiles && chain_uses_half()) {
+            g.k_tiles_per_split = ceil_div(ceil_div(n_next, half::TK), splits);
+            if (splits == 1) return run_half<false, true, EPI_SIGMA_PRIME>(g, 1, s);
+            e = run_half<false, true, EPI_RAW>(g, splits, s);
+        } else if (big_tiles) {
             if (splits == 1) return run_big<false, true, EPI_SIGMA_PRIME>(g, 1, s);
             e = run_big<false, true, EPI_RAW>(g, splits, s);
         } else {
@@ -770,6 +1023,10 @@ hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev
     if (bf16) {
         g.P = D_bf;
         g.k_tiles_per_split = ceil_div(B, Tile<__bf16>::BK);
+        if (big_tiles && grad_uses_half()) {
+            g.k_tiles_per_split = ceil_div(B, half::TK);
+            return run_half<true, true, EPI_GRAD>(g, 1, s);
+        }
         if (big_tiles) return run_big<true, true, EPI_GRAD>(g, 1, s);
         return run<__bf16, true, true, EPI_GRAD>(g, 1, s);
     }

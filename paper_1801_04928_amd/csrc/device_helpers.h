@@ -42,6 +42,12 @@ __device__ __forceinline__ v4f buffer_load_v4f(__amdgpu_buffer_rsrc_t r, unsigne
     return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, 0));
 }
 
+// Streaming (non-temporal) 128-bit store through a buffer resource: an offset at or past the buffer's size
+// makes the store a no-op, so rows past the end need no branch.  (aux bit 1 = non-temporal.)
+__device__ __forceinline__ void buffer_store_nt_v4f(__amdgpu_buffer_rsrc_t r, unsigned byte_offset, v4f v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), r, byte_offset, 0, 2);
+}
+
 // Streaming (non-temporal) 128-bit store to global memory.
 __device__ __forceinline__ void store_global_nt_v4f(float* p, v4f v) {
     __builtin_nontemporal_store(v, (__attribute__((address_space(1))) v4f*)(p));

@@ -166,7 +166,10 @@ struct lf_net {
     std::vector<hipEvent_t> ev_done;   // per worker stream
     std::string err;
     // persistent path
+    unsigned debug_flags;              // LF_DEBUG_*
     bool p_ready, p_tables_dirty;
+    bool p_failed_over;                // LF_SCHED_AUTO: a persistent wait gave up; the handle has moved to streams
+    bool p_fused_ok;                   // the fused backward kernel's workgroups all fit the device at once
     int p_groups, p_rpg, p_bgroups, p_tpr, p_rs, p_workers, p_nap_fwd, p_nap_bwd;
     unsigned p_spin_limit;             // polls before a bounded wait gives up
     int* p_abort_host;                 // pinned, mapped; the kernels raise it when a wait gives up
@@ -231,7 +234,9 @@ bool persistent_possible(const lf_net* net) {
 }
 
 bool use_persistent(const lf_net* net) {
+    if (net->sched == LF_SCHED_FUSED) return true;           // (lf_set_schedule has checked the shape)
     if (net->sched == LF_SCHED_STREAMS || net->sched == LF_SCHED_REDUNDANT) return false;
+    if (net->sched == LF_SCHED_AUTO && net->p_failed_over) return false;
     return persistent_possible(net);
 }
 
@@ -241,10 +246,18 @@ lf_status check_abort(lf_net* net) {
     const int code = net->p_abort_host ? *reinterpret_cast<volatile int*>(net->p_abort_host) : 0;
     if (code) {
         static const char* const site[] = {"partial-sum wait", "forward gather", "chain gather", "gradient wait"};
-        return fail(net, LF_EHIP,
-                    std::string("a persistent kernel gave up waiting for its peers (") + site[(code >> 24) & 3] +
-                        ", layer " + std::to_string((code >> 10) & 0x3fff) + ", workgroup " +
-                        std::to_string(code & 0x3ff) + "); results are invalid");
+        std::string msg = std::string("a persistent kernel gave up waiting for its peers (") + site[(code >> 24) & 3] +
+                          ", layer " + std::to_string((code >> 10) & 0x3fff) + ", workgroup " +
+                          std::to_string(code & 0x3ff) + "); results are invalid";
+        if (net->sched == LF_SCHED_AUTO) {
+            // The library chose the persistent kernels; something else holds the compute units they need.
+            // This call reports the lost pass, later passes of the handle take the stream schedule.
+            *reinterpret_cast<volatile int*>(net->p_abort_host) = 0;
+            net->p_failed_over = true;
+            net->fwd_done = net->bwd_done = false;
+            msg += "; the handle takes the stream schedule from now on (run lf_forward again)";
+        }
+        return fail(net, LF_EHIP, msg);
     }
     return LF_OK;
 }
@@ -284,13 +297,22 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
         net->p_nap_bwd = envnb ? std::atoi(envnb) : 2 * nap;
         if (net->p_nap_fwd < 0 || net->p_nap_fwd > 1024) net->p_nap_fwd = 0;
         if (net->p_nap_bwd < 0 || net->p_nap_bwd > 1024) net->p_nap_bwd = 0;
-        // every workgroup of a launch waits for others of it, so all of them must be resident at once:
-        // two per compute unit (256 registers per thread at most)
-        if (cus > 0 && (net->p_groups > 2 * cus || net->p_bgroups + 1 > 2 * cus))
-            return fail(net, LF_EUNSUPPORTED, "persistent path: too few compute units for this N");
-        if (cus > 0 && net->p_workers > 2 * cus - net->p_bgroups) net->p_workers = 2 * cus - net->p_bgroups;
+        // Every workgroup of a launch waits for others of it, so all of them must be resident at once: the
+        // runtime's occupancy figure for the very kernel instances this shape takes says how many fit.
         if (net->p_rpg > lf::kMaxRowsPerGroup)
             return fail(net, LF_EUNSUPPORTED, "persistent path: too few compute units for this N");
+        {
+            lf::PersistArgs probe{};
+            probe.L = net->L; probe.N = net->N;
+            probe.G = net->p_groups; probe.RPG = net->p_rpg;
+            probe.GB = net->p_bgroups; probe.TPR = net->p_tpr; probe.RS = net->p_rs;
+            int occ_f = 0, occ_b = 0, occ_bf = 0;
+            LF_HIP(net, lf::persistent_resident_per_cu(probe, &occ_f, &occ_b, &occ_bf));
+            if (cus <= 0 || net->p_groups > occ_f * cus || net->p_bgroups + 1 > occ_b * cus)
+                return fail(net, LF_EUNSUPPORTED, "persistent path: the device cannot hold all workgroups of a launch at once");
+            if (net->p_workers > occ_b * cus - net->p_bgroups) net->p_workers = occ_b * cus - net->p_bgroups;
+            net->p_fused_ok = net->p_bgroups <= occ_bf * cus;
+        }
         if (!net->p_abort_host) {
             void* h = nullptr;
             LF_HIP(net, hipHostMalloc(&h, sizeof(int), hipHostMallocMapped));
@@ -338,7 +360,9 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     A.GW = net->p_workers;
     A.k = k < net->p_workers ? k : net->p_workers;   // never more partitions than worker workgroups
     A.sgd_eta = net->sgd_eta;
-    A.workers = (A.k > 1 || A.sgd_eta != 0.0f) ? 1 : 0;
+    A.fused = net->sched == LF_SCHED_FUSED ? 1 : 0;
+    A.no_grads = (net->debug_flags & LF_DEBUG_CHAIN_ONLY) ? 1 : 0;
+    A.workers = ((A.k > 1 || A.sgd_eta != 0.0f) && !A.fused && !A.no_grads) ? 1 : 0;
     A.reads_done = reinterpret_cast<unsigned long long*>(net->ws + net->lay.reads_off);
     A.epoch = 0;                                            // set by the kernel
     A.counts_fwd = reinterpret_cast<unsigned*>(net->ws + net->lay.counts_off);
@@ -493,6 +517,7 @@ lf_status lf_create_widths(lf_net** out, int L, const int* n, int B, lf_dtype dt
     net->have_params = net->have_grads = net->fwd_done = net->bwd_done = net->stepped = false;
     net->have_master = false;
     net->gemm_big = lf::gemm_use_big(N, B, dt == LF_BF16);
+    net->debug_flags = 0; net->p_failed_over = false; net->p_fused_ok = false;
     net->p_ready = false; net->p_tables_dirty = true; net->p_groups = net->p_rpg = net->p_bgroups = net->p_tpr = 0; net->p_workers = 0;
     net->p_abort_host = nullptr; net->p_abort_dev_view = nullptr;
     net->err = "no error";
@@ -567,14 +592,23 @@ lf_status lf_set_schedule(lf_net* net, lf_sched sched) {
             net->sched = sched;
             return LF_OK;
         case LF_SCHED_PERSISTENT:
+        case LF_SCHED_FUSED:
             if (!persistent_possible(net))
                 return fail(net, LF_EUNSUPPORTED,
-                            "lf_set_schedule: the persistent path needs B = 1, fp32, equal widths N <= 4096");
+                            "lf_set_schedule: the persistent kernels need B = 1, fp32, equal widths N <= 4096, L <= 1025");
             net->sched = sched;
             return LF_OK;
         default:
             return fail(net, LF_EINVAL, "lf_set_schedule: unknown schedule");
     }
+}
+
+lf_status lf_set_debug_flags(lf_net* net, unsigned flags) {
+    if (!net) return LF_EINVAL;
+    if (flags & ~(unsigned)LF_DEBUG_CHAIN_ONLY) return fail(net, LF_EINVAL, "lf_set_debug_flags: unknown flag");
+    net->debug_flags = flags;
+    net->bwd_done = false;
+    return LF_OK;
 }
 
 lf_status lf_set_cost_scale(lf_net* net, int log2_scale) {
@@ -665,13 +699,22 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
     net->bwd_done = false;
     lf_status st = check_abort(net);
     if (st != LF_OK) return st;
+    const bool chain_only = (net->debug_flags & LF_DEBUG_CHAIN_ONLY) != 0;
+    if (chain_only && net->sgd_eta != 0.0f)
+        return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog: LF_DEBUG_CHAIN_ONLY and lf_set_sgd exclude each other");
+    if (chain_only && net->sched == LF_SCHED_REDUNDANT)
+        return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog: LF_DEBUG_CHAIN_ONLY has no meaning for LF_SCHED_REDUNDANT");
     if (use_persistent(net)) {
+        if (net->sched == LF_SCHED_FUSED && net->sgd_eta != 0.0f)
+            return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog: LF_SCHED_FUSED does not take the descent step");
         st = prepare_persistent(net, s);
         if (st != LF_OK) return st;
+        if (net->sched == LF_SCHED_FUSED && !net->p_fused_ok)
+            return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog: the device cannot hold the fused kernel's workgroups at once");
         lf::PersistArgs A = persist_args(net, y, k);
         A.nap = net->p_nap_bwd;
         LF_HIP(net, lf::launch_bwd_persistent(A, s));
-        net->bwd_done = true;
+        net->bwd_done = !chain_only;
         if (net->sgd_eta != 0.0f) net->stepped = true;
         return LF_OK;
     }
@@ -704,6 +747,7 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
         // the worker rewrites w^l, which the chain still reads on its way to delta^{l-1}: layer l's work then
         // starts once delta^{l-1} is there (layer 2's, whose weights the chain never reads, with delta^2).
         const bool sgd = net->sgd_eta != 0.0f;
+        if (chain_only) continue;                       // the chain alone (a timing aid): no gradient is formed
         if (k == 1) {
             if (!sgd || l == 2) st = enqueue_grads(net, l, s);
             if (st == LF_OK && sgd && l < L) st = enqueue_grads(net, l + 1, s);
@@ -716,14 +760,14 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
             if (st != LF_OK) return st;
         }
     }
-    if (k > 1) {   // join
+    if (k > 1 && !chain_only) {   // join
         for (int j = 0; j < nstreams; ++j) {
             if (!used[j]) continue;
             LF_HIP(net, hipEventRecord(net->ev_done[j], net->workers[j]));
             LF_HIP(net, hipStreamWaitEvent(s, net->ev_done[j], 0));
         }
     }
-    net->bwd_done = true;
+    net->bwd_done = !chain_only;
     if (net->sgd_eta != 0.0f) net->stepped = true;     // the stored activations belong to the old weights
     return LF_OK;
 }

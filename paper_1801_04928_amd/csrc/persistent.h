@@ -20,6 +20,10 @@ struct PersistArgs {
     int GW, k;                           // gradient worker workgroups, worker partitions
     int workers;                         // 1 = the grid has gradient worker workgroups (k >= 2, or the descent
                                          // step is on); 0 = the chain workgroups form the gradients in line
+    int fused;                           // 1 = on-chain fusion: the chain workgroups store nabla_w^{l+1} inside the
+                                         // loop that multiplies w^{l+1} (a grid without workers)
+    int no_grads;                        // 1 = the chain alone: no gradient is formed (a timing aid; a grid
+                                         // without workers)
     float sgd_eta;                       // != 0: the workers apply w -= eta nabla_w, b -= eta nabla_b in place
     unsigned long long* reads_done;      // [L-1][kMaxGroups] tagged words, row l-2: chain workgroup g has
                                          // finished reading w^l (written only while the descent step is on)
@@ -57,6 +61,9 @@ size_t persistent_ll_layer_words(int N, int ll_shift);
 void persistent_forward_shape(int N, int num_cus, int requested, int* G, int* rpg);
 // row_split: 1, 2 or 4 row blocks per column strip, anything else = the default for this N.
 void persistent_backward_shape(int N, int num_cus, int requested, int row_split, int* GB, int* tpr, int* rs);
+// Workgroups of the forward / backward / fused backward kernel instance for A's shape that one compute unit
+// holds at a time (the runtime's occupancy figure for that very instance).
+hipError_t persistent_resident_per_cu(const PersistArgs& A, int* forward, int* backward, int* backward_fused);
 hipError_t launch_fill_u64(void* p, size_t n_words, unsigned long long v, hipStream_t s);
 hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s);
 hipError_t launch_bwd_persistent(const PersistArgs& A, hipStream_t s);

@@ -33,6 +33,7 @@
 // observe, the kernel drains, and the host reports LF_EHIP with the place of the failed wait.
 #include "lf_internal.h"
 #include "persistent.h"
+#include "persistent_epoch.h"
 
 namespace lf {
 namespace {
@@ -138,17 +139,18 @@ __device__ __forceinline__ void nap(int units) {
 // The tag of a launch's words lives in device memory, not in the kernel's arguments: a launch recorded in a
 // HIP graph is replayed with the same arguments, and a replay whose words carried the tags of the launch
 // before it would take that launch's leftovers for fresh data.  Every workgroup keeps a launch count of
-// its own (so nothing is shared and nobody waits): it reads the count when it starts and stores count + 1
-// right away.  All workgroups of a grid are launched equally often, so their counts agree; the end of the
-// kernel orders the store before the next launch.  (The value stays in a vector register: making it
-// scalar here would put the wait for the load in front of everything the kernel can do before it first
-// needs a tag.)
-__device__ __forceinline__ unsigned launch_count(unsigned* counts) {
-    unsigned* mine = counts + blockIdx.x;
-    const unsigned c = __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned next = c + 1u;
-    if (threadIdx.x == 0) __hip_atomic_store(mine, next != 0u ? next : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return c;
+// its own (so nothing is shared between workgroups and nobody waits).  All workgroups of a grid are launched
+// equally often, so their counts agree; the end of the kernel orders the store before the next launch.
+// One thread alone reads the count, stores the next one and hands the value to the rest of the workgroup
+// through LDS behind the kernel's first barrier (which waits for the per-layer pointer tables anyway): no
+// other thread ever reads the word in memory, so no wave can see the count of the next launch.
+__device__ __forceinline__ void take_launch_count(unsigned* counts, unsigned* s_count) {
+    if (threadIdx.x == 0) {
+        unsigned* mine = counts + blockIdx.x;
+        const unsigned c = __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mine, next_launch_count(c), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_count = c;
+    }
 }
 
 // Word that holds element i of an exchanged vector.  Groups of eight words (64 bytes) are spread
@@ -172,7 +174,8 @@ __device__ __forceinline__ const float* act_ptr(const PersistArgs& A, int l) {
 // SINGLE: the wave's rows of a layer are one chunk (the latency-bound small nets); otherwise an even
 // number of chunks per layer.
 template <int Q, int RF, bool SINGLE>
-__device__ __forceinline__ void forward_pass(const PersistArgs& A) {
+__device__ __forceinline__ void forward_pass(const PersistArgs& args) {
+    __shared__ unsigned s_count;
     __shared__ v4f s_a[Q * 64];
     __shared__ float s_bias[kMaxRowsPerGroup];
     __shared__ const float* s_w[kTableLds];      // w^l and b^l pointers: a table entry fetched from
@@ -180,9 +183,12 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& A) {
                                                  // and a generic load of it would be waited for together
                                                  // with every weight load in flight
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
+    PersistArgs A = args;
     const int N = A.N, L = A.L, RPG = A.RPG, nvec = N >> 2;
+    take_launch_count(A.counts_fwd, &s_count);
     for (int i = t; i < L - 1; i += kThreads) { s_w[i] = A.w[i]; s_b[i] = A.b[i]; }
     __syncthreads();
+    A.epoch = forward_epoch(s_count);
     auto wptr = [&](int i) { return s_w[i]; };
     auto bptr = [&](int i) { return s_b[i]; };
     const int RW = (RPG + kWaves - 1) / kWaves;             // rows per wave
@@ -408,16 +414,18 @@ __device__ __forceinline__ float ll_wait1(const u64* p, unsigned tag, Abort& ab,
 // With the descent step fused in it rewrites w^l, which the chain reads on its way to delta^{l-1}: it then also
 // waits until every chain workgroup has reported the end of its reads of w^l (one tagged word per chain
 // workgroup and layer, each polled by one thread).
-__device__ __forceinline__ void gradient_worker(const PersistArgs& A, int wid, int nworkers, Abort& ab) {
+__device__ __forceinline__ void gradient_worker(PersistArgs& A, unsigned* s_count, int wid, int nworkers,
+                                                Abort& ab) {
     __shared__ float s_wd[kThreads];
     __shared__ int s_wdead;
     const int N = A.N, L = A.L, k = A.k, t = threadIdx.x;
     const int part = wid % k, member = wid / k, members = (nworkers - part + k - 1) / k;
     const int RM = (N + members - 1) / members;
     const int jb = min(N, member * RM), je = min(N, jb + RM);
-    if (jb >= je) return;
     if (t == 0) s_wdead = 0;
     __syncthreads();
+    A.epoch = backward_epoch(*s_count, true);
+    if (jb >= je) return;                           // (behind the barrier: its launch count is taken)
     const bool sgd = A.sgd_eta != 0.0f;
     for (int layer = L - part; layer >= 2; layer -= k) {
         v4f ja[PG];
@@ -465,23 +473,36 @@ __device__ __forceinline__ float strip_column_sum(const v4f (&red)[kWaves * 4][T
 // rate); the price is one more exchange per step: the row blocks' partial sums go out as tagged words
 // and each of the RS workgroups finishes 1/RS of the strip's columns, adding the partials in row-block
 // order.
-template <int TPR, int CH, bool SINGLE, bool SPLIT>
-__device__ __forceinline__ void backward_pass(const PersistArgs& A) {
+// FUSED (a grid without workers): the on-chain fusion.  The thread that multiplies an entry of w^{l+1} into
+// the column sums of delta^l also forms and stores the same entry of nabla_w^{l+1} = delta^{l+1} (a^l)^T,
+// inside the same chunk loop (delta^{l+1} is in LDS for the product anyway, the four a^l values of the
+// thread's columns sit in registers).  Layer 2, whose weights the chain never reads, is stored at the end.
+template <int TPR, int CH, bool SINGLE, bool SPLIT, bool FUSED>
+__device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     constexpr int CPG = 4 * TPR;              // columns per chain workgroup
     constexpr int RPP = kThreads / TPR;       // rows covered by one load of the whole workgroup
     __shared__ v4f s_delta4[kMaxPersistentN / 4];       // delta^{l+1}, all of it
     __shared__ v4f s_red[kWaves * 4][TPR];              // per row of 16 lanes
     __shared__ const float* s_w[kTableLds];             // w^l pointers (see the forward kernel)
+    __shared__ float* s_gw[FUSED ? kTableLds : 1];      // nabla_w^l, nabla_b^l pointers (on-chain fusion only)
+    __shared__ float* s_gb[FUSED ? kTableLds : 1];
+    __shared__ unsigned s_count;
     float* s_delta = reinterpret_cast<float*>(s_delta4);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
+    PersistArgs A = args;
     const int N = A.N, L = A.L, GB = A.GB, nvec = N >> 2;
     Abort ab{A.abort_dev, A.abort_host, false, A.spin_limit};
+    take_launch_count(A.workers ? A.counts_bwdk : A.counts_bwd1, &s_count);
     if (g >= GB) {
-        gradient_worker(A, g - GB, (int)gridDim.x - GB, ab);
+        gradient_worker(A, &s_count, g - GB, (int)gridDim.x - GB, ab);
         return;
     }
-    for (int i = t; i < L - 1; i += kThreads) s_w[i] = A.w[i];
+    for (int i = t; i < L - 1; i += kThreads) {
+        s_w[i] = A.w[i];
+        if constexpr (FUSED) { s_gw[i] = A.gw[i]; s_gb[i] = A.gb[i]; }
+    }
     __syncthreads();
+    A.epoch = backward_epoch(s_count, A.workers != 0);
     auto wptr = [&](int i) { return s_w[i]; };
     // strips of workgroups on one XCD (workgroups are dealt to the 8 XCDs round-robin) are adjacent,
     // and the workgroups that share a strip sit on one XCD
@@ -571,6 +592,17 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
     const int nfin = SPLIT ? CPG / RS : CPG, fcol0 = col0 + rb * nfin;
     const bool own = t < nfin && fcol0 + t < N;
     float a_next = (own && L > 2) ? load_global_f32_here(act_ptr(A, L - 1) + fcol0 + t) : 0.0f;
+    // on-chain fusion: a^l at my four columns, the second factor of my entries of nabla_w^{l+1}; requested where
+    // a_next is, element by element (a load the compiler leaves in place)
+    auto load_strip_activation = [&](int layer) -> v4f {
+        const float* ap = act_ptr(A, layer) + col;
+        return v4f{load_global_f32_here(ap), load_global_f32_here(ap + 1), load_global_f32_here(ap + 2),
+                   load_global_f32_here(ap + 3)};
+    };
+    v4f a4_next = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (FUSED) { if (L > 2) a4_next = load_strip_activation(L - 1); }
+    const bool bias_writer = FUSED && strip == 0 && cg == 0;
+    const bool inline_bursts = !A.workers && !A.no_grads && !FUSED;    // the sequential pass's gradient bursts
     v4f buf[NB][CH];
     if (L > 2) {                                     // my strip of w^L, needed by the first chain step
         load_chunk(buf[0], wptr(L - 2), 0);
@@ -596,7 +628,13 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
         }
     }
 
-    auto fma_chunk = [&](const v4f (&buf)[CH], int ci, v4f& acc) {
+    // gwl, gbl, a4 (on-chain fusion only): nabla_w^{l+1}, nabla_b^{l+1}, a^l at my columns.  nabla_w^{l+1} is laid
+    // out like w^{l+1}, so an entry is stored through a buffer at the very offset its weight was loaded from,
+    // and rows past the end of my row block fall outside the buffer (no store).
+    auto fma_chunk = [&](const v4f (&buf)[CH], int ci, v4f& acc, float* gwl, float* gbl, const v4f& a4) {
+        const unsigned gskip = (unsigned)(ci * CH) * pass_bytes;
+        const __amdgpu_buffer_rsrc_t gr = make_buffer(reinterpret_cast<const char*>(gwl) + (FUSED ? gskip : 0u),
+                                                      FUSED && block_bytes > gskip ? block_bytes - gskip : 0u);
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             const int row = row_lo + rs + RPP * (ci * CH + u);
@@ -606,6 +644,11 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
             acc.y = fmaf(buf[u].y, d, acc.y);
             acc.z = fmaf(buf[u].z, d, acc.z);
             acc.w = fmaf(buf[u].w, d, acc.w);
+            if constexpr (FUSED) {
+                const v4f o = {d * a4.x, d * a4.y, d * a4.z, d * a4.w};
+                buffer_store_nt_v4f(gr, strip_offset + (unsigned)u * pass_bytes, o);
+                if (bias_writer && row < row_hi) store_global_f32(gbl + row, d);
+            }
         }
     };
     // One chain step, delta^{l+1} -> delta^l.  SINGLE: on entry bufA holds (possibly still in flight) my
@@ -616,13 +659,17 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
     // the time, also across the exchange, without any register copy.
     auto step = [&](v4f (&bufA)[CH], v4f (&bufB)[CH], int l) {
         const float a_l = a_next;
-        if (!A.workers) inline_grads(l + 1);
+        const v4f a4 = a4_next;
+        float* gwl = nullptr;
+        float* gbl = nullptr;
+        if constexpr (FUSED) { gwl = s_gw[l - 1]; gbl = s_gb[l - 1]; }
+        if (inline_bursts) inline_grads(l + 1);
         const float* W = wptr(l - 1);
         const float* Wn = l > 2 ? wptr(l - 2) : nullptr;
         v4f acc = {0.f, 0.f, 0.f, 0.f};
         if constexpr (SINGLE) {
             if (Wn) load_chunk(bufB, Wn, 0);
-            fma_chunk(bufA, 0, acc);
+            fma_chunk(bufA, 0, acc, gwl, gbl, a4);
         } else {
             // every refill is one unconditional load: past the last layer it reads an empty buffer
             // (zeros, no memory traffic), so a buffer's registers are never carried around a branch
@@ -632,7 +679,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
                 const bool same = ci + NB < nchunks;
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
-                    fma_chunk(buf[j], ci + j, acc);
+                    fma_chunk(buf[j], ci + j, acc, gwl, gbl, a4);
                     load_chunk_of(buf[j], same ? W : Wnext, same ? ci + j + NB : j, same ? block_bytes : next_bytes);
                 }
             }
@@ -665,13 +712,17 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
                 A.d_base[(size_t)(l - 2) * A.d_stride + fcol0 + t] = d;
                 if (l > 2) a_next = load_global_f32_here(act_ptr(A, l - 1) + fcol0 + t);
             }
-        } else if (own) {
-            const int q = t >> 2, e = t & 3;
-            const float u = strip_column_sum(s_red, q, e);
-            const float d = u * (a_l * (1.0f - a_l));
-            ll_store(A.DLL + (size_t)(l - 2) * A.ll_layer + ll_index(A, col0 + t), d, A.epoch);
-            A.d_base[(size_t)(l - 2) * A.d_stride + col0 + t] = d;
-            if (l > 2) a_next = load_global_f32_here(act_ptr(A, l - 1) + col0 + t);
+            if constexpr (FUSED) { if (l > 2) a4_next = load_strip_activation(l - 1); }
+        } else {
+            if (own) {
+                const int q = t >> 2, e = t & 3;
+                const float u = strip_column_sum(s_red, q, e);
+                const float d = u * (a_l * (1.0f - a_l));
+                ll_store(A.DLL + (size_t)(l - 2) * A.ll_layer + ll_index(A, col0 + t), d, A.epoch);
+                A.d_base[(size_t)(l - 2) * A.d_stride + col0 + t] = d;
+                if (l > 2) a_next = load_global_f32_here(act_ptr(A, l - 1) + col0 + t);
+            }
+            if constexpr (FUSED) { if (l > 2) a4_next = load_strip_activation(l - 1); }
         }
         // exchange: all of delta^l (every workgroup is past its last read of delta^{l+1})
         nap(A.nap);
@@ -687,24 +738,21 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& A) {
     } else {
         for (int l = L - 1; l >= 2; --l) step(buf[0], buf[1], l);
     }
-    if (!A.workers) inline_grads(2);
+    if (!A.workers && !A.no_grads) inline_grads(2);
 }
 
 template <int Q, int RF, bool SINGLE>
 __global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArgs args) {
-    PersistArgs A = args;
-    A.epoch = launch_count(args.counts_fwd);
-    forward_pass<Q, RF, SINGLE>(A);
+    forward_pass<Q, RF, SINGLE>(args);
 }
-// The backward kernel runs with two grids: chain workgroups only (k = 1 without the descent step), or chain +
-// gradient workers.  Each grid has its own counts; odd tags belong to the first, even tags to the second, so
-// the words of one can never pass for the other's.
-template <int TPR, int CH, bool SINGLE, bool SPLIT>
-__global__ __launch_bounds__(kThreads, 2) void k_bwd_persistent(const PersistArgs args) {
-    PersistArgs A = args;
-    if (!args.workers) A.epoch = 2u * launch_count(args.counts_bwd1) + 1u;
-    else A.epoch = 2u * launch_count(args.counts_bwdk);
-    backward_pass<TPR, CH, SINGLE, SPLIT>(A);
+// The backward kernel runs with two grids: chain workgroups only (k = 1 without the descent step, the on-chain
+// fusion, the chain alone), or chain + gradient workers.  Each grid has its own launch counts and its own
+// tags (see persistent_epoch.h), so the words of one can never pass for the other's.
+// (The fused grid has no worker workgroups to share a compute unit with: one wave per SIMD, hence twice the
+// registers, which the extra stores of its multi-chunk loops need.)
+template <int TPR, int CH, bool SINGLE, bool SPLIT, bool FUSED>
+__global__ __launch_bounds__(kThreads, FUSED ? 1 : 2) void k_bwd_persistent(const PersistArgs args) {
+    backward_pass<TPR, CH, SINGLE, SPLIT, FUSED>(args);
 }
 
 __global__ __launch_bounds__(kThreads) void k_fill_u64(u64* p, size_t n, u64 v) {
@@ -765,54 +813,97 @@ hipError_t launch_fill_u64(void* p, size_t n_words, unsigned long long v, hipStr
     return hipGetLastError();
 }
 
-hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s) {
-    if (!persistent_supported(A.L, A.N) || A.G > kMaxLaunchGroups) return hipErrorInvalidValue;
+typedef void (*persist_kernel_t)(const PersistArgs);
+
+// The forward kernel instance for this shape (nullptr: none).
+static persist_kernel_t forward_kernel(const PersistArgs& A) {
+    if (!persistent_supported(A.L, A.N) || A.G > kMaxLaunchGroups) return nullptr;
     const int q = (A.N / 4 + 63) / 64;                       // float4 groups per lane and row
     const int rw = (A.RPG + kWaves - 1) / kWaves;            // rows per wave
     if (q <= 4) {
-        if (rw == 1) k_fwd_persistent<4, 1, true><<<A.G, kThreads, 0, s>>>(A);
-        else if (rw == 2) k_fwd_persistent<4, 2, true><<<A.G, kThreads, 0, s>>>(A);
-        else if (rw <= 4) k_fwd_persistent<4, 4, true><<<A.G, kThreads, 0, s>>>(A);
-        else k_fwd_persistent<4, 4, false><<<A.G, kThreads, 0, s>>>(A);
-    } else if (q <= 8) {
-        if (rw == 1) k_fwd_persistent<8, 1, true><<<A.G, kThreads, 0, s>>>(A);
-        else if (rw == 2) k_fwd_persistent<8, 2, true><<<A.G, kThreads, 0, s>>>(A);
-        else k_fwd_persistent<8, 2, false><<<A.G, kThreads, 0, s>>>(A);
-    } else if (q <= 16) {
-        if (rw == 1) k_fwd_persistent<16, 1, true><<<A.G, kThreads, 0, s>>>(A);
-        else k_fwd_persistent<16, 1, false><<<A.G, kThreads, 0, s>>>(A);
-    } else {
-        return hipErrorInvalidValue;
+        if (rw == 1) return k_fwd_persistent<4, 1, true>;
+        if (rw == 2) return k_fwd_persistent<4, 2, true>;
+        if (rw <= 4) return k_fwd_persistent<4, 4, true>;
+        return k_fwd_persistent<4, 4, false>;
     }
-    return hipGetLastError();
+    if (q <= 8) {
+        if (rw == 1) return k_fwd_persistent<8, 1, true>;
+        if (rw == 2) return k_fwd_persistent<8, 2, true>;
+        return k_fwd_persistent<8, 2, false>;
+    }
+    if (q <= 16) {
+        if (rw == 1) return k_fwd_persistent<16, 1, true>;
+        return k_fwd_persistent<16, 1, false>;
+    }
+    return nullptr;
 }
 
-template <int TPR>
-static hipError_t launch_bwd_tpr(const PersistArgs& A, int grid, hipStream_t s) {
+template <int TPR, bool FUSED>
+static persist_kernel_t backward_kernel_tpr(const PersistArgs& A) {
     const int nloads = (A.N + kThreads / TPR - 1) / (kThreads / TPR);
-    if (A.RS > 1) k_bwd_persistent<TPR, 8, false, true><<<grid, kThreads, 0, s>>>(A);
-    else if (nloads <= 4) k_bwd_persistent<TPR, 4, true, false><<<grid, kThreads, 0, s>>>(A);
-    else if (nloads <= 8) k_bwd_persistent<TPR, 8, true, false><<<grid, kThreads, 0, s>>>(A);
-    else k_bwd_persistent<TPR, 8, false, false><<<grid, kThreads, 0, s>>>(A);
+    if (A.RS > 1) return k_bwd_persistent<TPR, 8, false, true, FUSED>;
+    if (nloads <= 4) return k_bwd_persistent<TPR, 4, true, false, FUSED>;
+    if (nloads <= 8) return k_bwd_persistent<TPR, 8, true, false, FUSED>;
+    return k_bwd_persistent<TPR, 8, false, false, FUSED>;
+}
+
+template <bool FUSED>
+static persist_kernel_t backward_kernel_of(const PersistArgs& A) {
+    switch (A.TPR) {
+        case 1: return backward_kernel_tpr<1, FUSED>(A);
+        case 2: return backward_kernel_tpr<2, FUSED>(A);
+        case 4: return backward_kernel_tpr<4, FUSED>(A);
+        case 8: return backward_kernel_tpr<8, FUSED>(A);
+        case 16: return A.RS == 4 ? backward_kernel_tpr<16, FUSED>(A) : nullptr;
+        default: return nullptr;
+    }
+}
+
+// The backward kernel instance for this shape and variant (nullptr: none).
+static persist_kernel_t backward_kernel(const PersistArgs& A) {
+    if (A.GB > kMaxGroups * 2 || !persistent_supported(A.L, A.N)) return nullptr;
+    if (A.RS != 1 && A.RS != 2 && A.RS != 4) return nullptr;
+    if (A.GB % A.RS != 0 || (4 * A.TPR) % A.RS != 0) return nullptr;
+    if (A.GB > kMaxGroups || kMaxGroups > kThreads) return nullptr;   // one polling thread per chain workgroup
+    return A.fused ? backward_kernel_of<true>(A) : backward_kernel_of<false>(A);
+}
+
+// How many workgroups of each kernel instance one compute unit holds at a time, by the runtime's own
+// occupancy calculation for that instance (registers, LDS, waves).
+hipError_t persistent_resident_per_cu(const PersistArgs& A, int* forward, int* backward, int* backward_fused) {
+    PersistArgs B = A;
+    const persist_kernel_t kf = forward_kernel(A);
+    B.fused = 0;
+    const persist_kernel_t kb = backward_kernel(B);
+    B.fused = 1;
+    const persist_kernel_t kbf = backward_kernel(B);
+    if (!kf || !kb || !kbf) return hipErrorInvalidValue;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(forward, kf, kThreads, 0);
+    if (e != hipSuccess) return e;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(backward, kb, kThreads, 0);
+    if (e != hipSuccess) return e;
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(backward_fused, kbf, kThreads, 0);
+}
+
+hipError_t launch_fwd_persistent(const PersistArgs& A, hipStream_t s) {
+    const persist_kernel_t k = forward_kernel(A);
+    if (!k) return hipErrorInvalidValue;
+    k<<<A.G, kThreads, 0, s>>>(A);
     return hipGetLastError();
 }
 
 hipError_t launch_bwd_persistent(const PersistArgs& A, hipStream_t s) {
-    if (A.GB > kMaxGroups * 2 || !persistent_supported(A.L, A.N)) return hipErrorInvalidValue;
-    if (A.RS != 1 && A.RS != 2 && A.RS != 4) return hipErrorInvalidValue;
-    if (A.GB % A.RS != 0 || (4 * A.TPR) % A.RS != 0) return hipErrorInvalidValue;
-    if ((A.k > 1 || A.sgd_eta != 0.0f) != (A.workers != 0)) return hipErrorInvalidValue;
-    if (A.GB > kMaxGroups || kMaxGroups > kThreads) return hipErrorInvalidValue;   // one polling thread per chain workgroup
+    const persist_kernel_t k = backward_kernel(A);
+    if (!k) return hipErrorInvalidValue;
+    if ((A.k > 1 || A.sgd_eta != 0.0f) != (A.workers != 0)) {
+        if (!(A.workers == 0 && (A.fused || A.no_grads))) return hipErrorInvalidValue;
+    }
+    if (A.workers && (A.fused || A.no_grads)) return hipErrorInvalidValue;
+    if (A.fused && A.sgd_eta != 0.0f) return hipErrorInvalidValue;
     const int grid = A.GB + (A.workers ? A.GW : 0);  // chain workgroups, then the gradient workers
     if (grid > kMaxLaunchGroups) return hipErrorInvalidValue;
-    switch (A.TPR) {
-        case 1: return launch_bwd_tpr<1>(A, grid, s);
-        case 2: return launch_bwd_tpr<2>(A, grid, s);
-        case 4: return launch_bwd_tpr<4>(A, grid, s);
-        case 8: return launch_bwd_tpr<8>(A, grid, s);
-        case 16: return A.RS == 4 ? launch_bwd_tpr<16>(A, grid, s) : hipErrorInvalidValue;
-        default: return hipErrorInvalidValue;
-    }
+    k<<<grid, kThreads, 0, s>>>(A);
+    return hipGetLastError();
 }
 
 }  // namespace lf

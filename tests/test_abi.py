@@ -155,7 +155,12 @@ def test_call_order_and_argument_checks():
         assert P.lf_set_cost_scale(h, -127) == P.LF_EINVAL
         assert P.lf_set_cost_scale(h, 100) == P.LF_OK
         assert P.lf_set_schedule(h, 99) == P.LF_EINVAL
+        assert P.lf_set_schedule(h, P.LF_SCHED_FUSED) == P.LF_OK           # B = 1, fp32, N <= 4096
         assert P.lf_set_schedule(h, P.LF_SCHED_STREAMS) == P.LF_OK
+        assert P.lf_set_debug_flags(h, 2) == P.LF_EINVAL                    # unknown bit
+        assert P.lf_set_debug_flags(h, P.LF_DEBUG_CHAIN_ONLY) == P.LF_OK
+        assert P.lf_set_debug_flags(h, 0) == P.LF_OK
+        assert P.lf_set_debug_flags(None, 0) == P.LF_EINVAL
     finally:
         P.lf_destroy(h)
     P.lf_destroy(None)
@@ -202,6 +207,7 @@ def test_algorithm1_owner_matches_the_algorithm_run_literally(L):
     P.lf_destroy(h)
     hb = _handle(4, 256, 8, P.LF_F32)
     assert P.lf_set_schedule(hb, P.LF_SCHED_REDUNDANT) == P.LF_EUNSUPPORTED
+    assert P.lf_set_schedule(hb, P.LF_SCHED_FUSED) == P.LF_EUNSUPPORTED
     P.lf_destroy(hb)
 
 

@@ -14,7 +14,7 @@ def _free(g):
     g.close()
 
 
-SCHEDS = {"streams": 1, "persistent": 2}   # LF_SCHED_STREAMS, LF_SCHED_PERSISTENT
+SCHEDS = {"streams": 1, "persistent": 2, "fused": 4}   # LF_SCHED_STREAMS, LF_SCHED_PERSISTENT, LF_SCHED_FUSED
 
 
 # ---------------------------------------------------------------- single sample, fp32
@@ -63,13 +63,14 @@ def test_single_sample_outer_product_is_exact(sched):
 
 
 @pytest.mark.parametrize("L,N,B,dtype,sched", [
-    (12, 1024, 1, "f32", "streams"), (12, 1024, 1, "f32", "persistent"), (7, 2052, 1, "f32", "persistent"),
-    (6, 392, 5, "f32", None), (6, 264, 9, "bf16", None)])
+    (12, 1024, 1, "f32", "streams"), (12, 1024, 1, "f32", "persistent"), (10, 2052, 1, "f32", "persistent"),
+    (10, 392, 5, "f32", None), (10, 264, 9, "bf16", None), (9, 520, 260, "bf16", None)])
 def test_gradients_bit_identical_for_every_k(L, N, B, dtype, sched):
-    """Leapfrogging only reassigns who computes (bp3),(bp4) (Theorem 1): same bits for every k."""
+    """Leapfrogging only reassigns who computes (bp3),(bp4) (Theorem 1): same bits for k = 1, 2, 4, 8 and
+    the odd ones."""
     net = make_net(L, N, B, dtype=dtype, seed=77)
     ref = None
-    for k in (1, 2, 4, 5, L - 1):
+    for k in (1, 2, 4, 8, 5, L - 1):
         g = run_gpu(net, k, sched=SCHEDS.get(sched))
         cur = [(to_np(g.grads(l)[0]).copy(), to_np(g.grads(l)[1]).copy()) for l in range(2, L + 1)]
         if ref is None:
@@ -81,20 +82,32 @@ def test_gradients_bit_identical_for_every_k(L, N, B, dtype, sched):
         _free(g)
 
 
-@pytest.mark.parametrize("sched", ["streams", "persistent"])
+def _grad_hash(g):
+    """Order-sensitive 64-bit checksum of every gradient bit, computed on the device."""
+    torch = g.torch
+    h = torch.zeros((), dtype=torch.int64, device=g.device)
+    for i, t in enumerate(g.nabla_w + g.nabla_b):
+        v = t.view(torch.int32).to(torch.int64).flatten()
+        h = h * 1000003 + (v * (torch.arange(v.numel(), device=g.device) % 8191 + 1)).sum() + i
+    return int(h)
+
+
+@pytest.mark.parametrize("sched", ["streams", "persistent", "fused"])
 def test_repeated_passes_are_deterministic_and_overwrite(sched):
-    """Gradients are overwritten (not accumulated) and identical on every pass; the activations,
-    errors and gradients are poisoned with NaN between passes so a worker that ran ahead of its
-    delta would show."""
+    """Gradients are overwritten (not accumulated) and identical on every one of 100 passes (a checksum of all
+    gradient bits per pass); the activations, errors and gradients are poisoned with NaN before each pass so
+    a worker that ran ahead of its delta would show."""
     import torch
     net = make_net(10, 640, 1, seed=3)
     g = run_gpu(net, 4, sched=SCHEDS[sched])
     first = [to_np(g.grads(l)[0]).copy() for l in range(2, 11)]
-    for _ in range(20):
+    want = _grad_hash(g)
+    for i in range(100):
         poison_buffers(g, whole_workspace=False)
         g.forward()
         g.backward(4)
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        assert _grad_hash(g) == want, f"pass {i} differs"
     for l in range(2, 11):
         assert np.array_equal(first[l - 2].view(np.uint32), to_np(g.grads(l)[0]).view(np.uint32))
     _free(g)
@@ -661,7 +674,17 @@ def test_config1_full():
     _free(g)
 
 
-@pytest.mark.parametrize("sched", ["streams", "persistent"])
+def _clone_grads(g):
+    return [t.clone() for t in g.nabla_w + g.nabla_b]
+
+
+def _assert_same_bits(g, ref, what):
+    torch = g.torch
+    for i, (t, r) in enumerate(zip(g.nabla_w + g.nabla_b, ref)):
+        assert bool(torch.equal(t.view(torch.int32), r.view(torch.int32))), f"{what}: tensor {i} differs"
+
+
+@pytest.mark.parametrize("sched", ["streams", "persistent", "fused"])
 @pytest.mark.parametrize("k", [1, 2, 4, 8])
 def test_config2_full(k, sched):
     net = config_net("cfg2", cache=True)
@@ -671,15 +694,57 @@ def test_config2_full(k, sched):
     _free(g)
 
 
+@pytest.mark.parametrize("sched", ["streams", "persistent"])
+def test_config2_same_bits_for_k_1_2_4_8(sched):
+    """Configuration 2 at full size: the gradients of k = 1, 2, 4, 8 are the same bits (Theorem 1: leapfrogging
+    changes who computes (bp3),(bp4), never what), and so are the on-chain fusion's."""
+    import torch
+    import paper_1801_04928_amd as P
+    net = config_net("cfg2", cache=True)
+    g = run_gpu(net, 1, sched=SCHEDS[sched])
+    ref = _clone_grads(g)
+    for k in (2, 4, 8):
+        poison_buffers(g, whole_workspace=False)
+        g.forward()
+        g.backward(k)
+        torch.cuda.synchronize()
+        _assert_same_bits(g, ref, f"cfg2 {sched} k={k}")
+    if sched == "persistent":
+        g.set_schedule(P.LF_SCHED_FUSED)
+        poison_buffers(g, whole_workspace=False)
+        g.forward()
+        g.backward(1)
+        torch.cuda.synchronize()
+        _assert_same_bits(g, ref, "cfg2 fused")
+    _free(g)
+
+
 def test_config3_full():
     """L=64: delta underflows into the fp32 subnormal range near the input; those layers are
-    compared in denormal ulps and listed."""
+    compared in denormal ulps and listed.  Persistent kernels, k = 8: against the oracle; k = 1 (the chain
+    workgroups' in-line gradient bursts, rows taken from the row block), k = 4 and the on-chain fusion: the same
+    bits as k = 8.  Stream schedule, k = 4 (another summation order): against the oracle."""
+    import torch
+    import paper_1801_04928_amd as P
     net = config_net("cfg3", cache=True)
-    for sched, k in (("persistent", 8), ("streams", 4)):
-        g = run_gpu(net, k, sched=SCHEDS[sched])
-        rep = check_against_oracle(net, g)
-        log(f"cfg3 k={k} {sched}: worst {rep['worst']:.2e}; subnormal tensors: {rep.get('subnormal', [])}")
-        _free(g)
+    g = run_gpu(net, 8, sched=SCHEDS["persistent"])
+    rep = check_against_oracle(net, g)
+    log(f"cfg3 k=8 persistent: worst {rep['worst']:.2e}; subnormal tensors: {rep.get('subnormal', [])}")
+    ref = _clone_grads(g)
+    for k, sched in ((1, "persistent"), (4, "persistent"), (8, "fused")):
+        g.set_schedule(SCHEDS[sched])
+        poison_buffers(g, whole_workspace=False)
+        g.forward()
+        g.backward(k)
+        torch.cuda.synchronize()
+        _assert_same_bits(g, ref, f"cfg3 {sched} k={k}")
+        log(f"cfg3 k={k} {sched}: same bits as k=8")
+    del ref
+    _free(g)
+    g = run_gpu(net, 4, sched=SCHEDS["streams"])
+    rep = check_against_oracle(net, g)
+    log(f"cfg3 k=4 streams: worst {rep['worst']:.2e}; subnormal tensors: {rep.get('subnormal', [])}")
+    _free(g)
 
 
 def test_config3_fused_descent_step():
@@ -721,17 +786,37 @@ def test_config3_fused_descent_step():
     _free(g)
 
 
+def _check_whole_gradient_against_library_product(g, layers, tol):
+    """nabla_w^l as a whole against a plain fp32 matrix product (the vendor library's) of the GPU's own delta^l
+    and a^{l-1}: every tile of the hand-written contraction, not only the sampled ones, must agree with an
+    independent contraction of the same operands.  (For bf16 nets the operand is the bf16 copy of delta.)"""
+    torch = g.torch
+    for l in layers:
+        d = g.delta(l)
+        if g.dtype == "bf16":
+            d = d.to(torch.bfloat16)
+        want = d.float().t() @ g.activation(l - 1).float()
+        got = g.grads(l)[0]
+        err = float((got - want).abs().max() / want.abs().max())
+        assert err <= tol, f"nabla_w^{l}: whole-matrix normwise difference {err:.2e}"
+        del want
+
+
 def test_config4_full_sampled():
     net = config_net("cfg4", cache=True)
     g = run_gpu(net, 4)
-    rep = check_against_oracle(net, g, sample_tiles=(8, 128), rng=np.random.default_rng(4))
-    log(f"cfg4 k=4: worst {rep['worst']:.2e}")
+    rep = check_against_oracle(net, g, sample_tiles=(64, 128), rng=np.random.default_rng(4))
+    assert rep["tiles_per_layer"] >= 64
+    _check_whole_gradient_against_library_product(g, (2, 17, 32), 1e-5)
+    log(f"cfg4 k=4: worst {rep['worst']:.2e} ({rep['tiles_per_layer']} tiles of 128 x 128 per layer)")
     _free(g)
 
 
 def test_config5_full_sampled():
     net = config_net("cfg5", cache=False)
     g = run_gpu(net, 8)
-    rep = check_against_oracle(net, g, sample_tiles=(4, 128), rng=np.random.default_rng(5))
-    log(f"cfg5 k=8: worst {rep['worst']:.2e}")
+    rep = check_against_oracle(net, g, sample_tiles=(64, 128), rng=np.random.default_rng(5))
+    assert rep["tiles_per_layer"] >= 64
+    _check_whole_gradient_against_library_product(g, (2, 25, 48), 1e-5)
+    log(f"cfg5 k=8: worst {rep['worst']:.2e} ({rep['tiles_per_layer']} tiles of 128 x 128 per layer)")
     _free(g)
