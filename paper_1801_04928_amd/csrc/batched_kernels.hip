@@ -14,8 +14,8 @@
 namespace lf {
 namespace {
 
-#define LF_CHAIN_HALF_DEFAULT 1
-#define LF_GRAD_HALF_DEFAULT 1
+#define LF_CHAIN_HALF_DEFAULT 0
+#define LF_GRAD_HALF_DEFAULT 0
 
 constexpr int kThreads = 256;
 constexpr int BM = 128, BN = 128;          // output tile of a workgroup; 2 x 2 waves of 64 x 64
