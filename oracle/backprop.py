@@ -157,19 +157,17 @@ def backward_algorithm1(w, a, y, L: int, k: int):
         seeds[i] = chain_step(w[i + 1], seeds[i + 1], a[i])
         save(i, seeds[i], "parent")
 
-    # threads t_0 .. t_{k-1}; thread j starts from delta^{L-j}
+    # Thread t is handed delta^{L-t}.  Its own layers are every k-th one below that: L-t-k, L-t-2k, ... down
+    # to layer 2 at the lowest.  To reach the next of them it walks the k chain steps in between by itself
+    # (so every thread recomputes the chain) and saves the gradients only where it arrives.
     for t in range(k):
-        j = t
-        delta = seeds[L - t]
-        while j < L - k - 1:
-            i = 0
-            while i < k:
-                l = L - 1 - j - i
+        held = L - t                         # the layer whose delta the thread holds
+        delta = seeds[held]
+        for own in range(held - k, 1, -k):
+            for l in range(held - 1, own - 1, -1):
                 delta = chain_step(w[l + 1], delta, a[l])
-                if i == k - 1:
-                    save(l, delta, t)
-                i += 1
-            j += k
+            save(own, delta, t)
+            held = own
     return nb, nw, owner, writes
 
 
@@ -181,10 +179,8 @@ def worker_of_layer(L: int, k: int) -> Dict[int, int]:
     the top k layers."""
     owner = {}
     for t in range(k):
-        j = t
-        while j < L - k - 1:
-            owner[L - 1 - j - (k - 1)] = t
-            j += k
+        for own in range(L - t - k, 1, -k):      # the thread's layers: every k-th one below delta^{L-t}
+            owner[own] = t
     for l in range(L, max(L - k, 1), -1):
         owner[l] = (L - l) % k
     return owner
