@@ -14,9 +14,6 @@
 namespace lf {
 namespace {
 
-#define LF_CHAIN_HALF_DEFAULT 0
-#define LF_GRAD_HALF_DEFAULT 0
-
 constexpr int kThreads = 256;
 constexpr int BM = 128, BN = 128;          // output tile of a workgroup; 2 x 2 waves of 64 x 64
 
@@ -867,48 +864,48 @@ hipError_t run_half(GemmArgs g, int splits, hipStream_t s) {
     return hipGetLastError();
 }
 
-// Which of the two wide-net bf16 kernels a product takes: the 128 x 256 one that shares a compute unit (default),
-// or the 256 x 256 one.  LF_GEMM_CHAIN_TILE / LF_GEMM_GRAD_TILE = "big" or "half" override it (A/B runs, tests);
-// read once.
-bool chain_uses_half() {
-    static const int v = [] { const char* e = getenv("LF_GEMM_CHAIN_TILE"); return e ? (e[0] == 'h') : LF_CHAIN_HALF_DEFAULT; }();
-    return v != 0;
-}
-bool grad_uses_half() {
-    static const int v = [] { const char* e = getenv("LF_GEMM_GRAD_TILE"); return e ? (e[0] == 'h') : LF_GRAD_HALF_DEFAULT; }();
-    return v != 0;
-}
-// Workgroups the split of a chain-side product aims at (LF_GEMM_SPLIT_TARGET overrides; read once).
-int half_split_target() {
-    static const int v = [] { const char* e = getenv("LF_GEMM_SPLIT_TARGET"); const int t = e ? atoi(e) : 0; return t >= 64 && t <= 2048 ? t : 256; }();
-    return v;
-}
-
 }  // namespace
 
-// Whether a net whose widest layer has N neurons takes the 256 x 256 bf16 kernel: when the forward product of
-// such a layer has at least 64 such tiles.  LF_GEMM_BIG=0/1 forces the choice (tests, A/B runs); the caller decides once per net.
-bool gemm_use_big(int N, int B, bool bf16) {
-    if (!bf16) return false;
+// Which kernels a minibatch net takes, decided once per net from its widest layer.  bf16 nets whose forward
+// product has at least 64 tiles of 256 x 256 take the wide-net kernels: by default the 256 x 256-tile kernel for
+// all three products (measured faster than the 128 x 256 one, alone and beside each other).  Overrides for
+// tests and A/B runs, read when the plan is made:
+// LF_GEMM_BIG=0/1 forces the narrow / wide-net kernels; LF_GEMM_CHAIN_TILE and LF_GEMM_GRAD_TILE = "big" or
+// "half" pick the wide-net kernel of the forward and chain products and of the gradient product;
+// LF_GEMM_SPLIT_TARGET = workgroups the split of a chain-side product aims at.
+GemmPlan gemm_plan(int N, int B, bool bf16) {
+    GemmPlan p{GEMM_128, GEMM_128, 512};
+    if (!bf16) return p;
+    bool wide = ceil_div(B, big::TM) * ceil_div(N, big::TN) >= 64;
     if (const char* e = getenv("LF_GEMM_BIG")) {
-        if (e[0] == '0') return false;
-        if (e[0] == '1') return true;
+        if (e[0] == '0') wide = false;
+        if (e[0] == '1') wide = true;
     }
-    return ceil_div(B, big::TM) * ceil_div(N, big::TN) >= 64;
+    if (!wide) return p;
+    p.chain = GEMM_BIG;
+    p.grad = GEMM_BIG;
+    p.split_target = 256;
+    if (const char* e = getenv("LF_GEMM_CHAIN_TILE")) p.chain = e[0] == 'b' ? GEMM_BIG : GEMM_HALF;
+    if (const char* e = getenv("LF_GEMM_GRAD_TILE")) p.grad = e[0] == 'b' ? GEMM_BIG : GEMM_HALF;
+    if (const char* e = getenv("LF_GEMM_SPLIT_TARGET")) {
+        const int t = atoi(e);
+        if (t >= 64 && t <= 2048) p.split_target = t;
+    }
+    return p;
 }
 
 // Number of K splits used for the two chain-side GEMMs (their output, B x n_out, is small, so a single pass
 // over the contraction length K would leave most compute units idle).  Depends on the shape (and the kernel
 // chosen) alone.
-int chain_splits(int n_out, int K, int B, bool bf16, bool big_tiles) {
-    if (big_tiles && chain_uses_half()) {
+int chain_splits(int n_out, int K, int B, bool bf16, int kernel, int target) {
+    if (kernel == GEMM_HALF) {
         const int tiles = ceil_div(n_out, half::TN) * ceil_div(B, half::TM);
         const int kt = ceil_div(K, half::TK);
         int s = 1;
-        while (tiles * s < half_split_target() && s < 16 && kt / (s * 2) >= 8) s *= 2;
+        while (tiles * s < target && s < 16 && kt / (s * 2) >= 8) s *= 2;
         return s;
     }
-    if (big_tiles) {
+    if (kernel == GEMM_BIG) {
         const int tiles = ceil_div(n_out, big::TN) * ceil_div(B, big::TM);
         const int kt = ceil_div(K, big::TK);
         int s = 1;
@@ -923,27 +920,27 @@ int chain_splits(int n_out, int K, int B, bool bf16, bool big_tiles) {
 }
 
 size_t split_workspace_floats(int n_out, int K, int B, bool bf16) {      // enough for any of the kernels
-    int s = chain_splits(n_out, K, B, bf16, false);
+    int s = chain_splits(n_out, K, B, bf16, GEMM_128, 512);
     if (bf16) s = max(s, 16);
     return s > 1 ? (size_t)s * B * n_out : 0;
 }
 
 template <typename T>
 static hipError_t fwd_impl(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
-                           int n_out, int n_in, int B, bool big_tiles, hipStream_t s) {
+                           int n_out, int n_in, int B, const GemmPlan& plan, hipStream_t s) {
     constexpr bool bf = sizeof(T) == 2;
-    const int splits = chain_splits(n_out, n_in, B, bf, big_tiles);
+    const int splits = chain_splits(n_out, n_in, B, bf, plan.chain, plan.split_target);
     GemmArgs g{};
     g.P = A_in; g.ldp = n_in; g.Q = W; g.ldq = n_in; g.M = B; g.Nn = n_out; g.K = n_in;
     g.k_tiles_per_split = ceil_div(ceil_div(n_in, Tile<T>::BK), splits);
     g.bias = bias; g.out = A_out; g.raw = raw;
     hipError_t e;
     if constexpr (bf) {
-        if (big_tiles && chain_uses_half()) {
+        if (plan.chain == GEMM_HALF) {
             g.k_tiles_per_split = ceil_div(ceil_div(n_in, half::TK), splits);
             if (splits == 1) return run_half<false, false, EPI_SIGMOID>(g, 1, s);
             e = run_half<false, false, EPI_RAW>(g, splits, s);
-        } else if (big_tiles) {
+        } else if (plan.chain == GEMM_BIG) {
             if (splits == 1) return run_big<false, false, EPI_SIGMOID>(g, 1, s);
             e = run_big<false, false, EPI_RAW>(g, splits, s);
         } else {
@@ -963,21 +960,21 @@ static hipError_t fwd_impl(const void* W, const float* bias, const void* A_in, v
 
 template <typename T>
 static hipError_t chain_impl(const void* W_next, const void* D_next_op, const void* A_l, float* D_l,
-                             void* D_l_bf, float* raw, int n_l, int n_next, int B, bool big_tiles,
+                             void* D_l_bf, float* raw, int n_l, int n_next, int B, const GemmPlan& plan,
                              hipStream_t s) {
     constexpr bool bf = sizeof(T) == 2;
-    const int splits = chain_splits(n_l, n_next, B, bf, big_tiles);
+    const int splits = chain_splits(n_l, n_next, B, bf, plan.chain, plan.split_target);
     GemmArgs g{};
     g.P = D_next_op; g.ldp = n_next; g.Q = W_next; g.ldq = n_l; g.M = B; g.Nn = n_l; g.K = n_next;
     g.k_tiles_per_split = ceil_div(ceil_div(n_next, Tile<T>::BK), splits);
     g.act = A_l; g.out = D_l; g.out_bf = D_l_bf; g.raw = raw;
     hipError_t e;
     if constexpr (bf) {
-        if (big_tiles && chain_uses_half()) {
+        if (plan.chain == GEMM_HALF) {
             g.k_tiles_per_split = ceil_div(ceil_div(n_next, half::TK), splits);
             if (splits == 1) return run_half<false, true, EPI_SIGMA_PRIME>(g, 1, s);
             e = run_half<false, true, EPI_RAW>(g, splits, s);
-        } else if (big_tiles) {
+        } else if (plan.chain == GEMM_BIG) {
             if (splits == 1) return run_big<false, true, EPI_SIGMA_PRIME>(g, 1, s);
             e = run_big<false, true, EPI_RAW>(g, splits, s);
         } else {
@@ -996,20 +993,21 @@ static hipError_t chain_impl(const void* W_next, const void* D_next_op, const vo
 }
 
 hipError_t launch_fwd_gemm(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
-                           int n_out, int n_in, int B, bool bf16, bool big_tiles, hipStream_t s) {
-    return bf16 ? fwd_impl<__bf16>(W, bias, A_in, A_out, raw, n_out, n_in, B, big_tiles, s)
-                : fwd_impl<float>(W, bias, A_in, A_out, raw, n_out, n_in, B, false, s);
+                           int n_out, int n_in, int B, bool bf16, const GemmPlan& plan, hipStream_t s) {
+    return bf16 ? fwd_impl<__bf16>(W, bias, A_in, A_out, raw, n_out, n_in, B, plan, s)
+                : fwd_impl<float>(W, bias, A_in, A_out, raw, n_out, n_in, B, GemmPlan{GEMM_128, GEMM_128, 512}, s);
 }
 
 hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void* D_next_bf,
                              const void* A_l, float* D_l, void* D_l_bf, float* raw, int n_l, int n_next,
-                             int B, bool bf16, bool big_tiles, hipStream_t s) {
-    return bf16 ? chain_impl<__bf16>(W_next, D_next_bf, A_l, D_l, D_l_bf, raw, n_l, n_next, B, big_tiles, s)
-                : chain_impl<float>(W_next, D_next, A_l, D_l, nullptr, raw, n_l, n_next, B, false, s);
+                             int B, bool bf16, const GemmPlan& plan, hipStream_t s) {
+    return bf16 ? chain_impl<__bf16>(W_next, D_next_bf, A_l, D_l, D_l_bf, raw, n_l, n_next, B, plan, s)
+                : chain_impl<float>(W_next, D_next, A_l, D_l, nullptr, raw, n_l, n_next, B,
+                                    GemmPlan{GEMM_128, GEMM_128, 512}, s);
 }
 
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
-                            float* nabla_b, int n_l, int n_prev, int B, bool bf16, bool big_tiles,
+                            float* nabla_b, int n_l, int n_prev, int B, bool bf16, const GemmPlan& plan,
                             float sgd_eta, void* w_bf, hipStream_t s) {
     if (sgd_eta != 0.0f && bf16 != (w_bf != nullptr)) return hipErrorInvalidValue;
     k_bias_grad<<<ceil_div(n_l, 32), kThreads, 0, s>>>(D, nabla_b, n_l, B, sgd_eta);
@@ -1023,11 +1021,11 @@ hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev
     if (bf16) {
         g.P = D_bf;
         g.k_tiles_per_split = ceil_div(B, Tile<__bf16>::BK);
-        if (big_tiles && grad_uses_half()) {
+        if (plan.grad == GEMM_HALF) {
             g.k_tiles_per_split = ceil_div(B, half::TK);
             return run_half<true, true, EPI_GRAD>(g, 1, s);
         }
-        if (big_tiles) return run_big<true, true, EPI_GRAD>(g, 1, s);
+        if (plan.grad == GEMM_BIG) return run_big<true, true, EPI_GRAD>(g, 1, s);
         return run<__bf16, true, true, EPI_GRAD>(g, 1, s);
     }
     g.P = D;

@@ -150,7 +150,7 @@ struct lf_net {
     lf_sched sched;
     float cost_scale;
     float sgd_eta;                     // != 0: the workers apply the descent step instead of storing gradients
-    bool gemm_big;                     // minibatch bf16: the 256 x 256-tile kernel (decided at creation)
+    lf::GemmPlan gemm;                 // minibatch: which matrix kernels the products take (decided at creation)
     char* ws;
     Layout lay;
     std::vector<const void*> w;       // index l-2
@@ -400,7 +400,7 @@ lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
                                               out_w, out_b, net->width(l), net->width(l - 1), net->sgd_eta, s));
     } else {
         LF_HIP(net, lf::launch_grad_gemm(net->d_ptr(l), net->dbf_ptr(l), net->a_ptr(l - 1), out_w, out_b,
-                                         net->width(l), net->width(l - 1), net->B, bf, net->gemm_big,
+                                         net->width(l), net->width(l - 1), net->B, bf, net->gemm,
                                          net->sgd_eta, w_bf, s));
     }
     return LF_OK;
@@ -516,7 +516,7 @@ lf_status lf_create_widths(lf_net** out, int L, const int* n, int B, lf_dtype dt
     net->x1 = nullptr;
     net->have_params = net->have_grads = net->fwd_done = net->bwd_done = net->stepped = false;
     net->have_master = false;
-    net->gemm_big = lf::gemm_use_big(N, B, dt == LF_BF16);
+    net->gemm = lf::gemm_plan(N, B, dt == LF_BF16);
     net->debug_flags = 0; net->p_failed_over = false; net->p_fused_ok = false;
     net->p_ready = false; net->p_tables_dirty = true; net->p_groups = net->p_rpg = net->p_bgroups = net->p_tpr = 0; net->p_workers = 0;
     net->p_abort_host = nullptr; net->p_abort_dev_view = nullptr;
@@ -672,7 +672,7 @@ lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream) {
         } else {
             LF_HIP(net, lf::launch_fwd_gemm(net->w[l - 2], net->b[l - 2], net->a_ptr(l - 1), net->a_ptr(l),
                                             net->raw(), net->width(l), net->width(l - 1), net->B, bf,
-                                            net->gemm_big, s));
+                                            net->gemm, s));
         }
     }
     net->fwd_done = true;
@@ -741,7 +741,7 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
         } else {
             LF_HIP(net, lf::launch_chain_gemm(net->w[l - 1], net->d_ptr(l + 1), net->dbf_ptr(l + 1), net->a_ptr(l),
                                               net->d_ptr(l), net->dbf_ptr(l), net->raw(), net->width(l),
-                                              net->width(l + 1), B, bf, net->gemm_big, s));
+                                              net->width(l + 1), B, bf, net->gemm, s));
         }
         // (bp3),(bp4) of layer l, off the chain: as soon as delta^l is there.  With the descent step fused in
         // the worker rewrites w^l, which the chain still reads on its way to delta^{l-1}: layer l's work then

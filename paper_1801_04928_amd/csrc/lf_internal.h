@@ -41,20 +41,28 @@ hipError_t launch_output_error(const void* a_L, const void* y, float* delta_L, v
 // Floats of scratch the split-K stage of a forward / chain contraction with a B x n_out result and
 // contraction length K needs (0 = no split).
 size_t split_workspace_floats(int n_out, int K, int B, bool bf16);
-// Whether a net whose widest layer has N neurons takes the 256 x 256-tile bf16 kernel (decided once per net;
-// `big_tiles` below).
-bool gemm_use_big(int N, int B, bool bf16);
+// Which matrix kernel a product takes: 128 x 128 tiles (fp32; bf16 nets of moderate width), or one of the two
+// wide-net bf16 kernels -- 256 x 256 tiles filling a compute unit, or 128 x 256 tiles sized so that two
+// workgroups (of one product or of two) share a compute unit.
+enum GemmKernel { GEMM_128 = 0, GEMM_BIG = 1, GEMM_HALF = 2 };
+struct GemmPlan {
+    int chain;          // GemmKernel of the forward and chain products
+    int grad;           // GemmKernel of the gradient product
+    int split_target;   // workgroups the K split of a chain-side product aims at
+};
+// The plan of a net whose widest layer has N neurons (decided once per net).
+GemmPlan gemm_plan(int N, int B, bool bf16);
 
 // eqs. (z),(a) for a minibatch: A_out[b][j] = sigma(sum_k A_in[b][k] W[j][k] + bias[j]); W is n_out x n_in.
 // `raw` is the split-K scratch, split_workspace_floats(n_out, n_in, B, bf16) floats (may be NULL when that is 0).
 hipError_t launch_fwd_gemm(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
-                           int n_out, int n_in, int B, bool bf16, bool big_tiles, hipStream_t s);
+                           int n_out, int n_in, int B, bool bf16, const GemmPlan& plan, hipStream_t s);
 // eq. (bp2) for a minibatch: D_l[b][k] = (sum_j D_next[b][j] W_next[j][k]) A_l[b][k] (1 - A_l[b][k]);
 // W_next is n_next x n_l.  For bf16, D_next_bf / D_l_bf are the bfloat16 copies used as matrix operands.
 // raw: split_workspace_floats(n_l, n_next, B, bf16) floats.
 hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void* D_next_bf,
                              const void* A_l, float* D_l, void* D_l_bf, float* raw,
-                             int n_l, int n_next, int B, bool bf16, bool big_tiles, hipStream_t s);
+                             int n_l, int n_next, int B, bool bf16, const GemmPlan& plan, hipStream_t s);
 // eqs. (bp3),(bp4) for a minibatch: nabla_w[j][k] = sum_b D[b][j] A_prev[b][k] (n_l x n_prev);
 // nabla_b[j] = sum_b D[b][j] (fixed summation order).
 // sgd_eta != 0: the descent step fused into the epilogues -- nabla_w and nabla_b are then w^l (in fp32) and b^l
@@ -62,7 +70,7 @@ hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void
 // nabla_w is the fp32 master copy of w^l, and w_bf, the bfloat16 weights, are rewritten as its rounding (w_bf
 // is NULL exactly when the storage is fp32).
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
-                            float* nabla_b, int n_l, int n_prev, int B, bool bf16, bool big_tiles,
+                            float* nabla_b, int n_l, int n_prev, int B, bool bf16, const GemmPlan& plan,
                             float sgd_eta, void* w_bf, hipStream_t s);
 
 }  // namespace lf

@@ -374,19 +374,46 @@ def test_minibatch_matches_oracle(L, N, B, dtype, k):
     _free(g)
 
 
+@pytest.mark.parametrize("tile", ["half", "big"])
 @pytest.mark.parametrize("L,N,B,k", [
-    (3, 264, 70, 1),        # one ragged 256 x 256 tile per product; k-tiles 64 + 6
+    (3, 264, 70, 1),        # one ragged tile per product; a ragged last k-tile
     (4, 520, 260, 2),       # 3 x 3 tiles with ragged edges, split K on the chain side
     (3, 1024, 512, 2),      # full tiles only
+    (4, 2056, 136, 3),      # ragged last column tile, two row tiles of the 128 x 256 kernel, long K split
 ])
-def test_minibatch_bf16_large_tile_kernel_matches_oracle(monkeypatch, L, N, B, k):
-    """The 256 x 256-tile bf16 contraction kernel (the one wide bf16 nets take), forced at sizes the oracle
-    finishes quickly and that leave ragged tiles in every dimension."""
+def test_minibatch_bf16_large_tile_kernel_matches_oracle(monkeypatch, L, N, B, k, tile):
+    """The two bf16 contraction kernels of wide nets (256 x 256 tiles: the default; 128 x 256 tiles, two
+    workgroups per compute unit), forced at sizes the oracle finishes quickly and that leave ragged tiles in
+    every dimension.  Both kernels give the same bits for every k."""
+    import torch
     monkeypatch.setenv("LF_GEMM_BIG", "1")
+    monkeypatch.setenv("LF_GEMM_CHAIN_TILE", tile)
+    monkeypatch.setenv("LF_GEMM_GRAD_TILE", tile)
     net = make_net(L, N, B, dtype="bf16", seed=7 * N + B)
     g = run_gpu(net, k)
     rep = check_against_oracle(net, g)
-    log(f"large-tile bf16: B={B} L={L} N={N} k={k}: worst normwise error {rep['worst']:.2e}")
+    ref = [to_np(t).copy() for t in g.nabla_w] + [to_np(t).copy() for t in g.nabla_b]
+    poison_buffers(g, whole_workspace=False)
+    g.forward()
+    g.backward(1 if k > 1 else 2)
+    torch.cuda.synchronize()
+    for a, b in zip(ref, [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    log(f"wide-net bf16 kernel {tile}: B={B} L={L} N={N} k={k}: worst normwise error {rep['worst']:.2e}")
+    _free(g)
+
+
+@pytest.mark.parametrize("target", ["512", "1024"])
+def test_minibatch_bf16_half_tile_kernel_deeper_split(monkeypatch, target):
+    """The 128 x 256-tile kernel with the chain-side products split further along K (more, shorter workgroups)."""
+    monkeypatch.setenv("LF_GEMM_BIG", "1")
+    monkeypatch.setenv("LF_GEMM_CHAIN_TILE", "half")
+    monkeypatch.setenv("LF_GEMM_GRAD_TILE", "half")
+    monkeypatch.setenv("LF_GEMM_SPLIT_TARGET", target)
+    net = make_net(3, 2048, 136, dtype="bf16", seed=int(target))
+    g = run_gpu(net, 2)
+    rep = check_against_oracle(net, g)
+    log(f"wide-net bf16 kernel, split target {target}: worst normwise error {rep['worst']:.2e}")
     _free(g)
 
 
@@ -526,8 +553,9 @@ def test_fused_descent_step(shape, B, k, sched):
     _free(g)
 
 
-@pytest.mark.parametrize("L,N,B,k,big", [(4, 264, 70, 2, "0"), (3, 520, 260, 1, "1")])
-def test_fused_descent_step_bf16_master_weights(monkeypatch, L, N, B, k, big):
+@pytest.mark.parametrize("L,N,B,k,big,tile", [(4, 264, 70, 2, "0", "half"), (3, 520, 260, 1, "1", "half"),
+                                              (3, 520, 260, 1, "1", "big")])
+def test_fused_descent_step_bf16_master_weights(monkeypatch, L, N, B, k, big, tile):
     """bfloat16 storage: the step is taken on fp32 master copies and the bf16 weights are rewritten as their
     rounding.  Checked against the gradients the library stores without the step (master' is the fp32 value
     nearest to master - eta g), against the oracle's step within the bf16 tolerance, for w = rne(master')
@@ -537,6 +565,7 @@ def test_fused_descent_step_bf16_master_weights(monkeypatch, L, N, B, k, big):
     from lf_inputs import round_to_bf16
     from oracle import backprop as O
     monkeypatch.setenv("LF_GEMM_BIG", big)
+    monkeypatch.setenv("LF_GEMM_GRAD_TILE", tile)
     net = make_net(L, N, B, dtype="bf16", seed=N + B)
     g = run_gpu(net, k)
     check_against_oracle(net, g)
