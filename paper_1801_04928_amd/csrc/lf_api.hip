@@ -225,7 +225,13 @@ lf_status ensure_worker_streams(lf_net* net, size_t want) {
 
 // The stream schedule's workers: k streams (none for the sequential pass, which runs on the caller's).
 lf_status ensure_workers(lf_net* net, int k) {
-    return ensure_worker_streams(net, k > 1 ? (size_t)(k < kMaxWorkerStreams ? k : kMaxWorkerStreams) : 0);
+    // LF_WORKER_STREAMS (tuning): fewer streams than workers; worker j then runs on stream j mod that number
+    int cap = kMaxWorkerStreams;
+    if (const char* e = std::getenv("LF_WORKER_STREAMS")) {
+        const int v = std::atoi(e);
+        if (v >= 1 && v <= kMaxWorkerStreams) cap = v;
+    }
+    return ensure_worker_streams(net, k > 1 ? (size_t)(k < cap ? k : cap) : 0);
 }
 
 bool persistent_possible(const lf_net* net) {
@@ -407,11 +413,10 @@ lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
 }
 
 // The same on worker (L - l) mod k, once `ready` (an event recorded on the chain's stream) has passed.
-lf_status enqueue_grads_on_worker(lf_net* net, int l, int k, int nstreams, hipEvent_t ready,
-                                  std::vector<char>& used) {
+lf_status enqueue_grads_on_worker(lf_net* net, int l, int k, int nstreams, hipEvent_t ready, bool* used) {
     const int j = lf_schedule_worker(net->L, k, l) % nstreams;
     LF_HIP(net, hipStreamWaitEvent(net->workers[j], ready, 0));
-    used[j] = 1;
+    used[j] = true;
     return enqueue_grads(net, l, net->workers[j]);
 }
 
@@ -471,6 +476,81 @@ lf_status backward_redundant(lf_net* net, const void* y, int k, hipStream_t s) {
         LF_HIP(net, hipEventRecord(net->ev_done[j], q));
         LF_HIP(net, hipStreamWaitEvent(s, net->ev_done[j], 0));   // the join
     }
+    return LF_OK;
+}
+
+// Argument and state checks shared by the backward entry points.
+lf_status check_backward_call(lf_net* net, const void* y, int k) {
+    if (!y) return fail(net, LF_EINVAL, "lf_backward_leapfrog: y is NULL");
+    if (!aligned16(y)) return fail(net, LF_EINVAL, "lf_backward_leapfrog: y must be 16-byte aligned");
+    if (k < 1 || k > net->L - 1) return fail(net, LF_EINVAL, "lf_backward_leapfrog: need 1 <= k <= L-1");
+    if (!net->have_params) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_params first");
+    if (!net->have_grads && net->sgd_eta == 0.0f)
+        return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_grad_buffers first");
+    if (net->sgd_eta != 0.0f && net->dt == LF_BF16 && !net->have_master)
+        return fail(net, LF_ESTATE, "lf_backward_leapfrog: lf_set_sgd on a bf16 net needs lf_set_master_weights");
+    if (!net->fwd_done) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_forward first");
+    if (net->stepped)
+        return fail(net, LF_ESTATE, "lf_backward_leapfrog: the weights have been stepped since lf_forward; run it again");
+    if ((net->debug_flags & LF_DEBUG_CHAIN_ONLY) && net->sgd_eta != 0.0f)
+        return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog: LF_DEBUG_CHAIN_ONLY and lf_set_sgd exclude each other");
+    return LF_OK;
+}
+
+// The stream realisation of the schedule.  The chain runs on s; `partial` / `raw` are the scratch of its
+// products (the row-block partial sums of the single-sample step, the split-K partials of the minibatch
+// products).  in_line: layer l's gradient kernels follow delta^l on s itself (the sequential pass; also the
+// entry point that may not create streams); otherwise worker (L - l) mod k's stream takes them behind an event.
+lf_status backward_streams(lf_net* net, const void* y, int k, hipStream_t s, float* partial, float* raw,
+                           bool in_line) {
+    const int L = net->L, N = net->N, B = net->B;
+    const bool bf = net->dt == LF_BF16;
+    const bool b1 = single_sample_path(N, B, net->dt);
+    const bool chain_only = (net->debug_flags & LF_DEBUG_CHAIN_ONLY) != 0;
+    const bool sgd = net->sgd_eta != 0.0f;
+    const int nstreams = in_line ? 0 : ((int)net->workers.size() < k ? (int)net->workers.size() : k);
+    bool used[kMaxWorkerStreams] = {};
+    lf_status st = LF_OK;
+    for (int l = L; l >= 2; --l) {
+        // the chain: (bp1) at L, (bp2) below
+        if (l == L) {
+            LF_HIP(net, lf::launch_output_error(net->a_ptr(L), y, net->d_ptr(L), net->dbf_ptr(L),
+                                                (size_t)B * net->width(L), bf, net->cost_scale, s));
+        } else if (b1) {
+            // w^{l+1} has n_{l+1} rows and n_l columns
+            LF_HIP(net, lf::launch_chain_gemvT_f32(static_cast<const float*>(net->w[l - 1]), net->d_ptr(l + 1),
+                                                   static_cast<const float*>(net->a_ptr(l)), net->d_ptr(l),
+                                                   partial, net->width(l + 1), net->width(l), s));
+        } else {
+            LF_HIP(net, lf::launch_chain_gemm(net->w[l - 1], net->d_ptr(l + 1), net->dbf_ptr(l + 1), net->a_ptr(l),
+                                              net->d_ptr(l), net->dbf_ptr(l), raw, net->width(l),
+                                              net->width(l + 1), B, bf, net->gemm, s));
+        }
+        // (bp3),(bp4) of layer l, off the chain: as soon as delta^l is there.  With the descent step fused in
+        // the worker rewrites w^l, which the chain still reads on its way to delta^{l-1}: layer l's work then
+        // starts once delta^{l-1} is there (layer 2's, whose weights the chain never reads, with delta^2).
+        if (chain_only) continue;                       // the chain alone (a timing aid): no gradient is formed
+        if (in_line) {
+            if (!sgd || l == 2) st = enqueue_grads(net, l, s);
+            if (st == LF_OK && sgd && l < L) st = enqueue_grads(net, l + 1, s);
+            if (st != LF_OK) return st;
+        } else {
+            LF_HIP(net, hipEventRecord(net->ev_delta[l - 2], s));
+            if (!sgd || l == 2) st = enqueue_grads_on_worker(net, l, k, nstreams, net->ev_delta[l - 2], used);
+            if (st == LF_OK && sgd && l < L)
+                st = enqueue_grads_on_worker(net, l + 1, k, nstreams, net->ev_delta[l - 2], used);
+            if (st != LF_OK) return st;
+        }
+    }
+    if (!in_line && !chain_only) {   // join
+        for (int j = 0; j < nstreams; ++j) {
+            if (!used[j]) continue;
+            LF_HIP(net, hipEventRecord(net->ev_done[j], net->workers[j]));
+            LF_HIP(net, hipStreamWaitEvent(s, net->ev_done[j], 0));
+        }
+    }
+    net->bwd_done = !chain_only;
+    if (sgd) net->stepped = true;                      // the stored activations belong to the old weights
     return LF_OK;
 }
 
@@ -681,27 +761,13 @@ lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream) {
 
 lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stream) {
     if (!net) return LF_EINVAL;
-    if (!y) return fail(net, LF_EINVAL, "lf_backward_leapfrog: y is NULL");
-    if (!aligned16(y)) return fail(net, LF_EINVAL, "lf_backward_leapfrog: y must be 16-byte aligned");
-    if (k < 1 || k > net->L - 1) return fail(net, LF_EINVAL, "lf_backward_leapfrog: need 1 <= k <= L-1");
-    if (!net->have_params) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_params first");
-    if (!net->have_grads && net->sgd_eta == 0.0f)
-        return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_set_grad_buffers first");
-    if (net->sgd_eta != 0.0f && net->dt == LF_BF16 && !net->have_master)
-        return fail(net, LF_ESTATE, "lf_backward_leapfrog: lf_set_sgd on a bf16 net needs lf_set_master_weights");
-    if (!net->fwd_done) return fail(net, LF_ESTATE, "lf_backward_leapfrog: call lf_forward first");
-    if (net->stepped)
-        return fail(net, LF_ESTATE, "lf_backward_leapfrog: the weights have been stepped since lf_forward; run it again");
+    lf_status st = check_backward_call(net, y, k);
+    if (st != LF_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int L = net->L, N = net->N, B = net->B;
-    const bool bf = net->dt == LF_BF16;
-    const bool b1 = single_sample_path(N, B, net->dt);
     net->bwd_done = false;
-    lf_status st = check_abort(net);
+    st = check_abort(net);
     if (st != LF_OK) return st;
     const bool chain_only = (net->debug_flags & LF_DEBUG_CHAIN_ONLY) != 0;
-    if (chain_only && net->sgd_eta != 0.0f)
-        return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog: LF_DEBUG_CHAIN_ONLY and lf_set_sgd exclude each other");
     if (chain_only && net->sched == LF_SCHED_REDUNDANT)
         return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog: LF_DEBUG_CHAIN_ONLY has no meaning for LF_SCHED_REDUNDANT");
     if (use_persistent(net)) {
@@ -725,51 +791,7 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
     }
     st = ensure_workers(net, k);
     if (st != LF_OK) return st;
-    const int nstreams = (int)net->workers.size() < k ? (int)net->workers.size() : k;
-    std::vector<char> used(nstreams > 0 ? nstreams : 1, 0);
-
-    for (int l = L; l >= 2; --l) {
-        // the chain: (bp1) at L, (bp2) below
-        if (l == L) {
-            LF_HIP(net, lf::launch_output_error(net->a_ptr(L), y, net->d_ptr(L), net->dbf_ptr(L),
-                                                (size_t)B * net->width(L), bf, net->cost_scale, s));
-        } else if (b1) {
-            // w^{l+1} has n_{l+1} rows and n_l columns
-            LF_HIP(net, lf::launch_chain_gemvT_f32(static_cast<const float*>(net->w[l - 1]), net->d_ptr(l + 1),
-                                                   static_cast<const float*>(net->a_ptr(l)), net->d_ptr(l),
-                                                   net->partial(), net->width(l + 1), net->width(l), s));
-        } else {
-            LF_HIP(net, lf::launch_chain_gemm(net->w[l - 1], net->d_ptr(l + 1), net->dbf_ptr(l + 1), net->a_ptr(l),
-                                              net->d_ptr(l), net->dbf_ptr(l), net->raw(), net->width(l),
-                                              net->width(l + 1), B, bf, net->gemm, s));
-        }
-        // (bp3),(bp4) of layer l, off the chain: as soon as delta^l is there.  With the descent step fused in
-        // the worker rewrites w^l, which the chain still reads on its way to delta^{l-1}: layer l's work then
-        // starts once delta^{l-1} is there (layer 2's, whose weights the chain never reads, with delta^2).
-        const bool sgd = net->sgd_eta != 0.0f;
-        if (chain_only) continue;                       // the chain alone (a timing aid): no gradient is formed
-        if (k == 1) {
-            if (!sgd || l == 2) st = enqueue_grads(net, l, s);
-            if (st == LF_OK && sgd && l < L) st = enqueue_grads(net, l + 1, s);
-            if (st != LF_OK) return st;
-        } else {
-            LF_HIP(net, hipEventRecord(net->ev_delta[l - 2], s));
-            if (!sgd || l == 2) st = enqueue_grads_on_worker(net, l, k, nstreams, net->ev_delta[l - 2], used);
-            if (st == LF_OK && sgd && l < L)
-                st = enqueue_grads_on_worker(net, l + 1, k, nstreams, net->ev_delta[l - 2], used);
-            if (st != LF_OK) return st;
-        }
-    }
-    if (k > 1 && !chain_only) {   // join
-        for (int j = 0; j < nstreams; ++j) {
-            if (!used[j]) continue;
-            LF_HIP(net, hipEventRecord(net->ev_done[j], net->workers[j]));
-            LF_HIP(net, hipStreamWaitEvent(s, net->ev_done[j], 0));
-        }
-    }
-    net->bwd_done = !chain_only;
-    if (net->sgd_eta != 0.0f) net->stepped = true;     // the stored activations belong to the old weights
-    return LF_OK;
+    return backward_streams(net, y, k, s, net->partial(), net->raw(), /*in_line=*/k == 1);
 }
 
 lf_status lf_grads(lf_net* net, int l, const float** nabla_w, const float** nabla_b) {
