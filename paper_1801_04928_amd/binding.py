@@ -39,6 +39,12 @@ def lib() -> C.CDLL:
         path = library_path()
         if not os.path.exists(path):
             raise RuntimeError(f"{path} is missing: build it with `python -m paper_1801_04928_amd.build`")
+        # PyTorch brings a HIP runtime of its own; the library must bind to that same runtime, not to a second
+        # copy loaded before it (two runtimes in one process do not share a device context), so torch goes first.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(path)
         vp, vpp, i, sz = C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_size_t
         L.lf_workspace_bytes.restype, L.lf_workspace_bytes.argtypes = sz, [i, i, i, i]
@@ -55,6 +61,8 @@ def lib() -> C.CDLL:
         L.lf_set_master_weights.restype, L.lf_set_master_weights.argtypes = i, [vp, vpp]
         L.lf_forward.restype, L.lf_forward.argtypes = i, [vp, vp, vp]
         L.lf_backward_leapfrog.restype, L.lf_backward_leapfrog.argtypes = i, [vp, vp, i, vp]
+        L.lf_backward_leapfrog_noalloc.restype, L.lf_backward_leapfrog_noalloc.argtypes = i, [vp, vp, i, vp]
+        L.lf_noalloc_scratch_limit.restype, L.lf_noalloc_scratch_limit.argtypes = sz, []
         L.lf_grads.restype, L.lf_grads.argtypes = i, [vp, i, vpp, vpp]
         L.lf_activations.restype, L.lf_activations.argtypes = i, [vp, i, vpp, vpp]
         L.lf_schedule_worker.restype, L.lf_schedule_worker.argtypes = i, [i, i, i]
@@ -135,6 +143,14 @@ def lf_forward(net, x1: int, hip_stream: int = 0) -> int:
 
 def lf_backward_leapfrog(net, y: int, k: int, hip_stream: int = 0) -> int:
     return lib().lf_backward_leapfrog(net, C.c_void_p(y), k, C.c_void_p(hip_stream))
+
+
+def lf_backward_leapfrog_noalloc(net, y: int, k: int, hip_stream: int = 0) -> int:
+    return lib().lf_backward_leapfrog_noalloc(net, C.c_void_p(y), k, C.c_void_p(hip_stream))
+
+
+def lf_noalloc_scratch_limit() -> int:
+    return int(lib().lf_noalloc_scratch_limit())
 
 
 def lf_grads(net, l: int):
