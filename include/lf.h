@@ -194,6 +194,25 @@ lf_status lf_forward(lf_net* net, const void* x1, void* hip_stream);
  * LF_EINVAL unless 1 <= k <= L-1. */
 lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stream);
 
+/* lf_backward_leapfrog for callers that cannot allocate: code that records the pass into a HIP graph on its
+ * first call, tight serving loops, harnesses that forbid hipMalloc.  (lf_backward_leapfrog may create worker
+ * streams and events, or pinned memory, the first time a handle runs with a new k or schedule.)  This call
+ * allocates nothing, on the device or through any library: it enqueues the stream schedule's kernels -- chain
+ * and gradient kernels of layer L, L-1, ..., 2 in that order -- on hip_stream alone, and the scratch of the chain
+ * products (row-block partial sums at B = 1, split-K partials of a minibatch) is a static device array inside
+ * the library instead of the caller's workspace.  Same arguments, same checks, same results bit for bit as
+ * lf_backward_leapfrog with LF_SCHED_STREAMS (k only names the worker a layer would belong to; the gradients do
+ * not depend on it).  lf_forward must have run (with LF_SCHED_STREAMS it allocates nothing either).
+ * Limits: the chain scratch of the net's shape (a part of lf_workspace_bytes) must fit
+ * lf_noalloc_scratch_limit() bytes -- 8 MiB: every B = 1 net up to N = 8192, small minibatch nets -- else
+ * LF_EUNSUPPORTED, with both sizes in lf_last_error(); the handle's schedule
+ * must be LF_SCHED_AUTO, LF_SCHED_STREAMS or LF_SCHED_PERSISTENT (which only matter to the other calls).
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams, two
+ * handles, two threads) race on it; order them on one stream or with events.  The array is held from the
+ * first call on a GPU until the process ends. */
+lf_status lf_backward_leapfrog_noalloc(lf_net* net, const void* y, int k, void* hip_stream);
+size_t lf_noalloc_scratch_limit(void);
+
 /* Device pointers to nabla_w^l and nabla_b^l of the last backward pass (the
  * registered buffers).  Valid to read once the stream of that pass has reached
  * the end of it.  LF_ESTATE if no backward pass has been enqueued. */

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     LfError, lib, library_path,
     lf_workspace_bytes, lf_create, lf_workspace_bytes_widths, lf_create_widths,
     lf_set_params, lf_set_grad_buffers, lf_set_schedule, lf_set_debug_flags, lf_set_cost_scale, lf_set_sgd, lf_set_master_weights,
-    lf_forward, lf_backward_leapfrog, lf_grads, lf_activations, lf_schedule_worker, lf_algorithm1_owner,
+    lf_forward, lf_backward_leapfrog, lf_backward_leapfrog_noalloc, lf_noalloc_scratch_limit, lf_grads, lf_activations, lf_schedule_worker, lf_algorithm1_owner,
     lf_last_error, lf_destroy,
     LeapfrogNet,
 )

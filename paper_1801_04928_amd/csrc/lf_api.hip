@@ -12,11 +12,22 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
 
+// Scratch of lf_backward_leapfrog_noalloc: device memory that exists from the moment the library is loaded, so
+// that the call needs no allocation.  Every GPU the library runs on holds its own copy at its own address; in
+// host code the name below is only a handle for hipGetSymbolAddress, never an address to hand to a kernel.
+#define LF_STATIC_SCRATCH_BYTES (8u << 20)
+static __device__ __align__(256) unsigned char scratch[LF_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_static_scratch[kMaxDevices];   // device address of `scratch` on each device; null = not asked yet
+std::mutex g_static_scratch_mutex;
 
 constexpr size_t kAlign = 256;
 constexpr int kMaxL = 4096;
@@ -554,6 +565,23 @@ lf_status backward_streams(lf_net* net, const void* y, int k, hipStream_t s, flo
     return LF_OK;
 }
 
+// Address of this device's copy of `scratch` (asked once per device, with that device current).
+lf_status static_scratch_of_current_device(lf_net* net, void** out) {
+    int dev = -1;
+    LF_HIP(net, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog_noalloc: device index beyond 63");
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch[dev]) {
+        void* p = nullptr;
+        LF_HIP(net, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(net, LF_EHIP, "lf_backward_leapfrog_noalloc: the static scratch has no device address");
+        g_static_scratch[dev] = p;
+    }
+    *out = g_static_scratch[dev];
+    return LF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -792,6 +820,29 @@ lf_status lf_backward_leapfrog(lf_net* net, const void* y, int k, void* hip_stre
     st = ensure_workers(net, k);
     if (st != LF_OK) return st;
     return backward_streams(net, y, k, s, net->partial(), net->raw(), /*in_line=*/k == 1);
+}
+
+size_t lf_noalloc_scratch_limit(void) { return LF_STATIC_SCRATCH_BYTES; }
+
+lf_status lf_backward_leapfrog_noalloc(lf_net* net, const void* y, int k, void* hip_stream) {
+    if (!net) return LF_EINVAL;
+    lf_status st = check_backward_call(net, y, k);
+    if (st != LF_OK) return st;
+    if (net->sched == LF_SCHED_REDUNDANT || net->sched == LF_SCHED_FUSED)
+        return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog_noalloc: runs the stream schedule's kernels only");
+    const size_t need = net->lay.partial_bytes > net->lay.raw_bytes ? net->lay.partial_bytes : net->lay.raw_bytes;
+    if (need > LF_STATIC_SCRATCH_BYTES)
+        return fail(net, LF_EUNSUPPORTED,
+                    "lf_backward_leapfrog_noalloc: this shape needs " + std::to_string(need) +
+                        " bytes of chain scratch, the static scratch holds " + std::to_string(LF_STATIC_SCRATCH_BYTES));
+    void* area = nullptr;
+    st = static_scratch_of_current_device(net, &area);
+    if (st != LF_OK) return st;
+    net->bwd_done = false;
+    // every word of the scratch a pass reads it has written before (the chain's partial sums are stored
+    // whole, then summed): nothing needs clearing between calls
+    return backward_streams(net, y, k, static_cast<hipStream_t>(hip_stream), static_cast<float*>(area),
+                            static_cast<float*>(area), /*in_line=*/true);
 }
 
 lf_status lf_grads(lf_net* net, int l, const float** nabla_w, const float** nabla_b) {
