@@ -551,6 +551,125 @@ __global__ __launch_bounds__(kThreadsBig) void k_gemm_big(const GemmArgs g) {
     }
 }
 
+// The gradient product nabla_w = D^T A_prev as one stream of k-tiles over several output tiles.
+// Its contraction (the minibatch) is short -- 8 k-tiles at B = 512 -- so a workgroup per output tile spends
+// more time starting up (launch, first operands from memory) and storing its 256 KB of fp32 results than
+// multiplying.  Here a workgroup is resident for the whole product and walks its tiles: the k-tiles of all of
+// them form one stream through the same double-buffered pipeline, so the first operands of the next tile are
+// requested, and written to LDS, while the current tile is still being multiplied.  At a tile's end every wave
+// stores its accumulators straight to memory (for a fixed accumulator element a half wave holds 32
+// consecutive columns of one row: one 128-byte line per row and store instruction; no LDS staging, which
+// would collide with the next tile's operands) and goes on multiplying with operands that arrived before
+// the stores were issued.
+template <int DUMMY>
+__global__ __launch_bounds__(kThreadsBig) void k_grad_stream(const GemmArgs g, int tiles_x, int tiles_total) {
+    __shared__ __attribute__((aligned(16))) __bf16 s_p0[ELEMS];
+    __shared__ __attribute__((aligned(16))) __bf16 s_q0[ELEMS];
+    __shared__ __attribute__((aligned(16))) __bf16 s_p1[ELEMS];
+    __shared__ __attribute__((aligned(16))) __bf16 s_q1[ELEMS];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
+    const int r32 = lane & 31, half = lane >> 5;
+    const int T = ceil_div(g.K, TK);                         // k-tiles per output tile
+    // my tiles: blockIdx.x, blockIdx.x + gridDim.x, ...  (with a multiple of 8 tile columns and a grid that is a
+    // multiple of 8, all of them lie in tile columns of one residue mod 8: the operands of one XCD's L2)
+    const int first = blockIdx.x, stride = gridDim.x;
+    const int mine = first < tiles_total ? (tiles_total - first + stride - 1) / stride : 0;
+
+    v16f acc[2][4];
+    auto clear = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    };
+    clear();
+
+    StageBig<true> sp, sq;
+    const __amdgpu_buffer_rsrc_t P = make_buffer(g.P, g.p_bytes);
+    const __amdgpu_buffer_rsrc_t Q = make_buffer(g.Q, g.q_bytes);
+    const __amdgpu_buffer_rsrc_t OUT = make_buffer(g.out, (unsigned)((size_t)g.M * g.Nn * 4u));
+    // the k-tile the next request fetches: tile number req_tile of mine, k-tile req_kt of it
+    int req_tile = 0, req_kt = 0;
+    auto request = [&]() {          // past my last tile: loads of zeros, no branch around a request
+        const bool live = req_tile < mine;
+        const int t = first + req_tile * stride;
+        const int m0 = (t / tiles_x) * TM, n0 = (t % tiles_x) * TN;
+        sp.load(P, g.ldp, m0, req_kt * TK, g.M, g.K, live);
+        sq.load(Q, g.ldq, n0, req_kt * TK, g.Nn, g.K, live);
+        if (++req_kt == T) { req_kt = 0; ++req_tile; }
+    };
+    auto multiply = [&](const __bf16* tp, const __bf16* tq) {
+#pragma unroll
+        for (int kk = 0; kk < TK; kk += 16) {
+            v8bf a[2], b[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = lds_operand_transposed(tp, LDI, wm + i * 32, kk);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = lds_operand_transposed(tq, LDI, wn + j * 32, kk);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    };
+    // Accumulator element e of lane (r32, half) in tile (i, j) is
+    // C[m0 + wm + 32 i + 8 (e/4) + 4 half + e%4][n0 + wn + 32 j + r32].  The whole byte offset of a store goes
+    // into the bounds-checked vector offset (a scalar offset would not be checked): a row past the end of the
+    // matrix then lies outside the buffer (no store; the launcher guarantees the sum cannot wrap), a column
+    // past the end is given an offset outside it.
+    auto store_tile = [&](int tile_no) {
+        const int t = first + tile_no * stride;
+        const int m0 = (t / tiles_x) * TM, n0 = (t % tiles_x) * TN;
+        const int n = n0 + wn + r32;
+        const unsigned lane_off = ((unsigned)(m0 + wm + 4 * half) * (unsigned)g.Nn + (unsigned)n) * 4u;
+        const unsigned row_bytes = (unsigned)g.Nn * 4u;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool col_ok = n + 32 * j < g.Nn;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const unsigned off = lane_off + 128u * j + (unsigned)(32 * i + 8 * (e >> 2) + (e & 3)) * row_bytes;
+                    const float v = acc[i][j][e];      // (a copy: a bit cast of the vector element itself reads element 0)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), OUT, col_ok ? off : kOutside, 0, 2);
+                }
+            }
+    };
+    int kt_in_tile = 0, tile_no = 0;
+    auto tile_block = [&](const __bf16* cur_p, const __bf16* cur_q, __bf16* nxt_p, __bf16* nxt_q) {
+        sp.store(nxt_p);
+        sq.store(nxt_q);
+        request();
+        multiply(cur_p, cur_q);
+        interleave<true, true>();
+        __syncthreads();
+        if (++kt_in_tile == T) {
+            store_tile(tile_no);
+            clear();
+            kt_in_tile = 0;
+            ++tile_no;
+        }
+    };
+    if (mine > 0) {
+        request();
+        sp.store(s_p0);
+        sq.store(s_q0);
+        request();
+        __syncthreads();
+        const int total = mine * T;
+        for (int it = 0; it < total; it += 2) {
+            tile_block(s_p0, s_q0, s_p1, s_q1);
+            if (it + 1 < total) tile_block(s_p1, s_q1, s_p0, s_q0);
+        }
+    }
+}
+
 static_assert(TK == Tile<__bf16>::BK, "both bf16 kernels count k-tiles of the same length");
 static_assert(2 * 2 * ELEMS * 2 <= 160 * 1024, "LDS of one compute unit");
 }  // namespace big
@@ -852,6 +971,19 @@ hipError_t run_big(GemmArgs g, int splits, hipStream_t s) {
     return hipGetLastError();
 }
 
+// The streamed gradient product (big::k_grad_stream): `groups` resident workgroups walk all output tiles.
+hipError_t run_grad_stream(GemmArgs g, int groups, hipStream_t s) {
+    const unsigned long long pb = (unsigned long long)g.K * g.ldp * 2ull, qb = (unsigned long long)g.K * g.ldq * 2ull;
+    // (the result is addressed with 32-bit offsets that may point up to one tile of rows past its end)
+    const unsigned long long ob = (unsigned long long)(g.M + big::TM) * g.Nn * 4ull;
+    if (pb >= 0xFFFFFFF0ull || qb >= 0xFFFFFFF0ull || ob >= 0xFFFFFFF0ull) return hipErrorInvalidValue;
+    g.p_bytes = (unsigned)pb;
+    g.q_bytes = (unsigned)qb;
+    const int tiles_x = ceil_div(g.Nn, big::TN), tiles = tiles_x * ceil_div(g.M, big::TM);
+    big::k_grad_stream<0><<<groups < tiles ? groups : tiles, big::kThreadsBig, 0, s>>>(g, tiles_x, tiles);
+    return hipGetLastError();
+}
+
 template <bool P_IC, bool Q_IC, int EPI>
 hipError_t run_half(GemmArgs g, int splits, hipStream_t s) {
     const unsigned long long pb = (unsigned long long)(P_IC ? g.K : g.M) * g.ldp * 2ull;
@@ -870,11 +1002,12 @@ hipError_t run_half(GemmArgs g, int splits, hipStream_t s) {
 // product has at least 64 tiles of 256 x 256 take the wide-net kernels: by default the 256 x 256-tile kernel for
 // all three products (measured faster than the 128 x 256 one, alone and beside each other).  Overrides for
 // tests and A/B runs, read when the plan is made:
-// LF_GEMM_BIG=0/1 forces the narrow / wide-net kernels; LF_GEMM_CHAIN_TILE and LF_GEMM_GRAD_TILE = "big" or
-// "half" pick the wide-net kernel of the forward and chain products and of the gradient product;
-// LF_GEMM_SPLIT_TARGET = workgroups the split of a chain-side product aims at.
+// LF_GEMM_BIG=0/1 forces the narrow / wide-net kernels; LF_GEMM_CHAIN_TILE = "big" or "half" picks the wide-net
+// kernel of the forward and chain products, LF_GEMM_GRAD_TILE = "stream" (default), "big" or "half" that of the
+// gradient product; LF_GEMM_SPLIT_TARGET = workgroups the split of a chain-side product aims at;
+// LF_GEMM_STREAM_GROUPS = resident workgroups of the streamed gradient product (default 256, one per compute unit).
 GemmPlan gemm_plan(int N, int B, bool bf16) {
-    GemmPlan p{GEMM_128, GEMM_128, 512};
+    GemmPlan p{GEMM_128, GEMM_128, 512, 256};
     if (!bf16) return p;
     bool wide = ceil_div(B, big::TM) * ceil_div(N, big::TN) >= 64;
     if (const char* e = getenv("LF_GEMM_BIG")) {
@@ -883,10 +1016,14 @@ GemmPlan gemm_plan(int N, int B, bool bf16) {
     }
     if (!wide) return p;
     p.chain = GEMM_BIG;
-    p.grad = GEMM_BIG;
+    p.grad = GEMM_STREAM;
     p.split_target = 256;
     if (const char* e = getenv("LF_GEMM_CHAIN_TILE")) p.chain = e[0] == 'b' ? GEMM_BIG : GEMM_HALF;
-    if (const char* e = getenv("LF_GEMM_GRAD_TILE")) p.grad = e[0] == 'b' ? GEMM_BIG : GEMM_HALF;
+    if (const char* e = getenv("LF_GEMM_GRAD_TILE")) p.grad = e[0] == 'b' ? GEMM_BIG : (e[0] == 's' ? GEMM_STREAM : GEMM_HALF);
+    if (const char* e = getenv("LF_GEMM_STREAM_GROUPS")) {
+        const int t = atoi(e);
+        if (t >= 8 && t <= 1024) p.stream_groups = t;
+    }
     if (const char* e = getenv("LF_GEMM_SPLIT_TARGET")) {
         const int t = atoi(e);
         if (t >= 64 && t <= 2048) p.split_target = t;
@@ -995,7 +1132,7 @@ static hipError_t chain_impl(const void* W_next, const void* D_next_op, const vo
 hipError_t launch_fwd_gemm(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
                            int n_out, int n_in, int B, bool bf16, const GemmPlan& plan, hipStream_t s) {
     return bf16 ? fwd_impl<__bf16>(W, bias, A_in, A_out, raw, n_out, n_in, B, plan, s)
-                : fwd_impl<float>(W, bias, A_in, A_out, raw, n_out, n_in, B, GemmPlan{GEMM_128, GEMM_128, 512}, s);
+                : fwd_impl<float>(W, bias, A_in, A_out, raw, n_out, n_in, B, GemmPlan{GEMM_128, GEMM_128, 512, 256}, s);
 }
 
 hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void* D_next_bf,
@@ -1003,7 +1140,7 @@ hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void
                              int B, bool bf16, const GemmPlan& plan, hipStream_t s) {
     return bf16 ? chain_impl<__bf16>(W_next, D_next_bf, A_l, D_l, D_l_bf, raw, n_l, n_next, B, plan, s)
                 : chain_impl<float>(W_next, D_next, A_l, D_l, nullptr, raw, n_l, n_next, B,
-                                    GemmPlan{GEMM_128, GEMM_128, 512}, s);
+                                    GemmPlan{GEMM_128, GEMM_128, 512, 256}, s);
 }
 
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
@@ -1025,7 +1162,12 @@ hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev
             g.k_tiles_per_split = ceil_div(B, half::TK);
             return run_half<true, true, EPI_GRAD>(g, 1, s);
         }
-        if (plan.grad == GEMM_BIG) return run_big<true, true, EPI_GRAD>(g, 1, s);
+        // the streamed kernel stores gradients only (the descent step keeps the tile-per-workgroup kernel) and
+        // addresses the result through one 32-bit buffer
+        if (plan.grad == GEMM_STREAM && sgd_eta == 0.0f &&
+            (unsigned long long)(n_l + big::TM) * n_prev * 4ull < 0xFFFFFFF0ull)
+            return run_grad_stream(g, plan.stream_groups, s);
+        if (plan.grad == GEMM_BIG || plan.grad == GEMM_STREAM) return run_big<true, true, EPI_GRAD>(g, 1, s);
         return run<__bf16, true, true, EPI_GRAD>(g, 1, s);
     }
     g.P = D;

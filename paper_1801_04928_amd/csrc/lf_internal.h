@@ -43,12 +43,14 @@ hipError_t launch_output_error(const void* a_L, const void* y, float* delta_L, v
 size_t split_workspace_floats(int n_out, int K, int B, bool bf16);
 // Which matrix kernel a product takes: 128 x 128 tiles (fp32; bf16 nets of moderate width), or one of the two
 // wide-net bf16 kernels -- 256 x 256 tiles filling a compute unit, or 128 x 256 tiles sized so that two
-// workgroups (of one product or of two) share a compute unit.
-enum GemmKernel { GEMM_128 = 0, GEMM_BIG = 1, GEMM_HALF = 2 };
+// workgroups (of one product or of two) share a compute unit; the gradient product also as resident workgroups
+// that stream through all their 256 x 256 tiles.
+enum GemmKernel { GEMM_128 = 0, GEMM_BIG = 1, GEMM_HALF = 2, GEMM_STREAM = 3 };   // STREAM: gradient product only
 struct GemmPlan {
     int chain;          // GemmKernel of the forward and chain products
     int grad;           // GemmKernel of the gradient product
     int split_target;   // workgroups the K split of a chain-side product aims at
+    int stream_groups;  // resident workgroups of the streamed gradient product
 };
 // The plan of a net whose widest layer has N neurons (decided once per net).
 GemmPlan gemm_plan(int N, int B, bool bf16);

@@ -374,7 +374,7 @@ def test_minibatch_matches_oracle(L, N, B, dtype, k):
     _free(g)
 
 
-@pytest.mark.parametrize("tile", ["half", "big"])
+@pytest.mark.parametrize("tile", ["stream", "half", "big"])
 @pytest.mark.parametrize("L,N,B,k", [
     (3, 264, 70, 1),        # one ragged tile per product; a ragged last k-tile
     (4, 520, 260, 2),       # 3 x 3 tiles with ragged edges, split K on the chain side
@@ -382,13 +382,16 @@ def test_minibatch_matches_oracle(L, N, B, dtype, k):
     (4, 2056, 136, 3),      # ragged last column tile, two row tiles of the 128 x 256 kernel, long K split
 ])
 def test_minibatch_bf16_large_tile_kernel_matches_oracle(monkeypatch, L, N, B, k, tile):
-    """The two bf16 contraction kernels of wide nets (256 x 256 tiles: the default; 128 x 256 tiles, two
-    workgroups per compute unit), forced at sizes the oracle finishes quickly and that leave ragged tiles in
+    """The bf16 contraction kernels of wide nets (256 x 256 tiles, the gradient product streamed through resident
+    workgroups: the default; 256 x 256 tiles with a workgroup per tile; 128 x 256 tiles, two workgroups per
+    compute unit), forced at sizes the oracle finishes quickly and that leave ragged tiles in
     every dimension.  Both kernels give the same bits for every k."""
     import torch
     monkeypatch.setenv("LF_GEMM_BIG", "1")
-    monkeypatch.setenv("LF_GEMM_CHAIN_TILE", tile)
+    monkeypatch.setenv("LF_GEMM_CHAIN_TILE", "big" if tile == "stream" else tile)
     monkeypatch.setenv("LF_GEMM_GRAD_TILE", tile)
+    if tile == "stream" and N > 2000:
+        monkeypatch.setenv("LF_GEMM_STREAM_GROUPS", "24")      # several tiles per resident workgroup
     net = make_net(L, N, B, dtype="bf16", seed=7 * N + B)
     g = run_gpu(net, k)
     rep = check_against_oracle(net, g)
