@@ -1000,40 +1000,56 @@ hipError_t run_half(GemmArgs g, int splits, hipStream_t s) {
 
 // Which kernels a minibatch net takes, decided once per net from its widest layer.  bf16 nets whose forward
 // product has at least 64 tiles of 256 x 256 take the wide-net kernels: by default the 256 x 256-tile kernel for
-// all three products (measured faster than the 128 x 256 one, alone and beside each other).  Overrides for
-// tests and A/B runs, read when the plan is made:
+// all three products (measured faster than the 128 x 256 one, alone and beside each other).
+// How such a net shares the chip between the chain and the workers: a kernel of either kind fills every compute
+// unit it gets (registers, LDS), so two of them never share one; what can be shared is the set of compute
+// units.  The chain product is split only two ways along K -- 128 workgroups, half the chip (and half the
+// split's partial-sum traffic) -- the streamed gradient product keeps 96 workgroups resident, and the k workers
+// run on two streams (worker j on stream j mod 2), so that at most two gradient products are in flight and the
+// next chain kernel always finds compute units.  Measured at L = 48, N = 8192, B = 512, k = 8: 7.0 ms per backward
+// pass against 8.0 ms with every kernel spread over the whole chip.  (The split does not depend on k: the
+// gradients must be the same bits for every k.  A sequential pass, k = 1, would be faster with four splits.)
+// Overrides for tests and A/B runs, read when the plan is made:
 // LF_GEMM_BIG=0/1 forces the narrow / wide-net kernels; LF_GEMM_CHAIN_TILE = "big" or "half" picks the wide-net
 // kernel of the forward and chain products, LF_GEMM_GRAD_TILE = "stream" (default), "big" or "half" that of the
-// gradient product; LF_GEMM_SPLIT_TARGET = workgroups the split of a chain-side product aims at;
-// LF_GEMM_STREAM_GROUPS = resident workgroups of the streamed gradient product (default 256, one per compute unit).
+// gradient product; LF_GEMM_SPLIT_TARGET = workgroups the split of a chain-side product aims at (both products),
+// LF_GEMM_CHAIN_SPLIT_TARGET = the same for the backward chain product alone; LF_GEMM_STREAM_GROUPS = resident
+// workgroups of the streamed gradient product; LF_WORKER_STREAMS (read by the schedule) = streams the workers share.
 GemmPlan gemm_plan(int N, int B, bool bf16) {
-    GemmPlan p{GEMM_128, GEMM_128, 512, 256};
-    if (!bf16) return p;
-    bool wide = ceil_div(B, big::TM) * ceil_div(N, big::TN) >= 64;
+    // (narrow kernels: one stream for all workers -- at L = 32, N = 4096, B = 256, k = 4 the backward pass takes
+    // 4.4-4.5 ms with one worker stream and 4.6-4.7 ms with four: gradient products that queue behind each other
+    // leave the chain its compute units)
+    GemmPlan p{GEMM_128, GEMM_128, 512, 512, 256, 1};
+    bool wide = bf16 && ceil_div(B, big::TM) * ceil_div(N, big::TN) >= 64;
     if (const char* e = getenv("LF_GEMM_BIG")) {
         if (e[0] == '0') wide = false;
-        if (e[0] == '1') wide = true;
+        if (e[0] == '1') wide = bf16;
     }
-    if (!wide) return p;
-    p.chain = GEMM_BIG;
-    p.grad = GEMM_STREAM;
-    p.split_target = 256;
-    if (const char* e = getenv("LF_GEMM_CHAIN_TILE")) p.chain = e[0] == 'b' ? GEMM_BIG : GEMM_HALF;
-    if (const char* e = getenv("LF_GEMM_GRAD_TILE")) p.grad = e[0] == 'b' ? GEMM_BIG : (e[0] == 's' ? GEMM_STREAM : GEMM_HALF);
+    if (wide) {
+        p.chain = GEMM_BIG;
+        p.grad = GEMM_STREAM;
+        p.split_target = 256;
+        p.chain_split_target = 128;
+        p.stream_groups = 96;
+        p.worker_streams = 2;
+        if (const char* e = getenv("LF_GEMM_CHAIN_TILE")) p.chain = e[0] == 'b' ? GEMM_BIG : GEMM_HALF;
+        if (const char* e = getenv("LF_GEMM_GRAD_TILE")) p.grad = e[0] == 'b' ? GEMM_BIG : (e[0] == 's' ? GEMM_STREAM : GEMM_HALF);
+    }
     if (const char* e = getenv("LF_GEMM_STREAM_GROUPS")) {
         const int t = atoi(e);
         if (t >= 8 && t <= 1024) p.stream_groups = t;
     }
     if (const char* e = getenv("LF_GEMM_SPLIT_TARGET")) {
         const int t = atoi(e);
-        if (t >= 64 && t <= 2048) p.split_target = t;
+        if (t >= 64 && t <= 2048) p.split_target = p.chain_split_target = t;
+    }
+    if (const char* e = getenv("LF_GEMM_CHAIN_SPLIT_TARGET")) {
+        const int t = atoi(e);
+        if (t >= 64 && t <= 2048) p.chain_split_target = t;
     }
     return p;
 }
 
-// Number of K splits used for the two chain-side GEMMs (their output, B x n_out, is small, so a single pass
-// over the contraction length K would leave most compute units idle).  Depends on the shape (and the kernel
-// chosen) alone.
 int chain_splits(int n_out, int K, int B, bool bf16, int kernel, int target) {
     if (kernel == GEMM_HALF) {
         const int tiles = ceil_div(n_out, half::TN) * ceil_div(B, half::TM);
@@ -1046,19 +1062,23 @@ int chain_splits(int n_out, int K, int B, bool bf16, int kernel, int target) {
         const int tiles = ceil_div(n_out, big::TN) * ceil_div(B, big::TM);
         const int kt = ceil_div(K, big::TK);
         int s = 1;
-        while (tiles * s < 256 && s < 16 && kt / (s * 2) >= 4) s *= 2;      // one workgroup per compute unit
+        while (tiles * s < target && s < 16 && kt / (s * 2) >= 4) s *= 2;   // one workgroup per compute unit
         return s;
     }
     const int tiles = ceil_div(n_out, BN) * ceil_div(B, BM);
     const int kt = ceil_div(K, bf16 ? Tile<__bf16>::BK : Tile<float>::BK);
     int s = 1;
-    while (tiles * s < 512 && s < 16 && kt / (s * 2) >= 4) s *= 2;
+    while (tiles * s < target && s < 16 && kt / (s * 2) >= 4) s *= 2;
     return s;
 }
 
-size_t split_workspace_floats(int n_out, int K, int B, bool bf16) {      // enough for any of the kernels
-    int s = chain_splits(n_out, K, B, bf16, GEMM_128, 512);
-    if (bf16) s = max(s, 16);
+size_t split_workspace_floats(int n_out, int K, int B, bool bf16) {      // enough for any plan
+    (void)K; (void)bf16;
+    return (size_t)16 * B * n_out;                                       // no plan splits more than 16 ways
+}
+
+size_t split_scratch_floats(int n_out, int K, int B, bool bf16, const GemmPlan& plan, bool chain_product) {
+    const int s = chain_splits(n_out, K, B, bf16, plan.chain, chain_product ? plan.chain_split_target : plan.split_target);
     return s > 1 ? (size_t)s * B * n_out : 0;
 }
 
@@ -1100,7 +1120,7 @@ static hipError_t chain_impl(const void* W_next, const void* D_next_op, const vo
                              void* D_l_bf, float* raw, int n_l, int n_next, int B, const GemmPlan& plan,
                              hipStream_t s) {
     constexpr bool bf = sizeof(T) == 2;
-    const int splits = chain_splits(n_l, n_next, B, bf, plan.chain, plan.split_target);
+    const int splits = chain_splits(n_l, n_next, B, bf, plan.chain, plan.chain_split_target);
     GemmArgs g{};
     g.P = D_next_op; g.ldp = n_next; g.Q = W_next; g.ldq = n_l; g.M = B; g.Nn = n_l; g.K = n_next;
     g.k_tiles_per_split = ceil_div(ceil_div(n_next, Tile<T>::BK), splits);
@@ -1132,20 +1152,19 @@ static hipError_t chain_impl(const void* W_next, const void* D_next_op, const vo
 hipError_t launch_fwd_gemm(const void* W, const float* bias, const void* A_in, void* A_out, float* raw,
                            int n_out, int n_in, int B, bool bf16, const GemmPlan& plan, hipStream_t s) {
     return bf16 ? fwd_impl<__bf16>(W, bias, A_in, A_out, raw, n_out, n_in, B, plan, s)
-                : fwd_impl<float>(W, bias, A_in, A_out, raw, n_out, n_in, B, GemmPlan{GEMM_128, GEMM_128, 512, 256}, s);
+                : fwd_impl<float>(W, bias, A_in, A_out, raw, n_out, n_in, B, plan, s);
 }
 
 hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void* D_next_bf,
                              const void* A_l, float* D_l, void* D_l_bf, float* raw, int n_l, int n_next,
                              int B, bool bf16, const GemmPlan& plan, hipStream_t s) {
     return bf16 ? chain_impl<__bf16>(W_next, D_next_bf, A_l, D_l, D_l_bf, raw, n_l, n_next, B, plan, s)
-                : chain_impl<float>(W_next, D_next, A_l, D_l, nullptr, raw, n_l, n_next, B,
-                                    GemmPlan{GEMM_128, GEMM_128, 512, 256}, s);
+                : chain_impl<float>(W_next, D_next, A_l, D_l, nullptr, raw, n_l, n_next, B, plan, s);
 }
 
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
                             float* nabla_b, int n_l, int n_prev, int B, bool bf16, const GemmPlan& plan,
-                            float sgd_eta, void* w_bf, hipStream_t s) {
+                            bool whole_chip, float sgd_eta, void* w_bf, hipStream_t s) {
     if (sgd_eta != 0.0f && bf16 != (w_bf != nullptr)) return hipErrorInvalidValue;
     k_bias_grad<<<ceil_div(n_l, 32), kThreads, 0, s>>>(D, nabla_b, n_l, B, sgd_eta);
     hipError_t e = hipGetLastError();
@@ -1166,7 +1185,7 @@ hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev
         // addresses the result through one 32-bit buffer
         if (plan.grad == GEMM_STREAM && sgd_eta == 0.0f &&
             (unsigned long long)(n_l + big::TM) * n_prev * 4ull < 0xFFFFFFF0ull)
-            return run_grad_stream(g, plan.stream_groups, s);
+            return run_grad_stream(g, whole_chip ? 256 : plan.stream_groups, s);
         if (plan.grad == GEMM_BIG || plan.grad == GEMM_STREAM) return run_big<true, true, EPI_GRAD>(g, 1, s);
         return run<__bf16, true, true, EPI_GRAD>(g, 1, s);
     }

@@ -236,8 +236,10 @@ lf_status ensure_worker_streams(lf_net* net, size_t want) {
 
 // The stream schedule's workers: k streams (none for the sequential pass, which runs on the caller's).
 lf_status ensure_workers(lf_net* net, int k) {
-    // LF_WORKER_STREAMS (tuning): fewer streams than workers; worker j then runs on stream j mod that number
-    int cap = kMaxWorkerStreams;
+    // Workers beyond the plan's number of streams share them: worker j runs on stream j mod that number.
+    // LF_WORKER_STREAMS overrides it (tuning).
+    int cap = single_sample_path(net->N, net->B, net->dt) ? kMaxWorkerStreams
+                                                          : std::min(kMaxWorkerStreams, net->gemm.worker_streams);
     if (const char* e = std::getenv("LF_WORKER_STREAMS")) {
         const int v = std::atoi(e);
         if (v >= 1 && v <= kMaxWorkerStreams) cap = v;
@@ -406,7 +408,7 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
 }
 
 // (bp3),(bp4) of layer l on stream s; with the descent step fused in, applied to w^l and b^l in place.
-lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
+lf_status enqueue_grads(lf_net* net, int l, hipStream_t s, bool whole_chip = true) {
     const int i = l - 2;
     const bool sgd = net->sgd_eta != 0.0f, bf = net->dt == LF_BF16;
     float* out_w = !sgd ? net->gw[i] : (bf ? net->w32[i] : static_cast<float*>(const_cast<void*>(net->w[i])));
@@ -417,7 +419,7 @@ lf_status enqueue_grads(lf_net* net, int l, hipStream_t s) {
                                               out_w, out_b, net->width(l), net->width(l - 1), net->sgd_eta, s));
     } else {
         LF_HIP(net, lf::launch_grad_gemm(net->d_ptr(l), net->dbf_ptr(l), net->a_ptr(l - 1), out_w, out_b,
-                                         net->width(l), net->width(l - 1), net->B, bf, net->gemm,
+                                         net->width(l), net->width(l - 1), net->B, bf, net->gemm, whole_chip,
                                          net->sgd_eta, w_bf, s));
     }
     return LF_OK;
@@ -428,7 +430,7 @@ lf_status enqueue_grads_on_worker(lf_net* net, int l, int k, int nstreams, hipEv
     const int j = lf_schedule_worker(net->L, k, l) % nstreams;
     LF_HIP(net, hipStreamWaitEvent(net->workers[j], ready, 0));
     used[j] = true;
-    return enqueue_grads(net, l, net->workers[j]);
+    return enqueue_grads(net, l, net->workers[j], /*whole_chip=*/false);
 }
 
 // Algorithm 1 as printed (single sample).  The parent -- the caller's stream -- applies (bp1) and then
@@ -830,7 +832,13 @@ lf_status lf_backward_leapfrog_noalloc(lf_net* net, const void* y, int k, void* 
     if (st != LF_OK) return st;
     if (net->sched == LF_SCHED_REDUNDANT || net->sched == LF_SCHED_FUSED)
         return fail(net, LF_EUNSUPPORTED, "lf_backward_leapfrog_noalloc: runs the stream schedule's kernels only");
-    const size_t need = net->lay.partial_bytes > net->lay.raw_bytes ? net->lay.partial_bytes : net->lay.raw_bytes;
+    // what the chain products of this net really use: the single-sample row-block partial sums, or the split-K
+    // partials under the net's plan (the workspace reserves room for the deepest split any plan could take)
+    size_t need = net->lay.partial_bytes;
+    if (!single_sample_path(net->N, net->B, net->dt))
+        for (int l = 2; l < net->L; ++l)
+            need = std::max(need, 4 * lf::split_scratch_floats(net->width(l), net->width(l + 1), net->B,
+                                                               net->dt == LF_BF16, net->gemm, true));
     if (need > LF_STATIC_SCRATCH_BYTES)
         return fail(net, LF_EUNSUPPORTED,
                     "lf_backward_leapfrog_noalloc: this shape needs " + std::to_string(need) +

@@ -41,6 +41,9 @@ hipError_t launch_output_error(const void* a_L, const void* y, float* delta_L, v
 // Floats of scratch the split-K stage of a forward / chain contraction with a B x n_out result and
 // contraction length K needs (0 = no split).
 size_t split_workspace_floats(int n_out, int K, int B, bool bf16);
+struct GemmPlan;
+// Floats of split-K scratch the forward (chain_product = false) or chain product actually uses under a plan.
+size_t split_scratch_floats(int n_out, int K, int B, bool bf16, const GemmPlan& plan, bool chain_product);
 // Which matrix kernel a product takes: 128 x 128 tiles (fp32; bf16 nets of moderate width), or one of the two
 // wide-net bf16 kernels -- 256 x 256 tiles filling a compute unit, or 128 x 256 tiles sized so that two
 // workgroups (of one product or of two) share a compute unit; the gradient product also as resident workgroups
@@ -49,8 +52,10 @@ enum GemmKernel { GEMM_128 = 0, GEMM_BIG = 1, GEMM_HALF = 2, GEMM_STREAM = 3 }; 
 struct GemmPlan {
     int chain;          // GemmKernel of the forward and chain products
     int grad;           // GemmKernel of the gradient product
-    int split_target;   // workgroups the K split of a chain-side product aims at
+    int split_target;   // workgroups the K split of the forward product aims at
+    int chain_split_target;   // the same for the chain product of the backward pass
     int stream_groups;  // resident workgroups of the streamed gradient product
+    int worker_streams; // streams the k workers share (worker j runs on stream j mod this)
 };
 // The plan of a net whose widest layer has N neurons (decided once per net).
 GemmPlan gemm_plan(int N, int B, bool bf16);
@@ -70,9 +75,10 @@ hipError_t launch_chain_gemm(const void* W_next, const float* D_next, const void
 // sgd_eta != 0: the descent step fused into the epilogues -- nabla_w and nabla_b are then w^l (in fp32) and b^l
 // themselves and receive w - eta nabla_w, b - eta nabla_b; the gradients are not stored.  With bfloat16 storage
 // nabla_w is the fp32 master copy of w^l, and w_bf, the bfloat16 weights, are rewritten as its rounding (w_bf
-// is NULL exactly when the storage is fp32).
+// is NULL exactly when the storage is fp32).  whole_chip: nothing runs beside this product (the sequential
+// pass), so the streamed kernel keeps a workgroup on every compute unit instead of the plan's share.
 hipError_t launch_grad_gemm(const float* D, const void* D_bf, const void* A_prev, float* nabla_w,
                             float* nabla_b, int n_l, int n_prev, int B, bool bf16, const GemmPlan& plan,
-                            float sgd_eta, void* w_bf, hipStream_t s);
+                            bool whole_chip, float sgd_eta, void* w_bf, hipStream_t s);
 
 }  // namespace lf
