@@ -406,6 +406,28 @@ def test_minibatch_bf16_large_tile_kernel_matches_oracle(monkeypatch, L, N, B, k
     _free(g)
 
 
+def test_minibatch_sharing_knobs_change_no_bits(monkeypatch):
+    """How a minibatch net shares the chip between chain and workers -- resident workgroups of the streamed
+    gradient product, streams the workers share -- is a matter of time only: the gradients are the same bits.
+    (The number of K splits of the chain product is part of the arithmetic and is not varied here.)"""
+    import torch
+    monkeypatch.setenv("LF_GEMM_BIG", "1")
+    net = make_net(6, 1032, 136, dtype="bf16", seed=99)
+    want = None
+    for groups, streams in (("96", "2"), ("8", "1"), ("256", "3"), ("40", "8")):
+        monkeypatch.setenv("LF_GEMM_STREAM_GROUPS", groups)
+        monkeypatch.setenv("LF_WORKER_STREAMS", streams)
+        g = run_gpu(net, 4)
+        got = [to_np(t).copy().view(np.uint32) for t in g.nabla_w + g.nabla_b]
+        if want is None:
+            check_against_oracle(net, g)
+            want = got
+        else:
+            for a, b in zip(want, got):
+                assert np.array_equal(a, b), f"groups {groups}, streams {streams}"
+        _free(g)
+
+
 @pytest.mark.parametrize("target", ["512", "1024"])
 def test_minibatch_bf16_half_tile_kernel_deeper_split(monkeypatch, target):
     """The 128 x 256-tile kernel with the chain-side products split further along K (more, shorter workgroups)."""
