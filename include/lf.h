@@ -36,7 +36,8 @@
  *     After a non-OK status lf_last_error() describes it.  A handle is not
  *     thread-safe.  Different handles share nothing, with one restriction: the persistent
  *     kernels (LF_SCHED_PERSISTENT, LF_SCHED_FUSED, and LF_SCHED_AUTO where it picks them: B = 1,
- *     fp32, equal widths N <= 4096) need every workgroup of a launch resident at once, because the
+ *     fp32, layers 2..L-1 of one width N <= 4096, the first and last no wider) need every workgroup
+ *     of a launch resident at once, because the
  *     workgroups wait for each other.  The library checks at set-up that the idle device holds them
  *     (the runtime's occupancy figure for the kernel); it cannot see what else runs.  So do not let
  *     such a pass overlap on the device with another kernel that holds compute units for long
@@ -123,9 +124,11 @@ lf_status lf_create(lf_net** out, int L, int N, int B, lf_dtype dt, lf_cost cost
                     void* workspace, size_t workspace_bytes);
 
 /* The same two calls for a net whose layers differ in width (section 2: the equations are valid for any
- * widths).  n: HOST array of L entries, n[l-1] = neurons of layer l, read during the call only.  Such a
- * net runs the stream schedule (the persistent kernels need equal widths: LF_SCHED_PERSISTENT is then
- * LF_EUNSUPPORTED, LF_SCHED_AUTO picks streams).  With all n[l-1] equal this is lf_create. */
+ * widths).  n: HOST array of L entries, n[l-1] = neurons of layer l, read during the call only.  The
+ * persistent kernels take a net whose layers 2..L-1 have one width and whose first and last layer are no
+ * wider than that (an input and an output of their own sizes around equal hidden layers); any other net runs
+ * the stream schedule (LF_SCHED_PERSISTENT is then LF_EUNSUPPORTED, LF_SCHED_AUTO picks streams).  With all
+ * n[l-1] equal this is lf_create. */
 size_t lf_workspace_bytes_widths(int L, const int* n, int B, lf_dtype dt);
 lf_status lf_create_widths(lf_net** out, int L, const int* n, int B, lf_dtype dt, lf_cost cost,
                            void* workspace, size_t workspace_bytes);

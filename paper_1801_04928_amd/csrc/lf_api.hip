@@ -81,6 +81,15 @@ bool all_equal(int L, const int* n) {
     return true;
 }
 
+// The shape the persistent kernels take: layers 2..L-1 all of the widest width, the first and the last layer
+// no wider (any two widths when L = 2).
+bool inner_layers_equal(int L, const int* n) {
+    const int N = widest(L, n);
+    for (int i = 1; i + 1 < L; ++i)
+        if (n[i] != N) return false;
+    return true;
+}
+
 bool single_sample_path(int N, int B, lf_dtype dt) { return B == 1 && dt == LF_F32 && N <= 16384; }
 
 // Spacing of the eight-word groups of an exchanged vector: 8 << shift bytes.
@@ -129,7 +138,7 @@ Layout make_layout(int L, const int* n, int B, lf_dtype dt) {
         y.red_off = off;
         off += kMaxRedundantWorkers * y.red_stride;
     }
-    if (all_equal(L, n) && single_sample_path(N, B, dt) && lf::persistent_supported(L, N)) {
+    if (inner_layers_equal(L, n) && single_sample_path(N, B, dt) && lf::persistent_supported(L, N)) {
         y.ll_shift = ll_spread_shift();
         y.ll_layer = lf::persistent_ll_layer_words(N, y.ll_shift);
         y.ll_words = M * y.ll_layer;
@@ -155,6 +164,7 @@ struct lf_net {
     int L, N, B;                       // N: the widest layer
     std::vector<int> n;                // n[l-1] = neurons of layer l
     bool uniform;                      // every layer has N neurons
+    bool inner_uniform;                // layers 2..L-1 have N neurons (the first and the last may have fewer)
     int width(int l) const { return n[l - 1]; }
     lf_dtype dt;
     lf_cost cost;
@@ -248,7 +258,7 @@ lf_status ensure_workers(lf_net* net, int k) {
 }
 
 bool persistent_possible(const lf_net* net) {
-    return net->uniform && single_sample_path(net->N, net->B, net->dt) &&
+    return net->inner_uniform && single_sample_path(net->N, net->B, net->dt) &&
            lf::persistent_supported(net->L, net->N);
 }
 
@@ -323,6 +333,7 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
         {
             lf::PersistArgs probe{};
             probe.L = net->L; probe.N = net->N;
+            probe.n_in = net->width(1); probe.n_out = net->width(net->L);
             probe.G = net->p_groups; probe.RPG = net->p_rpg;
             probe.GB = net->p_bgroups; probe.TPR = net->p_tpr; probe.RS = net->p_rs;
             int occ_f = 0, occ_b = 0, occ_bf = 0;
@@ -374,6 +385,7 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     const size_t M = (size_t)net->L - 1;
     lf::PersistArgs A{};
     A.L = net->L; A.N = net->N;
+    A.n_in = net->width(1); A.n_out = net->width(net->L);
     A.G = net->p_groups; A.RPG = net->p_rpg;
     A.GB = net->p_bgroups; A.TPR = net->p_tpr; A.RS = net->p_rs;
     A.GW = net->p_workers;
@@ -618,6 +630,7 @@ lf_status lf_create_widths(lf_net** out, int L, const int* n, int B, lf_dtype dt
     const int N = widest(L, n);
     net->L = L; net->N = N; net->B = B; net->dt = dt; net->cost = cost;
     net->uniform = all_equal(L, n);
+    net->inner_uniform = inner_layers_equal(L, n);
     net->sched = LF_SCHED_AUTO;
     net->cost_scale = 1.0f;
     net->sgd_eta = 0.0f;
@@ -705,7 +718,8 @@ lf_status lf_set_schedule(lf_net* net, lf_sched sched) {
         case LF_SCHED_FUSED:
             if (!persistent_possible(net))
                 return fail(net, LF_EUNSUPPORTED,
-                            "lf_set_schedule: the persistent kernels need B = 1, fp32, equal widths N <= 4096, L <= 1025");
+                            "lf_set_schedule: the persistent kernels need B = 1, fp32, L <= 1025, layers 2..L-1 of one width N <= 4096, "
+                            "the first and the last layer no wider");
             net->sched = sched;
             return LF_OK;
         default:

@@ -13,7 +13,8 @@ constexpr int kMaxRowSplit = 4;          // row blocks a backward column strip m
 constexpr int kMaxLaunchGroups = 1024;   // workgroups of one launch (chain + gradient workers)
 
 struct PersistArgs {
-    int L, N;
+    int L, N;                            // layers 2..L-1 have N neurons
+    int n_in, n_out;                     // neurons of layer 1 and of layer L: multiples of 4, at most N
     int G, RPG;                          // forward: workgroups, rows per workgroup
     int GB, TPR;                         // backward chain: workgroups, float4 column groups per strip
     int RS;                              // backward chain: row blocks per strip (1 = a strip is one workgroup's)

@@ -165,6 +165,19 @@ __device__ __forceinline__ const float* act_ptr(const PersistArgs& A, int l) {
     return l == 1 ? A.a1 : A.a_base + (size_t)(l - 2) * A.a_stride;
 }
 
+// w^l has rows_of(l) rows of cols_of(l) entries: the neurons of layer l and of layer l-1.  Only the first and
+// the last layer may be narrower than N.
+// (The fields are copied to values first: a choice between two members of the argument block would keep the
+// block in memory.)
+__device__ __forceinline__ int cols_of(const PersistArgs& A, int l) {
+    const int n = A.N, first = A.n_in;
+    return l == 2 ? first : n;
+}
+__device__ __forceinline__ int rows_of(const PersistArgs& A, int l) {
+    const int n = A.N, last = A.n_out, top = A.L;
+    return l == top ? last : n;
+}
+
 // ================================================================================================
 // forward
 // ================================================================================================
@@ -197,13 +210,14 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
     const int nchunks = SINGLE ? 1 : (((RW + RF - 1) / RF + 1) & ~1);   // even: see `layer` below
     Abort ab{A.abort_dev, A.abort_host, false, A.spin_limit};
 
-    auto load_chunk = [&](v4f (&buf)[RF][Q], const float* W, int ci) {
+    auto load_chunk = [&](v4f (&buf)[RF][Q], const float* W, int ci, int l) {        // W = w^l
+        const int cols = cols_of(A, l), last_row = rows_of(A, l) - 1;
 #pragma unroll
         for (int rr = 0; rr < RF; ++rr) {
             // one buffer per row: column groups past its end load zeros; rows past the end of the
             // matrix re-read the last row (their results are never used)
-            const int row = min(wrow0 + ci * RF + rr, N - 1);
-            const __amdgpu_buffer_rsrc_t r = make_buffer(W + (size_t)row * N, (unsigned)N * 4u);
+            const int row = min(wrow0 + ci * RF + rr, last_row);
+            const __amdgpu_buffer_rsrc_t r = make_buffer(W + (size_t)row * cols, (unsigned)cols * 4u);
 #pragma unroll
             for (int u = 0; u < Q; ++u) buf[rr][u] = buffer_load_v4f(r, (unsigned)(lane + 64 * u) * 16u);
         }
@@ -212,13 +226,14 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
     // A wait for one load also waits for every older load and store of the wave, and for nothing newer:
     // next layer's bias is requested ahead of next layer's weights.
     const bool own = t < RPG && g * RPG + t < N;
-    float bias_next = own ? load_global_f32_here(bptr(0) + g * RPG + t) : 0.0f;
+    auto own_row_of = [&](int l) { return own && g * RPG + t < rows_of(A, l); };      // my row exists in layer l
+    float bias_next = own_row_of(2) ? load_global_f32_here(bptr(0) + g * RPG + t) : 0.0f;
 
     // a^{l-1}, from the tagged words its owners published, into LDS
     auto gather_activation = [&](int l) -> bool {
         bool missed = false;
         if (l == 2) {
-            for (int v = t; v < nvec; v += kThreads) s_a[v] = reinterpret_cast<const v4f*>(A.a1)[v];
+            for (int v = t; v < (A.n_in >> 2); v += kThreads) s_a[v] = reinterpret_cast<const v4f*>(A.a1)[v];
             return false;
         }
         const u64* src = A.ALL + (size_t)(l - 3) * A.ll_layer;
@@ -250,13 +265,14 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
     // rows ci*RF .. of this wave: dot products with a^{l-1}, bias, sigma, publish
     auto finish_chunk = [&](const v4f (&buf)[RF][Q], int ci, int l) {
         float acc[RF];
+        const int nv = cols_of(A, l) >> 2, row_end = min(wrow_end, rows_of(A, l));
 #pragma unroll
         for (int rr = 0; rr < RF; ++rr) acc[rr] = 0.0f;
 #pragma unroll
         for (int u = 0; u < Q; ++u) {
             const int v = lane + 64 * u;
             const v4f av = s_a[min(v, Q * 64 - 1)];
-            const v4f a = v < nvec ? av : v4f{0.f, 0.f, 0.f, 0.f};
+            const v4f a = v < nv ? av : v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int rr = 0; rr < RF; ++rr) {
                 acc[rr] = fmaf(buf[rr][u].x, a.x, acc[rr]);
@@ -271,7 +287,7 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
         for (int rr = 0; rr < RF; ++rr) {
             const int row = wrow0 + ci * RF + rr;
             const float z = wave_sum(acc[rr]);
-            if (lane == 0 && row < wrow_end) {
+            if (lane == 0 && row < row_end) {
                 const float a = sigmoidf(z + s_bias[row - g * RPG]);
                 if (l < L) ll_store(pub + ll_index(A, row), a, A.epoch);
                 a_out[row] = a;
@@ -290,28 +306,28 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
         const float* W = wptr(l - 2);
         const float* Wn = l < L ? wptr(l - 1) : nullptr;
         // requested before any of the next layer's weights: the wait for it then leaves those in flight
-        if (own && l < L) bias_next = load_global_f32_here(bptr(l - 1) + g * RPG + t);
+        if (l < L) bias_next = own_row_of(l + 1) ? load_global_f32_here(bptr(l - 1) + g * RPG + t) : 0.0f;
         if constexpr (SINGLE) {
-            if (Wn) load_chunk(bufB, Wn, 0);
+            if (Wn) load_chunk(bufB, Wn, 0, l + 1);
             finish_chunk(bufA, 0, l);
         } else {
             // both buffers enter the layer loaded (chunks 0 and 1 were requested before the exchange, so
             // that twice as much is in flight while the workgroups wait for each other)
             for (int ci = 0; ci < nchunks; ci += 2) {
-                if (ci > 0) load_chunk(bufB, W, ci + 1);
+                if (ci > 0) load_chunk(bufB, W, ci + 1, l);
                 finish_chunk(bufA, ci, l);
-                if (ci + 2 < nchunks) load_chunk(bufA, W, ci + 2);
-                else if (Wn) load_chunk(bufA, Wn, 0);
+                if (ci + 2 < nchunks) load_chunk(bufA, W, ci + 2, l);
+                else if (Wn) load_chunk(bufA, Wn, 0, l + 1);
                 finish_chunk(bufB, ci + 1, l);
             }
-            if (Wn) load_chunk(bufB, Wn, 1);
+            if (Wn) load_chunk(bufB, Wn, 1, l + 1);
         }
         __syncthreads();   // s_a is rewritten by the next layer's gather
     };
 
     v4f buf0[RF][Q], buf1[RF][Q];
-    load_chunk(buf0, wptr(0), 0);
-    if constexpr (!SINGLE) load_chunk(buf1, wptr(0), 1);
+    load_chunk(buf0, wptr(0), 0, 2);
+    if constexpr (!SINGLE) load_chunk(buf1, wptr(0), 1, 2);
     if constexpr (SINGLE) {
         for (int l = 2; l <= L; l += 2) {
             layer(buf0, buf1, l);
@@ -330,7 +346,7 @@ constexpr int PG = kMaxPersistentN / 1024;   // float4 column groups a thread co
 // Rows row .. row+n-1 of nabla_w^layer and nabla_b^layer from their delta values d[0..n).
 __device__ __forceinline__ void store_gradient_rows(const PersistArgs& A, int layer, int row, int n,
                                                     const float d[4], const v4f (&ja)[PG]) {
-    const int t = threadIdx.x, N = A.N, nvec = N >> 2;
+    const int t = threadIdx.x, N = cols_of(A, layer), nvec = N >> 2;
     float* gw = A.gw[layer - 2];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -354,7 +370,7 @@ __device__ __forceinline__ void store_gradient_rows(const PersistArgs& A, int la
 // results stay in the caches: the next forward pass reads them.
 __device__ __forceinline__ void step_weight_rows(const PersistArgs& A, int layer, int row, int n,
                                                  const float d[4], const v4f (&ja)[PG]) {
-    const int t = threadIdx.x, N = A.N, nvec = N >> 2;
+    const int t = threadIdx.x, N = cols_of(A, layer), nvec = N >> 2;
     float* w = const_cast<float*>(A.w[layer - 2]);
     float* b = const_cast<float*>(A.b[layer - 2]);
     const float eta = A.sgd_eta;
@@ -387,7 +403,8 @@ __device__ __forceinline__ void step_weight_rows(const PersistArgs& A, int layer
 
 __device__ __forceinline__ void load_activation_groups(const PersistArgs& A, int layer, v4f (&ja)[PG]) {
     const float* ap = act_ptr(A, layer);
-    const int nvec = A.N >> 2;
+    const int n = A.N, first = A.n_in;
+    const int nvec = (layer == 1 ? first : n) >> 2;         // (never the last layer's)
 #pragma unroll
     for (int p = 0; p < PG; ++p) ja[p] = load_global_v4f(ap + 4 * min((int)threadIdx.x + kThreads * p, nvec - 1));
 }
@@ -428,12 +445,14 @@ __device__ __forceinline__ void gradient_worker(PersistArgs& A, unsigned* s_coun
     if (jb >= je) return;                           // (behind the barrier: its launch count is taken)
     const bool sgd = A.sgd_eta != 0.0f;
     for (int layer = L - part; layer >= 2; layer -= k) {
+        const int je_l = min(je, rows_of(A, layer));  // (a narrower last layer: some workgroups have no row of it)
+        if (jb >= je_l) continue;
         v4f ja[PG];
         load_activation_groups(A, layer - 1, ja);
         const u64* dl = A.DLL + (size_t)(layer - 2) * A.ll_layer;
         bool wait_reads = sgd && layer >= 3;        // the chain never reads w^2
-        for (int row0 = jb; row0 < je; row0 += kThreads) {
-            const int nb = min(kThreads, je - row0);
+        for (int row0 = jb; row0 < je_l; row0 += kThreads) {
+            const int nb = min(kThreads, je_l - row0);
             if (t < nb) s_wd[t] = ll_wait1(dl + ll_index(A, row0 + t), A.epoch, ab, abort_code(3, layer, (int)blockIdx.x));
             if (wait_reads && t < A.GB)
                 ll_wait1(A.reads_done + (size_t)(layer - 2) * kMaxGroups + t, A.epoch, ab, abort_code(3, layer, (int)blockIdx.x));
@@ -543,11 +562,16 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
         for (int u = 0; u < CH; ++u) buf[u] = buffer_load_v4f(r, strip_offset + (unsigned)u * pass_bytes);
     };
     auto load_chunk = [&](v4f (&buf)[CH], const float* W, int ci) { load_chunk_of(buf, W, ci, block_bytes); };
+    // w^L may have fewer rows than N: my row block of it ends where the matrix does
+    const int top_hi = min(row_hi, A.n_out);
+    const unsigned top_bytes = (unsigned)top_hi * (unsigned)N * 4u;
     auto inline_grads = [&](int layer) {        // k = 1: rows [jrow0, jrow1) of layer's gradients
+        const int jr1 = min(jrow1, rows_of(A, layer)), jr0 = min(jrow0, jr1);
+        if (jr0 >= jr1) return;
         v4f ja[PG];
         load_activation_groups(A, layer - 1, ja);
-        for (int row = jrow0; row < jrow1; row += 4) {
-            const int n = min(4, jrow1 - row);
+        for (int row = jr0; row < jr1; row += 4) {
+            const int n = min(4, jr1 - row);
             float d[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) d[c] = s_delta[min(row + c, N - 1)];
@@ -605,10 +629,10 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     const bool inline_bursts = !A.workers && !A.no_grads && !FUSED;    // the sequential pass's gradient bursts
     v4f buf[NB][CH];
     if (L > 2) {                                     // my strip of w^L, needed by the first chain step
-        load_chunk(buf[0], wptr(L - 2), 0);
+        load_chunk_of(buf[0], wptr(L - 2), 0, top_bytes);
         if constexpr (!SINGLE) {
 #pragma unroll
-            for (int j = 1; j < NB; ++j) load_chunk(buf[j], wptr(L - 2), j);
+            for (int j = 1; j < NB; ++j) load_chunk_of(buf[j], wptr(L - 2), j, top_bytes);
         }
     }
 
@@ -617,11 +641,15 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     {
         const float* aL = act_ptr(A, L);
         for (int i = t; i < N; i += kThreads) {
-            const float a = aL[i];
-            s_delta[i] = A.cost_scale * ((a - A.y[i]) * (a * (1.0f - a)));
+            float v = 0.0f;                          // (past a narrower last layer: zeros)
+            if (i < A.n_out) {
+                const float a = aL[i];
+                v = A.cost_scale * ((a - A.y[i]) * (a * (1.0f - a)));
+            }
+            s_delta[i] = v;
         }
         __syncthreads();
-        if (own) {
+        if (own && fcol0 + t < A.n_out) {
             const float d = s_delta[fcol0 + t];
             ll_store(A.DLL + (size_t)(L - 2) * A.ll_layer + ll_index(A, fcol0 + t), d, A.epoch);
             A.d_base[(size_t)(L - 2) * A.d_stride + fcol0 + t] = d;
@@ -631,15 +659,17 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     // gwl, gbl, a4 (on-chain fusion only): nabla_w^{l+1}, nabla_b^{l+1}, a^l at my columns.  nabla_w^{l+1} is laid
     // out like w^{l+1}, so an entry is stored through a buffer at the very offset its weight was loaded from,
     // and rows past the end of my row block fall outside the buffer (no store).
-    auto fma_chunk = [&](const v4f (&buf)[CH], int ci, v4f& acc, float* gwl, float* gbl, const v4f& a4) {
+    // (rhi, wbytes: the end of my row block of this step's matrix, as a row and in bytes)
+    auto fma_chunk = [&](const v4f (&buf)[CH], int ci, v4f& acc, float* gwl, float* gbl, const v4f& a4, int rhi,
+                         unsigned wbytes) {
         const unsigned gskip = (unsigned)(ci * CH) * pass_bytes;
         const __amdgpu_buffer_rsrc_t gr = make_buffer(reinterpret_cast<const char*>(gwl) + (FUSED ? gskip : 0u),
-                                                      FUSED && block_bytes > gskip ? block_bytes - gskip : 0u);
+                                                      FUSED && wbytes > gskip ? wbytes - gskip : 0u);
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             const int row = row_lo + rs + RPP * (ci * CH + u);
             const float dv = s_delta[min(row, N - 1)];
-            const float d = row < row_hi ? dv : 0.0f;
+            const float d = row < rhi ? dv : 0.0f;
             acc.x = fmaf(buf[u].x, d, acc.x);
             acc.y = fmaf(buf[u].y, d, acc.y);
             acc.z = fmaf(buf[u].z, d, acc.z);
@@ -647,7 +677,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
             if constexpr (FUSED) {
                 const v4f o = {d * a4.x, d * a4.y, d * a4.z, d * a4.w};
                 buffer_store_nt_v4f(gr, strip_offset + (unsigned)u * pass_bytes, o);
-                if (bias_writer && row < row_hi) store_global_f32(gbl + row, d);
+                if (bias_writer && row < rhi) store_global_f32(gbl + row, d);
             }
         }
     };
@@ -666,10 +696,12 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
         if (inline_bursts) inline_grads(l + 1);
         const float* W = wptr(l - 1);
         const float* Wn = l > 2 ? wptr(l - 2) : nullptr;
+        const int rhi = l + 1 == L ? top_hi : row_hi;
+        const unsigned wbytes = l + 1 == L ? top_bytes : block_bytes;
         v4f acc = {0.f, 0.f, 0.f, 0.f};
         if constexpr (SINGLE) {
             if (Wn) load_chunk(bufB, Wn, 0);
-            fma_chunk(bufA, 0, acc, gwl, gbl, a4);
+            fma_chunk(bufA, 0, acc, gwl, gbl, a4, rhi, wbytes);
         } else {
             // every refill is one unconditional load: past the last layer it reads an empty buffer
             // (zeros, no memory traffic), so a buffer's registers are never carried around a branch
@@ -679,8 +711,8 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
                 const bool same = ci + NB < nchunks;
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
-                    fma_chunk(buf[j], ci + j, acc, gwl, gbl, a4);
-                    load_chunk_of(buf[j], same ? W : Wnext, same ? ci + j + NB : j, same ? block_bytes : next_bytes);
+                    fma_chunk(buf[j], ci + j, acc, gwl, gbl, a4, rhi, wbytes);
+                    load_chunk_of(buf[j], same ? W : Wnext, same ? ci + j + NB : j, same ? wbytes : next_bytes);
                 }
             }
         }
@@ -816,8 +848,12 @@ hipError_t launch_fill_u64(void* p, size_t n_words, unsigned long long v, hipStr
 typedef void (*persist_kernel_t)(const PersistArgs);
 
 // The forward kernel instance for this shape (nullptr: none).
+static bool edge_widths_ok(const PersistArgs& A) {
+    return A.n_in >= 4 && A.n_in <= A.N && A.n_in % 4 == 0 && A.n_out >= 4 && A.n_out <= A.N && A.n_out % 4 == 0;
+}
+
 static persist_kernel_t forward_kernel(const PersistArgs& A) {
-    if (!persistent_supported(A.L, A.N) || A.G > kMaxLaunchGroups) return nullptr;
+    if (!persistent_supported(A.L, A.N) || !edge_widths_ok(A) || A.G > kMaxLaunchGroups) return nullptr;
     const int q = (A.N / 4 + 63) / 64;                       // float4 groups per lane and row
     const int rw = (A.RPG + kWaves - 1) / kWaves;            // rows per wave
     if (q <= 4) {
@@ -861,7 +897,7 @@ static persist_kernel_t backward_kernel_of(const PersistArgs& A) {
 
 // The backward kernel instance for this shape and variant (nullptr: none).
 static persist_kernel_t backward_kernel(const PersistArgs& A) {
-    if (A.GB > kMaxGroups * 2 || !persistent_supported(A.L, A.N)) return nullptr;
+    if (A.GB > kMaxGroups * 2 || !persistent_supported(A.L, A.N) || !edge_widths_ok(A)) return nullptr;
     if (A.RS != 1 && A.RS != 2 && A.RS != 4) return nullptr;
     if (A.GB % A.RS != 0 || (4 * A.TPR) % A.RS != 0) return nullptr;
     if (A.GB > kMaxGroups || kMaxGroups > kThreads) return nullptr;   // one polling thread per chain workgroup

@@ -65,7 +65,8 @@ def test_create_rejects_bad_arguments():
 
 def test_unequal_widths_workspace_and_create():
     """lf_workspace_bytes_widths / lf_create_widths: one width per layer, the same limits as N; equal widths
-    give lf_create's workspace; such a net has no persistent path."""
+    give lf_create's workspace; a net with hidden layers of different widths has no persistent path, one whose
+    first and last layer alone are narrower has."""
     F = P.LF_F32
     assert P.lf_workspace_bytes_widths(3, [8, 16, 4], 1, F) > 0
     assert P.lf_workspace_bytes_widths(3, [8, 16, 4], 1, F) % 256 == 0
@@ -81,7 +82,7 @@ def test_unequal_widths_workspace_and_create():
     st, h = P.lf_create_widths(4, widths, 1, F, P.LF_COST_QUADRATIC, FAKE, nbytes)
     assert st == P.LF_OK
     assert P.lf_set_schedule(h, P.LF_SCHED_PERSISTENT) == P.LF_EUNSUPPORTED
-    assert "equal widths" in P.lf_last_error(h)
+    assert "one width" in P.lf_last_error(h)
     assert P.lf_set_schedule(h, P.LF_SCHED_STREAMS) == P.LF_OK
     assert P.lf_set_schedule(h, P.LF_SCHED_AUTO) == P.LF_OK
     P.lf_destroy(h)
@@ -91,6 +92,11 @@ def test_unequal_widths_workspace_and_create():
     assert st == P.LF_EINVAL and "width" in P.lf_last_error(None)
     st, h = P.lf_create_widths(4, None, 1, F, P.LF_COST_QUADRATIC, FAKE, nbytes)
     assert st == P.LF_EINVAL
+    # a narrower input and output around equal hidden layers: the persistent path is there; not with a wider input
+    for w4, want in (([64, 256, 256, 32], P.LF_OK), ([512, 256, 256, 32], P.LF_EUNSUPPORTED)):
+        st, h = P.lf_create_widths(4, w4, 1, F, P.LF_COST_QUADRATIC, FAKE, P.lf_workspace_bytes_widths(4, w4, 1, F))
+        assert st == P.LF_OK and P.lf_set_schedule(h, P.LF_SCHED_PERSISTENT) == want
+        P.lf_destroy(h)
     # equal widths through the general call: the persistent path is there
     st, h = P.lf_create_widths(8, [256] * 8, 1, F, P.LF_COST_QUADRATIC, FAKE, P.lf_workspace_bytes(8, 256, 1, F))
     assert st == P.LF_OK and P.lf_set_schedule(h, P.LF_SCHED_PERSISTENT) == P.LF_OK

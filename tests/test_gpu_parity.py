@@ -506,6 +506,8 @@ def test_unequal_layer_widths_outer_product_is_exact():
     ((4, 3076), 1, 3, "persistent"),               # strips in row blocks, several float4 groups per thread
     ((2, 256), 1, 1, "persistent"),                # no chain step: nothing to wait for
     ((32, 1024), 1, 8, "persistent"),              # configuration 2's shape: 31 layers stepped behind the chain
+    ((64, 256, 256, 32), 1, 2, "persistent"),      # a narrower first and last layer
+    ((1024, 3076, 3076, 260), 1, 3, "persistent"), # the same with strips in row blocks
 ])
 def test_fused_descent_step(shape, B, k, sched):
     """lf_set_sgd: the pass applies w <- w - eta nabla_w, b <- b - eta nabla_b in place.  Checked (i) against
