@@ -53,15 +53,23 @@ def measured_traffic(cfg_name, k):
     since they were taken."""
     import hashlib
     path = os.path.join(ROOT, "profiles", "traffic.json")
+
+    def source_hash(names):
+        h = hashlib.sha256()
+        for name in names:
+            h.update(open(os.path.join(ROOT, "paper_1801_04928_amd", "csrc", name), "rb").read())
+        return h.hexdigest()
     try:
         rec = json.load(open(path))
-        h = hashlib.sha256()
-        for name in ("persistent_kernels.hip", "persistent.h", "device_helpers.h"):
-            h.update(open(os.path.join(ROOT, "paper_1801_04928_amd", "csrc", name), "rb").read())
-        if rec.get("kernel_source_sha256") != h.hexdigest():
-            return None
         e = rec.get(f"{cfg_name}_k{k}")
-        return None if e is None else e["fetch_bytes"] + e["write_bytes"]
+        if e is None:
+            return None
+        if "source_sha256" in e:          # a minibatch pass: the sum over its kernels, hashed with their sources
+            if e["source_sha256"] != source_hash(e["sources"]):
+                return None
+        elif rec.get("kernel_source_sha256") != source_hash(("persistent_kernels.hip", "persistent.h", "device_helpers.h")):
+            return None
+        return e["fetch_bytes"] + e["write_bytes"]
     except Exception:
         return None
 
@@ -409,7 +417,8 @@ def run_config(net, name, args, steps, warmup, rates, P, torch, extras=True):
         achievable = dict(rates.hbm() if work["bound"] == "hbm" else rates.mfma(s.dtype))
         if work["bound"] == "mfma":
             achievable["same_shapes"] = rates.vendor_same_shapes(s)
-    traffic = measured_traffic(s.name, k) if persistent else None
+    traffic = measured_traffic(s.name, k) if (persistent or (s.B > 1 and sched == "auto" and not s.widths
+                                                            and args.sgd <= 0.0)) else None
     entry = {
         "config": name or s.name,
         "workload": f"{s.name}: sigmoid MLP L={s.L} N={s.N} B={s.B} {s.dtype}, k={k}, seed {s.seed}",
