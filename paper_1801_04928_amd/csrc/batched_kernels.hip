@@ -420,13 +420,26 @@ __global__ __launch_bounds__(kThreadsBig) void k_gemm_big(const GemmArgs g) {
     __shared__ __attribute__((aligned(16))) __bf16 s_p1[ELEMS];
     __shared__ __attribute__((aligned(16))) __bf16 s_q1[ELEMS];
 
-    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    // Which tile column and which split this workgroup takes.  Workgroups are dealt to the 8 XCDs round-robin
+    // in x-first order, so with a multiple of 8 tile columns the XCD is x % 8: the split is taken from x (x % S
+    // for S = 2, 4 or 8 splits), so that one XCD's workgroups all work in one range of the contraction and its L2
+    // fetches only that part of the operand every tile column shares (P); the workgroups of one tile column and
+    // split (they share Q's tiles) stay on one XCD, as before.  Only a matter of which workgroup does what.
+    int tile_x = blockIdx.x, split = blockIdx.z;
+    {
+        const int S = gridDim.z;
+        if (S > 1 && S <= 8 && (S & (S - 1)) == 0 && gridDim.x % 8 == 0) {
+            split = (int)blockIdx.x % S;
+            tile_x = (int)blockIdx.x / S + (int)(gridDim.x / S) * (int)blockIdx.z;
+        }
+    }
+    const int m0 = blockIdx.y * TM, n0 = tile_x * TN;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
     const int r32 = lane & 31, half = lane >> 5;
 
     const int kt_total = ceil_div(g.K, TK);
-    const int kt_begin = blockIdx.z * g.k_tiles_per_split;
+    const int kt_begin = split * g.k_tiles_per_split;
     const int kt_end = min(kt_total, kt_begin + g.k_tiles_per_split);
     const int T = kt_end - kt_begin;
 
@@ -528,7 +541,7 @@ __global__ __launch_bounds__(kThreadsBig) void k_gemm_big(const GemmArgs g) {
                     store_global_nt_v4f(dst, v);
                 }
             } else if constexpr (EPI == EPI_RAW) {
-                *reinterpret_cast<v4f*>(g.raw + (size_t)blockIdx.z * g.M * g.Nn + o) = v;
+                *reinterpret_cast<v4f*>(g.raw + (size_t)split * g.M * g.Nn + o) = v;
             } else if constexpr (EPI == EPI_SIGMOID) {
                 const v4f bs = *reinterpret_cast<const v4f*>(g.bias + n);
                 const v4bf a = {(__bf16)sigmoidf(v.x + bs.x), (__bf16)sigmoidf(v.y + bs.y),
