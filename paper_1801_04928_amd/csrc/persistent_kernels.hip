@@ -343,11 +343,23 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
 // ================================================================================================
 constexpr int PG = kMaxPersistentN / 1024;   // float4 column groups a thread covers in a gradient row
 
-// Rows row .. row+n-1 of nabla_w^layer and nabla_b^layer from their delta values d[0..n).
-__device__ __forceinline__ void store_gradient_rows(const PersistArgs& A, int layer, int row, int n,
-                                                    const float d[4], const v4f (&ja)[PG]) {
+// Marks a loaded value as used here: the wait for it is placed here and not at its first real use.  In front of a
+// loop of stores this matters: a wait inside the loop, for a value requested before the loop, is a wait for every
+// store of the iterations before as well (the counter cannot tell them apart), and the stores then leave one
+// group at a time.
+template <typename T>
+__device__ __forceinline__ void arrived(T& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void arrived(v4f (&ja)[PG]) {
+#pragma unroll
+    for (int p = 0; p < PG; ++p) arrived(ja[p]);
+}
+
+// Rows row .. row+n-1 of nabla_w^layer (at gw) and nabla_b^layer (at gb) from their delta values d[0..n).
+// (The caller reads the two pointers from their table once per layer: read here, before every group of rows, the
+// wait for the pointer would also wait for every store of the group before.)
+__device__ __forceinline__ void store_gradient_rows(const PersistArgs& A, int layer, float* gw, float* gb, int row,
+                                                    int n, const float d[4], const v4f (&ja)[PG]) {
     const int t = threadIdx.x, N = cols_of(A, layer), nvec = N >> 2;
-    float* gw = A.gw[layer - 2];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         if (c < n) {
@@ -360,7 +372,7 @@ __device__ __forceinline__ void store_gradient_rows(const PersistArgs& A, int la
                     store_global_nt_v4f(out + 4 * v, o);
                 }
             }
-            if (t == 0) store_global_f32(A.gb[layer - 2] + row + c, d[c]);
+            if (t == 0) store_global_f32(gb + row + c, d[c]);
         }
     }
 }
@@ -449,6 +461,8 @@ __device__ __forceinline__ void gradient_worker(PersistArgs& A, unsigned* s_coun
         if (jb >= je_l) continue;
         v4f ja[PG];
         load_activation_groups(A, layer - 1, ja);
+        float* gw = A.gw[layer - 2];
+        float* gb = A.gb[layer - 2];
         const u64* dl = A.DLL + (size_t)(layer - 2) * A.ll_layer;
         bool wait_reads = sgd && layer >= 3;        // the chain never reads w^2
         for (int row0 = jb; row0 < je_l; row0 += kThreads) {
@@ -460,12 +474,25 @@ __device__ __forceinline__ void gradient_worker(PersistArgs& A, unsigned* s_coun
             if (ab.dead) s_wdead = 1;
             __syncthreads();
             if (s_wdead) return;                    // the same for every thread
-            for (int r = 0; r < nb; r += 4) {
-                float d[4];
+            arrived(ja);
+            arrived(gw);
+            arrived(gb);
+            // (two loops, not one with the choice inside: the loads of the descent step would otherwise be on a
+            // path around the store loop, and the stores would wait for registers those loads might still owe)
+            if (sgd) {
+                for (int r = 0; r < nb; r += 4) {
+                    float d[4];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) d[c] = s_wd[min(r + c, nb - 1)];
-                if (sgd) step_weight_rows(A, layer, row0 + r, min(4, nb - r), d, ja);
-                else store_gradient_rows(A, layer, row0 + r, min(4, nb - r), d, ja);
+                    for (int c = 0; c < 4; ++c) d[c] = s_wd[min(r + c, nb - 1)];
+                    step_weight_rows(A, layer, row0 + r, min(4, nb - r), d, ja);
+                }
+            } else {
+                for (int r = 0; r < nb; r += 4) {
+                    float d[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) d[c] = s_wd[min(r + c, nb - 1)];
+                    store_gradient_rows(A, layer, gw, gb, row0 + r, min(4, nb - r), d, ja);
+                }
             }
             __syncthreads();                        // the next batch overwrites s_wd
         }
@@ -500,13 +527,17 @@ template <int TPR, int CH, bool SINGLE, bool SPLIT, bool FUSED>
 __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     constexpr int CPG = 4 * TPR;              // columns per chain workgroup
     constexpr int RPP = kThreads / TPR;       // rows covered by one load of the whole workgroup
-    __shared__ v4f s_delta4[kMaxPersistentN / 4];       // delta^{l+1}, all of it
+    __shared__ v4f s_delta4[2][kMaxPersistentN / 4];    // delta^{l+1}, all of it, and delta^l as it is gathered
     __shared__ v4f s_red[kWaves * 4][TPR];              // per row of 16 lanes
     __shared__ const float* s_w[kTableLds];             // w^l pointers (see the forward kernel)
     __shared__ float* s_gw[FUSED ? kTableLds : 1];      // nabla_w^l, nabla_b^l pointers (on-chain fusion only)
     __shared__ float* s_gb[FUSED ? kTableLds : 1];
     __shared__ unsigned s_count;
-    float* s_delta = reinterpret_cast<float*>(s_delta4);
+    // (two buffers that change roles after every step: the sequential pass still reads delta^{l+1} for its
+    // gradient rows when delta^l has been gathered)
+    v4f* s_delta4_cur = s_delta4[0];
+    v4f* s_delta4_nxt = s_delta4[1];
+    auto delta_cur = [&]() { return reinterpret_cast<const float*>(s_delta4_cur); };
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
     PersistArgs A = args;
     const int N = A.N, L = A.L, GB = A.GB, nvec = N >> 2;
@@ -565,17 +596,19 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     // w^L may have fewer rows than N: my row block of it ends where the matrix does
     const int top_hi = min(row_hi, A.n_out);
     const unsigned top_bytes = (unsigned)top_hi * (unsigned)N * 4u;
-    auto inline_grads = [&](int layer) {        // k = 1: rows [jrow0, jrow1) of layer's gradients
+    // k = 1: rows [jrow0, jrow1) of layer's gradients (stored at gw, gb); ja = a^{layer-1} as load_activation_groups
+    // leaves it
+    auto inline_grads = [&](int layer, float* gw, float* gb, v4f (&ja)[PG]) {
         const int jr1 = min(jrow1, rows_of(A, layer)), jr0 = min(jrow0, jr1);
-        if (jr0 >= jr1) return;
-        v4f ja[PG];
-        load_activation_groups(A, layer - 1, ja);
+        arrived(ja);
+        arrived(gw);
+        arrived(gb);
         for (int row = jr0; row < jr1; row += 4) {
             const int n = min(4, jr1 - row);
             float d[4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) d[c] = s_delta[min(row + c, N - 1)];
-            store_gradient_rows(A, layer, row, n, d, ja);
+            for (int c = 0; c < 4; ++c) d[c] = delta_cur()[min(row + c, N - 1)];
+            store_gradient_rows(A, layer, gw, gb, row, n, d, ja);
         }
     };
     // delta^layer's rows of my row block (float4 groups [gv0, gv1)), from their tagged words, into LDS
@@ -587,7 +620,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
             if (t >= gv0 && t < gv1) {
                 float o[4];
                 missed = ll_wait4(src + ll_index(A, 4 * t), 4, A.epoch, o, ab, abort_code(2, layer, g));
-                s_delta4[t] = v4f{o[0], o[1], o[2], o[3]};
+                s_delta4_nxt[t] = v4f{o[0], o[1], o[2], o[3]};
             }
         } else {
             for (int v0 = gv0 + t; v0 < gv1; v0 += 4 * kThreads) {
@@ -603,7 +636,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
                 missed |= ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(2, layer, g));
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    if (gn[i]) s_delta4[v0 + i * kThreads] = v4f{o[i][0], o[i][1], o[i][2], o[i][3]};
+                    if (gn[i]) s_delta4_nxt[v0 + i * kThreads] = v4f{o[i][0], o[i][1], o[i][2], o[i][3]};
             }
         }
         return missed;
@@ -646,11 +679,11 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
                 const float a = aL[i];
                 v = A.cost_scale * ((a - A.y[i]) * (a * (1.0f - a)));
             }
-            s_delta[i] = v;
+            reinterpret_cast<float*>(s_delta4_cur)[i] = v;
         }
         __syncthreads();
         if (own && fcol0 + t < A.n_out) {
-            const float d = s_delta[fcol0 + t];
+            const float d = delta_cur()[fcol0 + t];
             ll_store(A.DLL + (size_t)(L - 2) * A.ll_layer + ll_index(A, fcol0 + t), d, A.epoch);
             A.d_base[(size_t)(L - 2) * A.d_stride + fcol0 + t] = d;
         }
@@ -668,7 +701,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             const int row = row_lo + rs + RPP * (ci * CH + u);
-            const float dv = s_delta[min(row, N - 1)];
+            const float dv = delta_cur()[min(row, N - 1)];
             const float d = row < rhi ? dv : 0.0f;
             acc.x = fmaf(buf[u].x, d, acc.x);
             acc.y = fmaf(buf[u].y, d, acc.y);
@@ -693,7 +726,16 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
         float* gwl = nullptr;
         float* gbl = nullptr;
         if constexpr (FUSED) { gwl = s_gw[l - 1]; gbl = s_gb[l - 1]; }
-        if (inline_bursts) inline_grads(l + 1);
+        // the sequential pass stores layer l+1's gradients during this step's exchange; their second factor, a^l, is
+        // requested here, a whole strip ahead of its use
+        v4f ja[PG];
+        float* jgw = nullptr;
+        float* jgb = nullptr;
+        if (inline_bursts) {
+            load_activation_groups(A, l, ja);
+            jgw = A.gw[l - 1];
+            jgb = A.gb[l - 1];
+        }
         const float* W = wptr(l - 1);
         const float* Wn = l > 2 ? wptr(l - 2) : nullptr;
         const int rhi = l + 1 == L ? top_hi : row_hi;
@@ -756,10 +798,16 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
             }
             if constexpr (FUSED) { if (l > 2) a4_next = load_strip_activation(l - 1); }
         }
-        // exchange: all of delta^l (every workgroup is past its last read of delta^{l+1})
-        nap(A.nap);
+        // exchange: all of delta^l, into the other buffer.  The sequential pass stores its rows of layer l+1's
+        // gradients between publishing and gathering, from delta^{l+1} in the buffer the step has just used: the
+        // stores fill the time the peers' words are under way.
+        if (inline_bursts) inline_grads(l + 1, jgw, jgb, ja);
+        else nap(A.nap);
         gather_delta(l);
         __syncthreads();
+        v4f* const was = s_delta4_cur;
+        s_delta4_cur = s_delta4_nxt;
+        s_delta4_nxt = was;
     };
 
     if constexpr (SINGLE) {
@@ -770,7 +818,11 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     } else {
         for (int l = L - 1; l >= 2; --l) step(buf[0], buf[1], l);
     }
-    if (!A.workers && !A.no_grads) inline_grads(2);
+    if (!A.workers && !A.no_grads) {
+        v4f ja[PG];
+        load_activation_groups(A, 1, ja);
+        inline_grads(2, A.gw[0], A.gb[0], ja);
+    }
 }
 
 template <int Q, int RF, bool SINGLE>
