@@ -596,10 +596,16 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     // w^L may have fewer rows than N: my row block of it ends where the matrix does
     const int top_hi = min(row_hi, A.n_out);
     const unsigned top_bytes = (unsigned)top_hi * (unsigned)N * 4u;
-    // k = 1: rows [jrow0, jrow1) of layer's gradients (stored at gw, gb); ja = a^{layer-1} as load_activation_groups
-    // leaves it
-    auto inline_grads = [&](int layer, float* gw, float* gb, v4f (&ja)[PG]) {
+    // k = 1: rows [jrow0, jrow1) of layer's gradients.  (What the store loop needs is requested and awaited here,
+    // under the one condition the call stands under: requested at the top of the step, the compiler would see a
+    // path from request to the next step without the use, and make every step wait for all loads in flight.)
+    auto inline_grads = [&](int layer) {
         const int jr1 = min(jrow1, rows_of(A, layer)), jr0 = min(jrow0, jr1);
+        if (jr0 >= jr1) return;
+        v4f ja[PG];
+        load_activation_groups(A, layer - 1, ja);
+        float* gw = A.gw[layer - 2];
+        float* gb = A.gb[layer - 2];
         arrived(ja);
         arrived(gw);
         arrived(gb);
@@ -726,23 +732,17 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
         float* gwl = nullptr;
         float* gbl = nullptr;
         if constexpr (FUSED) { gwl = s_gw[l - 1]; gbl = s_gb[l - 1]; }
-        // the sequential pass stores layer l+1's gradients during this step's exchange; their second factor, a^l, is
-        // requested here, a whole strip ahead of its use
-        v4f ja[PG];
-        float* jgw = nullptr;
-        float* jgb = nullptr;
-        if (inline_bursts) {
-            load_activation_groups(A, l, ja);
-            jgw = A.gw[l - 1];
-            jgb = A.gb[l - 1];
-        }
         const float* W = wptr(l - 1);
         const float* Wn = l > 2 ? wptr(l - 2) : nullptr;
         const int rhi = l + 1 == L ? top_hi : row_hi;
         const unsigned wbytes = l + 1 == L ? top_bytes : block_bytes;
         v4f acc = {0.f, 0.f, 0.f, 0.f};
         if constexpr (SINGLE) {
-            if (Wn) load_chunk(bufB, Wn, 0);
+            // (unconditional, like the refills below: past the last layer it reads an empty buffer.  With a
+            // branch around it there is a path on which bufA's loads are the youngest in flight, and the waits
+            // in front of the multiplications are then set for that path: they would wait for bufB as well,
+            // i.e. for the next step's weights within this step.)
+            load_chunk_of(bufB, Wn ? Wn : W, 0, Wn ? block_bytes : 0u);
             fma_chunk(bufA, 0, acc, gwl, gbl, a4, rhi, wbytes);
         } else {
             // every refill is one unconditional load: past the last layer it reads an empty buffer
@@ -801,7 +801,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
         // exchange: all of delta^l, into the other buffer.  The sequential pass stores its rows of layer l+1's
         // gradients between publishing and gathering, from delta^{l+1} in the buffer the step has just used: the
         // stores fill the time the peers' words are under way.
-        if (inline_bursts) inline_grads(l + 1, jgw, jgb, ja);
+        if (inline_bursts) inline_grads(l + 1);
         else nap(A.nap);
         gather_delta(l);
         __syncthreads();
@@ -818,11 +818,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     } else {
         for (int l = L - 1; l >= 2; --l) step(buf[0], buf[1], l);
     }
-    if (!A.workers && !A.no_grads) {
-        v4f ja[PG];
-        load_activation_groups(A, 1, ja);
-        inline_grads(2, A.gw[0], A.gb[0], ja);
-    }
+    if (!A.workers && !A.no_grads) inline_grads(2);
 }
 
 template <int Q, int RF, bool SINGLE>
