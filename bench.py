@@ -11,6 +11,7 @@ cores.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -229,6 +230,20 @@ class MachineRates:
                 out["stream_" + name] = {
                     "value": moved / (best * 1e-3) / 1e9 if moved > 0 else None, "unit": "GB/s",
                     "what": "plain 128-bit streaming kernel over 1 GiB per buffer, best launch shape of 5, best of 3"}
+            # the single-sample backward pass's own access patterns (N = 4096) as plain kernels
+            probe.probe_strips_beside_rows.restype = ctypes.c_double
+            probe.probe_strips_beside_rows.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                                       ctypes.c_int, ctypes.c_void_p]
+            mats, passes = nbytes // (4096 * 4096 * 4), 62
+            for mode, name in ((0, "strips_read"), (1, "rows_written"), (2, "strips_read_beside_rows_written")):
+                ms = min(probe.probe_strips_beside_rows(mode, src.data_ptr(), dst.data_ptr(), mats, passes,
+                                                        sink.data_ptr()) for _ in range(3))
+                moved = passes * 4096 * 4096 * 4 * (2 if mode == 2 else 1)
+                out[name] = {
+                    "value": moved / (ms * 1e-3) / 1e9 if ms > 0 else None, "unit": "GB/s",
+                    "what": "plain kernels with the N = 4096 backward pass's access patterns (256-byte column strips in "
+                            "four row blocks read by 256 workgroups, rows written by 256 workgroups, 62 matrices each), "
+                            "best of 3"}
         except OSError as ex:
             out["stream_read"] = {"value": None, "what": f"not measured: {str(ex)[:80]}"}
         del src, dst
@@ -469,6 +484,11 @@ def run_config(net, name, args, steps, warmup, rates, P, torch, extras=True):
                 rate = (achievable.get("stream_read_and_write") or {}).get("value") or achievable["value"]
                 floor_ms = work["bwd"] / (rate * 1e9) * 1e3
                 model["floor_what"] = "backward bytes / measured rate of plain kernels reading and writing at once"
+                same = (achievable.get("strips_read_beside_rows_written") or {}).get("value")
+                if same and not small:
+                    # the same bytes at the rate plain kernels with this pass's own access patterns reach side by side
+                    model["floor_same_patterns_ms"] = work["bwd"] / (same * 1e9) * 1e3
+                    model["frac_of_same_patterns_rate"] = achieved / same
             else:
                 rate = (achievable.get("mfma_loop") or {}).get("value") or achievable["value"]
                 floor_ms = work["bwd"] / (rate * 1e12) * 1e3
@@ -477,6 +497,9 @@ def run_config(net, name, args, steps, warmup, rates, P, torch, extras=True):
         bound = max(model["chain_alone_ms"], floor_ms or 0.0)
         model["hidden_bound_ms"] = 1.05 * bound
         model["gradients_hidden_behind_chain"] = bool(model[f"bwd_ms_k{k}"] <= 1.05 * bound) if k > 1 else None
+        if "floor_same_patterns_ms" in model and k > 1:
+            model["within_5_percent_of_same_patterns_floor"] = bool(
+                model[f"bwd_ms_k{k}"] <= 1.05 * max(model["chain_alone_ms"], model["floor_same_patterns_ms"]))
         # restore the full pass's gradients for the parity leg
         g.forward()
         g.backward(k)

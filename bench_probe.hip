@@ -1,4 +1,5 @@
-// Measurement aid for bench.py, not part of the backpropagation library: plain streaming kernels, and a loop of matrix instructions that
+// Measurement aid for bench.py, not part of the backpropagation library: plain streaming kernels, the access patterns of the
+// single-sample backward pass as plain kernels, and a loop of matrix instructions that
 // never leaves the registers, on every compute unit, to show what the matrix cores sustain on this machine
 // at the clock they hold under that load (the published peaks are quoted at the maximum clock).
 #include <hip/hip_runtime.h>
@@ -98,9 +99,76 @@ __global__ __launch_bounds__(kThreads) void k_stream_read_write(const v4f* __res
     }
 }
 
+// The access patterns of the single-sample backward pass at N = 4096, without its arithmetic and exchanges: 256
+// workgroups that read the matrices as column strips of 256 bytes in four row blocks (sixteen 128-bit loads in
+// flight per thread), and 256 workgroups that write matrices row by row with non-temporal 128-bit stores.
+constexpr int kPatternN = 4096;
+__global__ __launch_bounds__(kThreads) void k_strip_read(const float* base, int matrices, int passes, float* sink) {
+    constexpr int N = kPatternN, TPS = 16, RPP = kThreads / TPS, STRIPS = N * 4 / 256;
+    const int RB = gridDim.x / STRIPS, NR = N / RB;        // (not constants: the loop below is then left rolled, the
+    const int strip = blockIdx.x % STRIPS, rb = blockIdx.x / STRIPS;        // faster form by a quarter)
+    const int t = threadIdx.x, c = t % TPS, rs = t / TPS;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    for (int m = 0; m < passes; ++m) {
+        const float* W = base + (size_t)(m % matrices) * N * N + (size_t)(rb * NR + rs) * N + strip * 64 + 4 * c;
+        for (int r = 0; r < NR; r += RPP * 16) {
+            v4f v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = __builtin_nontemporal_load((const v4f*)(W + (size_t)(r + u * RPP) * N));
+#pragma unroll
+            for (int u = 0; u < 16; ++u) acc += v[u];
+        }
+    }
+    if (acc.x + acc.y + acc.z + acc.w == 12345.678f) sink[0] = acc.x;
+}
+__global__ __launch_bounds__(kThreads) void k_row_write(float* base, int matrices, int passes) {
+    constexpr int N = kPatternN;
+    const int t = threadIdx.x, rows = N / gridDim.x;
+    for (int m = 0; m < passes; ++m) {
+        float* G = base + (size_t)(m % matrices) * N * N;
+        for (int row = blockIdx.x * rows; row < (blockIdx.x + 1) * rows; ++row)
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const v4f o = {(float)row, (float)p, 1.f, 2.f};
+                __builtin_nontemporal_store(o, (v4f*)(G + (size_t)row * N + 4 * (t + kThreads * p)));
+            }
+    }
+}
+
 }  // namespace
 
 extern "C" {
+
+// The two pattern kernels above, each on a stream of its own: `passes` matrices of 4096 x 4096 floats read from
+// src (mode 0), written to dst (mode 1), or both side by side (mode 2); each buffer holds `matrices` of them, used
+// in turn.  Synchronous.  Returns the milliseconds from the start of the first to the end of the last kernel, a
+// negative number on a bad argument or a HIP error.
+double probe_strips_beside_rows(int mode, const float* src, float* dst, int matrices, int passes, float* sink) {
+    if (mode < 0 || mode > 2 || matrices < 1 || passes < 1 || !sink || (mode != 1 && !src) || (mode != 0 && !dst)) return -1.0;
+    hipStream_t s1 = nullptr, s2 = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr, e2 = nullptr;
+    double ms = -1.0;
+    if (hipStreamCreate(&s1) == hipSuccess && hipStreamCreate(&s2) == hipSuccess && hipEventCreate(&e0) == hipSuccess &&
+        hipEventCreate(&e1) == hipSuccess && hipEventCreate(&e2) == hipSuccess && hipDeviceSynchronize() == hipSuccess) {
+        (void)hipEventRecord(e0, s1);
+        (void)hipStreamWaitEvent(s2, e0, 0);
+        if (mode != 1) k_strip_read<<<256, kThreads, 0, s1>>>(src, matrices, passes, sink);
+        if (mode != 0) k_row_write<<<256, kThreads, 0, s2>>>(dst, matrices, passes);
+        (void)hipEventRecord(e2, s2);
+        (void)hipStreamWaitEvent(s1, e2, 0);
+        (void)hipEventRecord(e1, s1);
+        float f = 0.0f;
+        if (hipEventSynchronize(e1) == hipSuccess && hipGetLastError() == hipSuccess &&
+            hipEventElapsedTime(&f, e0, e1) == hipSuccess)
+            ms = f;
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (e2) (void)hipEventDestroy(e2);
+    if (s1) (void)hipStreamDestroy(s1);
+    if (s2) (void)hipStreamDestroy(s2);
+    return ms;
+}
 
 // Enqueue one streaming kernel over `bytes` bytes (a multiple of 16) of each buffer it uses.  mode 0: read src;
 // 1: write dst; 2: read src and write dst at once.  groups: workgroups of 256 threads (even for mode 2).
