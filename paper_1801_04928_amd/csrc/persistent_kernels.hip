@@ -599,8 +599,10 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     // k = 1: rows [jrow0, jrow1) of layer's gradients.  (What the store loop needs is requested and awaited here,
     // under the one condition the call stands under: requested at the top of the step, the compiler would see a
     // path from request to the next step without the use, and make every step wait for all loads in flight.)
-    auto inline_grads = [&](int layer) {
-        const int jr1 = min(jrow1, rows_of(A, layer)), jr0 = min(jrow0, jr1);
+    auto inline_grads = [&](int layer, int part) {        // part 2: all rows; 0 / 1: their first / second half
+        const int jr1_all = min(jrow1, rows_of(A, layer)), jr0_all = min(jrow0, jr1_all);
+        const int mid = min(jr1_all, jr0_all + (((jr1_all - jr0_all) / 2 + 3) & ~3));
+        const int jr0 = part == 1 ? mid : jr0_all, jr1 = part == 0 ? mid : jr1_all;
         if (jr0 >= jr1) return;
         v4f ja[PG];
         load_activation_groups(A, layer - 1, ja);
@@ -777,6 +779,9 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
                 const float u = strip_column_sum(s_red, q, e);
                 ll_store(pl + (size_t)(col0 + t) * RS + rb, u, A.epoch);
             }
+            // (the sequential pass stores half of its rows of layer l+1's gradients while the partial sums are
+            // under way, the other half while delta^l is)
+            if (inline_bursts) inline_grads(l + 1, 0);
             if (own) {
                 float p[4];
                 ll_wait4(pl + (size_t)(fcol0 + t) * RS, RS, A.epoch, p, ab, abort_code(0, l, g));
@@ -801,7 +806,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
         // exchange: all of delta^l, into the other buffer.  The sequential pass stores its rows of layer l+1's
         // gradients between publishing and gathering, from delta^{l+1} in the buffer the step has just used: the
         // stores fill the time the peers' words are under way.
-        if (inline_bursts) inline_grads(l + 1);
+        if (inline_bursts) inline_grads(l + 1, SPLIT ? 1 : 2);
         else nap(A.nap);
         gather_delta(l);
         __syncthreads();
@@ -818,7 +823,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     } else {
         for (int l = L - 1; l >= 2; --l) step(buf[0], buf[1], l);
     }
-    if (!A.workers && !A.no_grads) inline_grads(2);
+    if (!A.workers && !A.no_grads) inline_grads(2, 2);
 }
 
 template <int Q, int RF, bool SINGLE>
