@@ -71,3 +71,24 @@ def test_stored_counter_figures_belong_to_the_sources_in_the_tree():
         es = 4 if spec.dtype == "f32" else 2
         assert t >= es * sum(sizes[1:]) + 4 * sum(sizes)
     assert bench.measured_traffic("cfg1", 2) is None and bench.measured_traffic("cfg5", 3) is None
+
+
+def test_the_measurement_aid_exports_what_bench_calls():
+    """libbench_probe.so (built beside the library) carries the three entry points bench.py's machine rates use;
+    called with bad arguments they refuse without touching a device."""
+    import ctypes
+    path = os.path.join(ROOT, "libbench_probe.so")
+    if not os.path.exists(path):
+        pytest.skip("libbench_probe.so is not built")
+    p = ctypes.CDLL(path)
+    for name in ("probe_stream", "probe_mfma_loop", "probe_strips_beside_rows"):
+        assert hasattr(p, name), name
+    p.probe_strips_beside_rows.restype = ctypes.c_double
+    p.probe_strips_beside_rows.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_void_p]
+    assert p.probe_strips_beside_rows(3, None, None, 1, 1, None) < 0        # no such mode
+    assert p.probe_strips_beside_rows(2, None, None, 16, 62, None) < 0      # no buffers
+    p.probe_stream.restype = ctypes.c_double
+    p.probe_stream.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                               ctypes.c_void_p, ctypes.c_void_p]
+    assert p.probe_stream(0, 512, None, None, 1 << 20, None, None) == 0.0
