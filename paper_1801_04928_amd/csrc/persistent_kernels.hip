@@ -191,6 +191,7 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
     __shared__ unsigned s_count;
     __shared__ v4f s_a[Q * 64];
     __shared__ float s_bias[kMaxRowsPerGroup];
+    __shared__ float s_z[kMaxRowsPerGroup];      // w^l a^{l-1} of my rows, until the layer's end
     __shared__ const float* s_w[kTableLds];      // w^l and b^l pointers: a table entry fetched from
     __shared__ const float* s_b[kTableLds];      // memory on the chain would cost a round trip per layer,
                                                  // and a generic load of it would be waited for together
@@ -262,7 +263,10 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
         }
         return missed;
     };
-    // rows ci*RF .. of this wave: dot products with a^{l-1}, bias, sigma, publish
+    // rows ci*RF .. of this wave: dot products with a^{l-1}, then bias, sigma, publish.  With several chunks per
+    // layer the sums are left in LDS and the rest follows at the layer's end, for all rows at once: a store between
+    // two chunks' loads would stand in front of the later loads in the wave's one queue, and the wait for those
+    // loads would also wait for the store to be acknowledged by memory (N = 4096: 875 -> 853 us per pass).
     auto finish_chunk = [&](const v4f (&buf)[RF][Q], int ci, int l) {
         float acc[RF];
         const int nv = cols_of(A, l) >> 2, row_end = min(wrow_end, rows_of(A, l));
@@ -281,16 +285,18 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
                 acc[rr] = fmaf(buf[rr][u].w, a.w, acc[rr]);
             }
         }
-        float* a_out = A.a_base + (size_t)(l - 2) * A.a_stride;
-        u64* pub = A.ALL + (size_t)(l - 2) * A.ll_layer;
 #pragma unroll
         for (int rr = 0; rr < RF; ++rr) {
             const int row = wrow0 + ci * RF + rr;
             const float z = wave_sum(acc[rr]);
-            if (lane == 0 && row < row_end) {
-                const float a = sigmoidf(z + s_bias[row - g * RPG]);
-                if (l < L) ll_store(pub + ll_index(A, row), a, A.epoch);
-                a_out[row] = a;
+            if constexpr (SINGLE) {
+                if (lane == 0 && row < row_end) {
+                    const float a = sigmoidf(z + s_bias[row - g * RPG]);
+                    if (l < L) ll_store(A.ALL + (size_t)(l - 2) * A.ll_layer + ll_index(A, row), a, A.epoch);
+                    A.a_base[(size_t)(l - 2) * A.a_stride + row] = a;
+                }
+            } else {
+                if (lane == 0 && row < row_end) s_z[row - g * RPG] = z;
             }
         }
     };
@@ -322,7 +328,13 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
             }
             if (Wn) load_chunk(bufB, Wn, 1, l + 1);
         }
-        __syncthreads();   // s_a is rewritten by the next layer's gather
+        __syncthreads();   // s_a is rewritten by the next layer's gather; every row's sum is in s_z
+        if (!SINGLE && own_row_of(l)) {
+            const int row = g * RPG + t;
+            const float a = sigmoidf(s_z[t] + s_bias[t]);
+            if (l < L) ll_store(A.ALL + (size_t)(l - 2) * A.ll_layer + ll_index(A, row), a, A.epoch);
+            A.a_base[(size_t)(l - 2) * A.a_stride + row] = a;
+        }
     };
 
     v4f buf0[RF][Q], buf1[RF][Q];
@@ -930,6 +942,13 @@ static persist_kernel_t forward_kernel(const PersistArgs& A) {
 template <int TPR, bool FUSED>
 static persist_kernel_t backward_kernel_tpr(const PersistArgs& A) {
     const int nloads = (A.N + kThreads / TPR - 1) / (kThreads / TPR);
+    // (row-block strips: chunks of eight loads beside gradient workers; chunks of two for the sequential pass, whose
+    // stores then have memory more to themselves -- with eight loads in flight per thread instead of thirty-two
+    // fewer of the next step's reads fall among them: 1.58 against 1.65 ms at L = 64, N = 4096; beside workers the
+    // short chunks lose, 1.76 against 1.67 ms)
+    if constexpr (!FUSED) {
+        if (A.RS > 1 && !A.workers) return k_bwd_persistent<TPR, 2, false, true, false>;
+    }
     if (A.RS > 1) return k_bwd_persistent<TPR, 8, false, true, FUSED>;
     if (nloads <= 4) return k_bwd_persistent<TPR, 4, true, false, FUSED>;
     if (nloads <= 8) return k_bwd_persistent<TPR, 8, true, false, FUSED>;
@@ -971,6 +990,15 @@ hipError_t persistent_resident_per_cu(const PersistArgs& A, int* forward, int* b
     if (e != hipSuccess) return e;
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(backward, kb, kThreads, 0);
     if (e != hipSuccess) return e;
+    // (the grids with and without workers may take different instances: the smaller figure serves both)
+    B.fused = 0;
+    B.workers = A.workers ? 0 : 1;
+    const persist_kernel_t kb2 = backward_kernel(B);
+    if (!kb2) return hipErrorInvalidValue;
+    int other = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&other, kb2, kThreads, 0);
+    if (e != hipSuccess) return e;
+    if (other < *backward) *backward = other;
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(backward_fused, kbf, kThreads, 0);
 }
 
