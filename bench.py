@@ -471,6 +471,13 @@ def run_config(net, name, args, steps, warmup, rates, P, torch, extras=True):
         if k > 1:
             model["bwd_ms_k1"] = time_backward_only(torch, g, 1, reps)[0]
         model[f"bwd_ms_k{k}"] = time_backward_only(torch, g, k, reps)[0]
+        for kk in (s.ks if name else ()):              # the configuration's other worker counts
+            if f"bwd_ms_k{kk}" not in model:
+                model[f"bwd_ms_k{kk}"] = time_backward_only(torch, g, kk, reps)[0]
+        timed = {int(key[8:]): v for key, v in model.items() if key.startswith("bwd_ms_k")}
+        best_k = min(timed, key=timed.get)
+        model["fastest_configured_k"] = {"k": best_k, "bwd_ms": timed[best_k],
+                                         "roofline_frac": work["bwd"] / (timed[best_k] * 1e-3) / work["scale"] / work["peak"]}
         g.set_debug_flags(P.LF_DEBUG_CHAIN_ONLY)
         model["chain_alone_ms"] = time_backward_only(torch, g, k, reps)[0]
         g.set_debug_flags(0)
