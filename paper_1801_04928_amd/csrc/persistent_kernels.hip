@@ -611,25 +611,31 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     // k = 1: rows [jrow0, jrow1) of layer's gradients.  (What the store loop needs is requested and awaited here,
     // under the one condition the call stands under: requested at the top of the step, the compiler would see a
     // path from request to the next step without the use, and make every step wait for all loads in flight.)
-    auto inline_grads = [&](int layer, int part) {        // part 2: all rows; 0 / 1: their first / second half
-        const int jr1_all = min(jrow1, rows_of(A, layer)), jr0_all = min(jrow0, jr1_all);
+    struct InlineInputs { v4f ja[PG]; float* gw; float* gb; };
+    auto inline_request = [&](int layer, InlineInputs& in) {
+        load_activation_groups(A, layer - 1, in.ja);
+        in.gw = A.gw[layer - 2];
+        in.gb = A.gb[layer - 2];
+        arrived(in.ja);
+        arrived(in.gw);
+        arrived(in.gb);
+    };
+    auto inline_store = [&](int layer, int part, const InlineInputs& in) {   // part 2: all rows; 0 / 1: their first /
+        const int jr1_all = min(jrow1, rows_of(A, layer)), jr0_all = min(jrow0, jr1_all);           // second half
         const int mid = min(jr1_all, jr0_all + (((jr1_all - jr0_all) / 2 + 3) & ~3));
         const int jr0 = part == 1 ? mid : jr0_all, jr1 = part == 0 ? mid : jr1_all;
-        if (jr0 >= jr1) return;
-        v4f ja[PG];
-        load_activation_groups(A, layer - 1, ja);
-        float* gw = A.gw[layer - 2];
-        float* gb = A.gb[layer - 2];
-        arrived(ja);
-        arrived(gw);
-        arrived(gb);
         for (int row = jr0; row < jr1; row += 4) {
             const int n = min(4, jr1 - row);
             float d[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) d[c] = delta_cur()[min(row + c, N - 1)];
-            store_gradient_rows(A, layer, gw, gb, row, n, d, ja);
+            store_gradient_rows(A, layer, in.gw, in.gb, row, n, d, in.ja);
         }
+    };
+    auto inline_grads = [&](int layer) {
+        InlineInputs in;
+        inline_request(layer, in);
+        inline_store(layer, 2, in);
     };
     // delta^layer's rows of my row block (float4 groups [gv0, gv1)), from their tagged words, into LDS
     const int gv0 = row_lo >> 2, gv1 = (row_hi + 3) >> 2;
@@ -791,17 +797,27 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
                 const float u = strip_column_sum(s_red, q, e);
                 ll_store(pl + (size_t)(col0 + t) * RS + rb, u, A.epoch);
             }
-            // (the sequential pass stores half of its rows of layer l+1's gradients while the partial sums are
-            // under way, the other half while delta^l is)
-            if (inline_bursts) inline_grads(l + 1, 0);
-            if (own) {
-                float p[4];
-                ll_wait4(pl + (size_t)(fcol0 + t) * RS, RS, A.epoch, p, ab, abort_code(0, l, g));
-                const float u = ((p[0] + p[1]) + p[2]) + p[3];      // slots past RS hold zeros
-                const float d = u * (a_l * (1.0f - a_l));
-                ll_store(A.DLL + (size_t)(l - 2) * A.ll_layer + ll_index(A, fcol0 + t), d, A.epoch);
-                A.d_base[(size_t)(l - 2) * A.d_stride + fcol0 + t] = d;
-                if (l > 2) a_next = load_global_f32_here(act_ptr(A, l - 1) + fcol0 + t);
+            auto finish_my_columns = [&]() {
+                if (own) {
+                    float p[4];
+                    ll_wait4(pl + (size_t)(fcol0 + t) * RS, RS, A.epoch, p, ab, abort_code(0, l, g));
+                    const float u = ((p[0] + p[1]) + p[2]) + p[3];      // slots past RS hold zeros
+                    const float d = u * (a_l * (1.0f - a_l));
+                    ll_store(A.DLL + (size_t)(l - 2) * A.ll_layer + ll_index(A, fcol0 + t), d, A.epoch);
+                    A.d_base[(size_t)(l - 2) * A.d_stride + fcol0 + t] = d;
+                    if (l > 2) a_next = load_global_f32_here(act_ptr(A, l - 1) + fcol0 + t);
+                }
+            };
+            if (inline_bursts) {
+                // the sequential pass stores half of its rows of layer l+1's gradients while the partial sums are
+                // under way, the other half while delta^l is (one request of what the stores need, one branch)
+                InlineInputs in;
+                inline_request(l + 1, in);
+                inline_store(l + 1, 0, in);
+                finish_my_columns();
+                inline_store(l + 1, 1, in);
+            } else {
+                finish_my_columns();
             }
             if constexpr (FUSED) { if (l > 2) a4_next = load_strip_activation(l - 1); }
         } else {
@@ -818,8 +834,10 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
         // exchange: all of delta^l, into the other buffer.  The sequential pass stores its rows of layer l+1's
         // gradients between publishing and gathering, from delta^{l+1} in the buffer the step has just used: the
         // stores fill the time the peers' words are under way.
-        if (inline_bursts) inline_grads(l + 1, SPLIT ? 1 : 2);
-        else nap(A.nap);
+        if constexpr (!SPLIT) {
+            if (inline_bursts) inline_grads(l + 1);
+        }
+        if (!inline_bursts) nap(A.nap);
         gather_delta(l);
         __syncthreads();
         v4f* const was = s_delta4_cur;
@@ -835,7 +853,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     } else {
         for (int l = L - 1; l >= 2; --l) step(buf[0], buf[1], l);
     }
-    if (!A.workers && !A.no_grads) inline_grads(2, 2);
+    if (!A.workers && !A.no_grads) inline_grads(2);
 }
 
 template <int Q, int RF, bool SINGLE>
