@@ -478,6 +478,9 @@ def run_config(net, name, args, steps, warmup, rates, P, torch, extras=True):
         best_k = min(timed, key=timed.get)
         model["fastest_configured_k"] = {"k": best_k, "bwd_ms": timed[best_k],
                                          "roofline_frac": work["bwd"] / (timed[best_k] * 1e-3) / work["scale"] / work["peak"]}
+        # (beside the figures of the timed steps, which run the configuration's largest k)
+        entry["roofline"]["fastest_configured_k"] = dict(model["fastest_configured_k"],
+                                                         what="backward-only passes, mean of %d" % reps)
         g.set_debug_flags(P.LF_DEBUG_CHAIN_ONLY)
         model["chain_alone_ms"] = time_backward_only(torch, g, k, reps)[0]
         g.set_debug_flags(0)
