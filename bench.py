@@ -6,7 +6,9 @@ Prints ONE JSON line.  Without --config the five benchmark configurations run on
 process: the top level of the line is the largest one (configuration 5, bf16 minibatch), and `per_config`
 carries the same figures for each.  The roofline objects price the backward pass against the HBM peak
 (B = 1) or the MFMA peak (minibatch); the cpu_baseline objects are the CPU oracle timed on this machine's
-cores.
+cores.  The timed steps run a configuration's largest worker count k; `cost_model` times the other configured
+worker counts, the chain alone and the sequential pass as well, and the fastest configured k is quoted under
+`roofline.fastest_configured_k`.
 """
 from __future__ import annotations
 
