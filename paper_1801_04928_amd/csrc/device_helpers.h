@@ -42,6 +42,12 @@ __device__ __forceinline__ v4f buffer_load_v4f(__amdgpu_buffer_rsrc_t r, unsigne
     return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, 0));
 }
 
+// The same load marked non-temporal (NT) or not: for data that is read once and is too large to stay in the caches.
+template <bool NT>
+__device__ __forceinline__ v4f buffer_load_v4f_as(__amdgpu_buffer_rsrc_t r, unsigned byte_offset) {
+    return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, NT ? 2 : 0));
+}
+
 // Streaming (non-temporal) 128-bit store through a buffer resource: an offset at or past the buffer's size
 // makes the store a no-op, so rows past the end need no branch.  (aux bit 1 = non-temporal.)
 __device__ __forceinline__ void buffer_store_nt_v4f(__amdgpu_buffer_rsrc_t r, unsigned byte_offset, v4f v) {

@@ -25,6 +25,8 @@ struct PersistArgs {
                                          // loop that multiplies w^{l+1} (a grid without workers)
     int no_grads;                        // 1 = the chain alone: no gradient is formed (a timing aid; a grid
                                          // without workers)
+    int stream_weights;                  // 1 = the weights are too many to stay in the caches from one use to the
+                                         // next: the wide-layer kernel instances read them with non-temporal loads
     float sgd_eta;                       // != 0: the workers apply w -= eta nabla_w, b -= eta nabla_b in place
     unsigned long long* reads_done;      // [L-1][kMaxGroups] tagged words, row l-2: chain workgroup g has
                                          // finished reading w^l (written only while the descent step is on)

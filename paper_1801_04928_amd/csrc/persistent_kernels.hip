@@ -186,7 +186,10 @@ __device__ __forceinline__ int rows_of(const PersistArgs& A, int l) {
 // flight, also across the exchange between two layers.
 // SINGLE: the wave's rows of a layer are one chunk (the latency-bound small nets); otherwise an even
 // number of chunks per layer.
-template <int Q, int RF, bool SINGLE>
+// NT: the weights are read with non-temporal loads (nets whose weights cannot stay in the caches between passes:
+// every entry is read once per pass, by one workgroup; measured at L = 64, N = 4096: forward 850 -> 790 us, backward
+// 1.67 -> 1.64 ms -- and 108 -> 169 us backward at L = 32, N = 1024, whose 130 MB of weights do stay).
+template <int Q, int RF, bool SINGLE, bool NT>
 __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
     __shared__ unsigned s_count;
     __shared__ v4f s_a[Q * 64];
@@ -220,7 +223,7 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
             const int row = min(wrow0 + ci * RF + rr, last_row);
             const __amdgpu_buffer_rsrc_t r = make_buffer(W + (size_t)row * cols, (unsigned)cols * 4u);
 #pragma unroll
-            for (int u = 0; u < Q; ++u) buf[rr][u] = buffer_load_v4f(r, (unsigned)(lane + 64 * u) * 16u);
+            for (int u = 0; u < Q; ++u) buf[rr][u] = buffer_load_v4f_as<NT>(r, (unsigned)(lane + 64 * u) * 16u);
         }
     };
 
@@ -535,7 +538,7 @@ __device__ __forceinline__ float strip_column_sum(const v4f (&red)[kWaves * 4][T
 // the column sums of delta^l also forms and stores the same entry of nabla_w^{l+1} = delta^{l+1} (a^l)^T,
 // inside the same chunk loop (delta^{l+1} is in LDS for the product anyway, the four a^l values of the
 // thread's columns sit in registers).  Layer 2, whose weights the chain never reads, is stored at the end.
-template <int TPR, int CH, bool SINGLE, bool SPLIT, bool FUSED>
+template <int TPR, int CH, bool SINGLE, bool SPLIT, bool FUSED, bool NT>
 __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     constexpr int CPG = 4 * TPR;              // columns per chain workgroup
     constexpr int RPP = kThreads / TPR;       // rows covered by one load of the whole workgroup
@@ -602,7 +605,7 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
         const __amdgpu_buffer_rsrc_t r = make_buffer(reinterpret_cast<const char*>(W) + skip,
                                                      bytes > skip ? bytes - skip : 0u);
 #pragma unroll
-        for (int u = 0; u < CH; ++u) buf[u] = buffer_load_v4f(r, strip_offset + (unsigned)u * pass_bytes);
+        for (int u = 0; u < CH; ++u) buf[u] = buffer_load_v4f_as<NT>(r, strip_offset + (unsigned)u * pass_bytes);
     };
     auto load_chunk = [&](v4f (&buf)[CH], const float* W, int ci) { load_chunk_of(buf, W, ci, block_bytes); };
     // w^L may have fewer rows than N: my row block of it ends where the matrix does
@@ -856,18 +859,19 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     if (!A.workers && !A.no_grads) inline_grads(2);
 }
 
-template <int Q, int RF, bool SINGLE>
+template <int Q, int RF, bool SINGLE, bool NT = false>
 __global__ __launch_bounds__(kThreads, 2) void k_fwd_persistent(const PersistArgs args) {
-    forward_pass<Q, RF, SINGLE>(args);
+    forward_pass<Q, RF, SINGLE, NT>(args);
 }
 // The backward kernel runs with two grids: chain workgroups only (k = 1 without the descent step, the on-chain
 // fusion, the chain alone), or chain + gradient workers.  Each grid has its own launch counts and its own
 // tags (see persistent_epoch.h), so the words of one can never pass for the other's.
 // (The fused grid has no worker workgroups to share a compute unit with: one wave per SIMD, hence twice the
 // registers, which the extra stores of its multi-chunk loops need.)
-template <int TPR, int CH, bool SINGLE, bool SPLIT, bool FUSED>
+template <int TPR, int CH, bool SINGLE, bool SPLIT, bool FUSED, bool NT = false>
 __global__ __launch_bounds__(kThreads, FUSED ? 1 : 2) void k_bwd_persistent(const PersistArgs args) {
-    backward_pass<TPR, CH, SINGLE, SPLIT, FUSED>(args);
+    static_assert(!NT || SPLIT, "non-temporal weight loads are instantiated for the wide-layer instances only");
+    backward_pass<TPR, CH, SINGLE, SPLIT, FUSED, NT>(args);
 }
 
 __global__ __launch_bounds__(kThreads) void k_fill_u64(u64* p, size_t n, u64 v) {
@@ -951,8 +955,8 @@ static persist_kernel_t forward_kernel(const PersistArgs& A) {
         return k_fwd_persistent<8, 2, false>;
     }
     if (q <= 16) {
-        if (rw == 1) return k_fwd_persistent<16, 1, true>;
-        return k_fwd_persistent<16, 1, false>;
+        if (rw == 1) return A.stream_weights ? k_fwd_persistent<16, 1, true, true> : k_fwd_persistent<16, 1, true>;
+        return A.stream_weights ? k_fwd_persistent<16, 1, false, true> : k_fwd_persistent<16, 1, false>;
     }
     return nullptr;
 }
@@ -965,9 +969,13 @@ static persist_kernel_t backward_kernel_tpr(const PersistArgs& A) {
     // fewer of the next step's reads fall among them: 1.58 against 1.65 ms at L = 64, N = 4096; beside workers the
     // short chunks lose, 1.76 against 1.67 ms)
     if constexpr (!FUSED) {
-        if (A.RS > 1 && !A.workers) return k_bwd_persistent<TPR, 2, false, true, false>;
+        if (A.RS > 1 && !A.workers)
+            return A.stream_weights ? k_bwd_persistent<TPR, 2, false, true, false, true>
+                                    : k_bwd_persistent<TPR, 2, false, true, false>;
     }
-    if (A.RS > 1) return k_bwd_persistent<TPR, 8, false, true, FUSED>;
+    if (A.RS > 1)
+        return A.stream_weights ? k_bwd_persistent<TPR, 8, false, true, FUSED, true>
+                                : k_bwd_persistent<TPR, 8, false, true, FUSED>;
     if (nloads <= 4) return k_bwd_persistent<TPR, 4, true, false, FUSED>;
     if (nloads <= 8) return k_bwd_persistent<TPR, 8, true, false, FUSED>;
     return k_bwd_persistent<TPR, 8, false, false, FUSED>;

@@ -221,6 +221,33 @@ def test_persistent_row_split_strips_match_oracle(monkeypatch, L, N, k, split):
     _free(g)
 
 
+@pytest.mark.parametrize("L,N,k,split", [
+    (5, 3076, 2, 4),      # ragged strips and row blocks, with workers
+    (4, 4096, 1, 4),      # the sequential pass
+    (4, 2052, 3, 2),      # a forced row split below the width that takes it by default
+])
+def test_persistent_wide_layer_instances_with_streamed_weights(monkeypatch, L, N, k, split):
+    """The wide-layer instances that read the weights with non-temporal loads (taken by default only by nets whose
+    weights are far larger than the cache), forced on small nets: the oracle's numbers, and the same bits as the
+    instances with ordinary loads -- how a load is cached changes no value."""
+    import torch
+    import paper_1801_04928_amd as P
+    monkeypatch.setenv("LF_PERSISTENT_ROW_SPLIT", str(split))
+    net = make_net(L, N, 1, seed=N + 7 * split)
+    bits = []
+    for stream in ("1", "0"):
+        monkeypatch.setenv("LF_PERSISTENT_STREAM_WEIGHTS", stream)
+        g = run_gpu(net, k, sched=P.LF_SCHED_PERSISTENT)
+        if stream == "1":
+            rep = check_against_oracle(net, g)
+            log(f"streamed weights: L={L} N={N} k={k} split {split}: worst {rep['worst']:.2e}")
+        bits.append([to_np(t).copy().view(np.uint32) for t in g.nabla_w + g.nabla_b] +
+                    [to_np(g.activation(l)).copy().view(np.uint32) for l in range(2, L + 1)])
+        _free(g)
+    for a, b in zip(*bits):
+        assert np.array_equal(a, b)
+
+
 @pytest.mark.parametrize("L,N,k,groups", [(5, 1024, 2, 16), (4, 2048, 3, 32), (6, 520, 1, 8), (4, 1000, 2, 4)])
 def test_persistent_with_few_workgroups(monkeypatch, L, N, k, groups):
     """The launch shapes a device with few compute units would get (many rows per forward workgroup, several
