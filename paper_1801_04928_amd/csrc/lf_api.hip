@@ -191,7 +191,7 @@ struct lf_net {
     bool p_ready, p_tables_dirty;
     bool p_failed_over;                // LF_SCHED_AUTO: a persistent wait gave up; the handle has moved to streams
     bool p_fused_ok;                   // the fused backward kernel's workgroups all fit the device at once
-    int p_groups, p_rpg, p_bgroups, p_tpr, p_rs, p_workers, p_nap_fwd, p_nap_bwd;
+    int p_groups, p_rpg, p_bgroups, p_tpr, p_rs, p_workers, p_spread, p_nap_fwd, p_nap_bwd;
     unsigned p_spin_limit;             // polls before a bounded wait gives up
     int* p_abort_host;                 // pinned, mapped; the kernels raise it when a wait gives up
     int* p_abort_dev_view;             // the same word as the device addresses it
@@ -328,6 +328,10 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
             if (w >= 1 && w <= 2 * lf::kMaxGroups) net->p_workers = w;
         }
         if (net->p_workers > net->N) net->p_workers = net->N;
+        // LF_PERSISTENT_SPREAD=0: worker partitions by workgroup index mod k for every k (a tuning knob; the
+        // default gives every partition members on all XCDs when k is a multiple of 4)
+        const char* envsp = std::getenv("LF_PERSISTENT_SPREAD");
+        net->p_spread = (envsp && envsp[0] == '0') ? 0 : 1;
         // LF_PERSISTENT_NAP_FWD / _BWD: pause before the first poll of an exchange, units of 256 cycles
         const char* envnf = std::getenv("LF_PERSISTENT_NAP_FWD");
         const char* envnb = std::getenv("LF_PERSISTENT_NAP_BWD");
@@ -405,6 +409,7 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     A.k = k < net->p_workers ? k : net->p_workers;   // never more partitions than worker workgroups
     A.sgd_eta = net->sgd_eta;
     A.stream_weights = weights_exceed_cache(net) ? 1 : 0;
+    A.spread = net->p_spread;
     A.fused = net->sched == LF_SCHED_FUSED ? 1 : 0;
     A.no_grads = (net->debug_flags & LF_DEBUG_CHAIN_ONLY) ? 1 : 0;
     A.workers = ((A.k > 1 || A.sgd_eta != 0.0f) && !A.fused && !A.no_grads) ? 1 : 0;
