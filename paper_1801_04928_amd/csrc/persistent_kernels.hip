@@ -34,6 +34,7 @@
 #include "lf_internal.h"
 #include "persistent.h"
 #include "persistent_epoch.h"
+#include "persistent_partition.h"
 
 namespace lf {
 namespace {
@@ -463,19 +464,10 @@ __device__ __forceinline__ void gradient_worker(PersistArgs& A, unsigned* s_coun
     __shared__ float s_wd[kThreads];
     __shared__ int s_wdead;
     const int N = A.N, L = A.L, k = A.k, t = threadIdx.x;
-    // Workgroups are dealt to the 8 XCDs round-robin, so partition = index mod k confines a partition to
-    // 8 / gcd(k, 8) of the XCDs -- to one, for k = 8 -- and a layer's stores to those XCDs' ports.  When k is a
-    // multiple of 4 the partition is therefore taken from the index / 8 instead, and a partition's members are
-    // numbered XCD by XCD within each run of 8k workgroups: every partition then has members on every XCD,
-    // and neighbouring blocks of rows still leave through different XCDs.
-    // (L = 64, N = 4096: 1.64 -> 1.53 ms at k = 8, 1.56 -> 1.51 ms at k = 4.  k = 2, whose partitions have four
-    // XCDs each anyway, is faster as it is.)
-    int v = wid;
-    if (A.spread && k % 4 == 0 && nworkers % 8 == 0 && (nworkers / 8) % k == 0)
-        v = (((wid / 8) / k) * 8 + wid % 8) * k + (wid / 8) % k;
-    const int part = v % k, member = v / k, members = (nworkers - part + k - 1) / k;
-    const int RM = (N + members - 1) / members;
-    const int jb = min(N, member * RM), je = min(N, jb + RM);
+    const int v = worker_slot(wid, nworkers, k, A.spread != 0);
+    const int part = v % k, member = v / k, members = partition_members(part, nworkers, k);
+    int jb, je;
+    member_rows(member, members, N, &jb, &je);
     if (t == 0) s_wdead = 0;
     __syncthreads();
     A.epoch = backward_epoch(*s_count, true);
@@ -617,7 +609,6 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
 #pragma unroll
         for (int u = 0; u < CH; ++u) buf[u] = buffer_load_v4f_as<NT>(r, strip_offset + (unsigned)u * pass_bytes);
     };
-    auto load_chunk = [&](v4f (&buf)[CH], const float* W, int ci) { load_chunk_of(buf, W, ci, block_bytes); };
     // w^L may have fewer rows than N: my row block of it ends where the matrix does
     const int top_hi = min(row_hi, A.n_out);
     const unsigned top_bytes = (unsigned)top_hi * (unsigned)N * 4u;
