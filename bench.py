@@ -70,7 +70,7 @@ def measured_traffic(cfg_name, k):
         if "source_sha256" in e:          # a minibatch pass: the sum over its kernels, hashed with their sources
             if e["source_sha256"] != source_hash(e["sources"]):
                 return None
-        elif rec.get("kernel_source_sha256") != source_hash(("persistent_kernels.hip", "persistent.h", "device_helpers.h")):
+        elif rec.get("kernel_source_sha256") != source_hash(("persistent_kernels.hip", "persistent.h", "persistent_partition.h", "device_helpers.h")):
             return None
         return e["fetch_bytes"] + e["write_bytes"]
     except Exception:

@@ -32,7 +32,7 @@ def counter(path, name):
     return d
 
 
-PERSISTENT_SOURCES = ("persistent_kernels.hip", "persistent.h", "device_helpers.h")
+PERSISTENT_SOURCES = ("persistent_kernels.hip", "persistent.h", "persistent_partition.h", "device_helpers.h")
 MINIBATCH_SOURCES = ("batched_kernels.hip", "b1_kernels.hip", "lf_internal.h", "device_helpers.h")
 
 
