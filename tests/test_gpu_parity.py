@@ -283,23 +283,30 @@ def test_persistent_exchange_layout_and_pause_knobs(monkeypatch, stride, nap):
 
 
 @pytest.mark.parametrize("L,N,k", [(11, 1000, 8), (7, 2052, 4), (19, 516, 16)])
-def test_persistent_worker_partition_layout_changes_no_bits(monkeypatch, L, N, k):
+def test_persistent_worker_partition_layout_and_pacing_change_no_bits(monkeypatch, L, N, k):
     """Which workgroups make up a worker partition (all XCDs for k a multiple of 4, or workgroup index mod k)
-    decides only who stores which rows of nabla_w^l: the oracle's numbers and the same bits either way."""
+    decides only who stores which rows of nabla_w^l, and pacing only when: the oracle's numbers and the same bits
+    every way."""
     import paper_1801_04928_amd as P
     net = make_net(L, N, 1, seed=N + k)
     g = run_gpu(net, k, sched=P.LF_SCHED_PERSISTENT)
     rep = check_against_oracle(net, g)
     want = [to_np(t).copy() for t in g.nabla_w] + [to_np(t).copy() for t in g.nabla_b]
     _free(g)
-    monkeypatch.setenv("LF_PERSISTENT_SPREAD", "0")
-    g = run_gpu(net, k, sched=P.LF_SCHED_PERSISTENT)
-    check_against_oracle(net, g)
-    got = [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]
-    for a, b in zip(want, got):
-        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
-    log(f"partition layouts: L={L} N={N} k={k}: worst {rep['worst']:.2e}")
-    _free(g)
+    # the other layout; then the default layout with the stores paced by the chain's steps (the default only for
+    # nets too large for the cache): k bursts per layer, and three
+    for env in ({"LF_PERSISTENT_SPREAD": "0"}, {"LF_PERSISTENT_PACE": str(k)}, {"LF_PERSISTENT_PACE": "3"}):
+        for name, value in env.items():
+            monkeypatch.setenv(name, value)
+        g = run_gpu(net, k, sched=P.LF_SCHED_PERSISTENT)
+        check_against_oracle(net, g)
+        got = [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]
+        for a, b in zip(want, got):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+        _free(g)
+        for name in env:
+            monkeypatch.delenv(name)
+    log(f"partition layouts and pacing: L={L} N={N} k={k}: worst {rep['worst']:.2e}")
 
 
 def test_persistent_pass_replays_from_a_hip_graph():
