@@ -597,17 +597,20 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     // strips of workgroups on one XCD (workgroups are dealt to the 8 XCDs round-robin) are adjacent,
     // and the workgroups that share a strip sit on one XCD (half-line strips share their lines through that L2)
     const int RS = SPLIT ? A.RS : 1;
-    int strip = g, rb = 0;
-    if (SPLIT && A.strip_map == 1 && (GB / RS) % 8 == 0) {
-        // Whole-line strips in a grid without workers: strips dealt to the XCDs one by one (strip mod 8), the row
-        // blocks of a strip still on one XCD.  The chain alone then reads 5 % faster at N = 4096 (0.886 -> 0.841 ms
-        // at L = 64) and the sequential pass is 2.6 % faster; beside worker workgroups it is 2.8 % slower.
-        strip = g % (GB / RS);
-        rb = g / (GB / RS);
-    } else if (GB % (8 * RS) == 0) {
-        const int j = g / 8;
+    // Whole-line strips in a grid without workers (strip_map = 1): strips dealt to the XCDs one by one (strip mod 8),
+    // the row blocks of a strip still on one XCD.  The chain alone then reads 5 % faster at N = 4096 (0.886 -> 0.841 ms
+    // at L = 64) and the sequential pass is 2.6 % faster; beside worker workgroups it is 2.8 % slower.  (Done by
+    // renumbering the workgroup in front of the one formula below.)
+    int gm = g;
+    if (SPLIT && A.strip_map == 1 && GB % (8 * RS) == 0) {
+        const int S = GB / RS, s8 = S / 8, st = g % S;
+        gm = 8 * ((st % s8) * RS + g / S) + st / s8;
+    }
+    int strip = gm, rb = 0;
+    if (GB % (8 * RS) == 0) {
+        const int j = gm / 8;
         rb = j % RS;
-        strip = (g % 8) * (GB / (8 * RS)) + j / RS;
+        strip = (gm % 8) * (GB / (8 * RS)) + j / RS;
     } else if constexpr (SPLIT) {
         rb = g % RS;
         strip = g / RS;
