@@ -200,8 +200,14 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
     __shared__ const float* s_b[kTableLds];      // memory on the chain would cost a round trip per layer,
                                                  // and a generic load of it would be waited for together
                                                  // with every weight load in flight
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, g = blockIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     PersistArgs A = args;
+    int g = blockIdx.x;
+    // Nets read from memory (fwd_band): the row blocks are numbered XCD by XCD, so that an XCD (workgroups are dealt
+    // to the 8 XCDs round-robin) owns a contiguous eighth of the rows of w^l instead of every eighth block
+    // (L = 64, N = 4096: 786 -> 757 us; runs of 4, 8 or 16 blocks per XCD: 768-772 us, of 2: 829 us).  Nets in the
+    // cache are slower that way (L = 32, N = 1024: 66 -> 70 us).  g is the row block from here on.
+    if (A.fwd_band && A.G % 8 == 0) g = (g % 8) * (A.G / 8) + g / 8;
     const int N = A.N, L = A.L, RPG = A.RPG, nvec = N >> 2;
     take_launch_count(A.counts_fwd, &s_count);
     for (int i = t; i < L - 1; i += kThreads) { s_w[i] = A.w[i]; s_b[i] = A.b[i]; }
@@ -245,7 +251,7 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
         if (nvec <= kThreads) {
             if (t < nvec) {
                 float o[4];
-                missed = ll_wait4(src + ll_index(A, 4 * t), 4, A.epoch, o, ab, abort_code(1, l, g));
+                missed = ll_wait4(src + ll_index(A, 4 * t), 4, A.epoch, o, ab, abort_code(1, l, (int)blockIdx.x));
                 s_a[t] = v4f{o[0], o[1], o[2], o[3]};
             }
             return missed;
@@ -260,7 +266,7 @@ __device__ __forceinline__ void forward_pass(const PersistArgs& args) {
                 gp[i] = src + ll_index(A, 4 * min(v, nvec - 1));
             }
             float o[4][4];
-            missed |= ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(1, l, g));
+            missed |= ll_gather4x4(gp, gn, A.epoch, o, ab, abort_code(1, l, (int)blockIdx.x));
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 if (gn[i]) s_a[v0 + i * kThreads] = v4f{o[i][0], o[i][1], o[i][2], o[i][3]};

@@ -292,15 +292,19 @@ def test_persistent_worker_partition_layout_and_pacing_change_no_bits(monkeypatc
     g = run_gpu(net, k, sched=P.LF_SCHED_PERSISTENT)
     rep = check_against_oracle(net, g)
     want = [to_np(t).copy() for t in g.nabla_w] + [to_np(t).copy() for t in g.nabla_b]
+    want += [to_np(g.activation(l)).copy() for l in range(2, L + 1)]
     _free(g)
     # the other layout; then the default layout with the stores paced by the chain's steps (the default only for
     # nets too large for the cache): k bursts per layer, and three
-    for env in ({"LF_PERSISTENT_SPREAD": "0"}, {"LF_PERSISTENT_PACE": str(k)}, {"LF_PERSISTENT_PACE": "3"}):
+    # ... and the forward kernel's other dealing of row blocks to XCDs (the default only for nets read from memory)
+    for env in ({"LF_PERSISTENT_SPREAD": "0"}, {"LF_PERSISTENT_PACE": str(k)}, {"LF_PERSISTENT_PACE": "3"},
+                {"LF_PERSISTENT_FWD_BAND": "1"}):
         for name, value in env.items():
             monkeypatch.setenv(name, value)
         g = run_gpu(net, k, sched=P.LF_SCHED_PERSISTENT)
         check_against_oracle(net, g)
         got = [to_np(t) for t in g.nabla_w] + [to_np(t) for t in g.nabla_b]
+        got += [to_np(g.activation(l)) for l in range(2, L + 1)]
         for a, b in zip(want, got):
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
         _free(g)
