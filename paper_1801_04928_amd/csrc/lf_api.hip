@@ -191,7 +191,7 @@ struct lf_net {
     bool p_ready, p_tables_dirty;
     bool p_failed_over;                // LF_SCHED_AUTO: a persistent wait gave up; the handle has moved to streams
     bool p_fused_ok;                   // the fused backward kernel's workgroups all fit the device at once
-    int p_groups, p_rpg, p_bgroups, p_tpr, p_rs, p_workers, p_spread, p_pace, p_strip_map, p_fwd_band, p_nap_fwd, p_nap_bwd;
+    int p_groups, p_rpg, p_bgroups, p_tpr, p_rs, p_workers, p_spread, p_pace, p_strip_run, p_fwd_band, p_nap_fwd, p_nap_bwd;
     unsigned p_spin_limit;             // polls before a bounded wait gives up
     int* p_abort_host;                 // pinned, mapped; the kernels raise it when a wait gives up
     int* p_abort_dev_view;             // the same word as the device addresses it
@@ -336,8 +336,9 @@ lf_status prepare_persistent(lf_net* net, hipStream_t s) {
         // at most k; default k for nets whose weights exceed the cache, else 0)
         const char* envfb = std::getenv("LF_PERSISTENT_FWD_BAND");
         net->p_fwd_band = envfb ? (envfb[0] == '1' ? 1 : 0) : -1;
-        const char* envm = std::getenv("LF_PERSISTENT_STRIP_MAP");
-        net->p_strip_map = envm ? (envm[0] == '1' ? 1 : 0) : -1;
+        const char* envm = std::getenv("LF_PERSISTENT_STRIP_RUN");
+        net->p_strip_run = envm ? std::atoi(envm) : 0;
+        if (net->p_strip_run < 0 || net->p_strip_run > 64) net->p_strip_run = 0;
         const char* envp = std::getenv("LF_PERSISTENT_PACE");
         net->p_pace = envp ? std::atoi(envp) : -1;
         if (net->p_pace < -1) net->p_pace = -1;
@@ -426,9 +427,9 @@ lf::PersistArgs persist_args(lf_net* net, const void* y, int k) {
     A.pace = net->p_pace >= 0 ? net->p_pace : (A.stream_weights ? A.k : 0);
     if (A.pace > A.k) A.pace = A.k;                          // a partition's next layer comes k steps later
     if (!A.workers || A.sgd_eta != 0.0f) A.pace = 0;
-    // (LF_PERSISTENT_FWD_BAND=0/1 and LF_PERSISTENT_STRIP_MAP=0/1 override, tuning knobs)
+    // (LF_PERSISTENT_FWD_BAND=0/1 and LF_PERSISTENT_STRIP_RUN=1/2/4/8 override, tuning knobs)
     A.fwd_band = net->p_fwd_band >= 0 ? net->p_fwd_band : A.stream_weights;
-    A.strip_map = net->p_strip_map >= 0 ? net->p_strip_map : (A.workers ? 0 : 1);
+    A.strip_run = net->p_strip_run > 0 ? net->p_strip_run : 2;
     A.reads_done = reinterpret_cast<unsigned long long*>(net->ws + net->lay.reads_off);
     A.epoch = 0;                                            // set by the kernel
     A.counts_fwd = reinterpret_cast<unsigned*>(net->ws + net->lay.counts_off);

@@ -29,7 +29,7 @@ struct PersistArgs {
                                          // next: the wide-layer kernel instances read them with non-temporal loads
     int spread;                          // 1 = worker partitions span all XCDs when k is a multiple of 4 (see gradient_worker)
     int pace;                            // > 1: a worker stores a layer's rows in this many bursts, one per chain step
-    int strip_map;                       // row-block strips: 0 = an XCD's strips adjacent, 1 = strips dealt to the XCDs one by one
+    int strip_run;                       // row-block strips: an XCD takes runs of this many adjacent strips (0: all of its strips adjacent)
     int fwd_band;                        // 1 = forward: an XCD owns a contiguous eighth of the rows (see forward_pass)
     float sgd_eta;                       // != 0: the workers apply w -= eta nabla_w, b -= eta nabla_b in place
     unsigned long long* reads_done;      // [L-1][kMaxGroups] tagged words, row l-2: chain workgroup g has

@@ -600,17 +600,19 @@ __device__ __forceinline__ void backward_pass(const PersistArgs& args) {
     __syncthreads();
     A.epoch = backward_epoch(s_count, A.workers != 0);
     auto wptr = [&](int i) { return s_w[i]; };
-    // strips of workgroups on one XCD (workgroups are dealt to the 8 XCDs round-robin) are adjacent,
-    // and the workgroups that share a strip sit on one XCD (half-line strips share their lines through that L2)
+    // Strips narrower than a line: strips of workgroups on one XCD (workgroups are dealt to the 8 XCDs round-robin)
+    // are adjacent, so that they share their lines through that XCD's L2.
     const int RS = SPLIT ? A.RS : 1;
-    // Whole-line strips in a grid without workers (strip_map = 1): strips dealt to the XCDs one by one (strip mod 8),
-    // the row blocks of a strip still on one XCD.  The chain alone then reads 5 % faster at N = 4096 (0.886 -> 0.841 ms
-    // at L = 64) and the sequential pass is 2.6 % faster; beside worker workgroups it is 2.8 % slower.  (Done by
-    // renumbering the workgroup in front of the one formula below.)
+    // Row-block strips (whole lines): an XCD takes runs of strip_run adjacent strips, the row blocks of a strip still
+    // on one XCD.  Runs of two (512 bytes of every row) are fastest in every kind of grid at N = 4096, L = 64: with
+    // workers 1.461 ms at k = 8 against 1.470, 1.478, 1.493 for runs of 4, 8 (an XCD's strips all adjacent) and 1;
+    // the sequential pass 1.473 against 1.508, 1.537, 1.501.  (Done by renumbering the workgroup in front of the one
+    // formula below: as a second formula beside it, it cost grids that never took it 2 %.)
     int gm = g;
-    if (SPLIT && A.strip_map == 1 && GB % (8 * RS) == 0) {
-        const int S = GB / RS, s8 = S / 8, st = g % S;
-        gm = 8 * ((st % s8) * RS + g / S) + st / s8;
+    if (SPLIT && A.strip_run > 0 && GB % (8 * RS) == 0 && ((GB / RS) / 8) % A.strip_run == 0) {
+        const int S = GB / RS, s8 = S / 8, c = A.strip_run, j0 = g / 8, x = g % 8, i = j0 / RS, rb0 = j0 % RS;
+        const int target = ((i / c) * 8 + x) * c + i % c;
+        gm = 8 * ((target % s8) * RS + rb0) + target / s8;
     }
     int strip = gm, rb = 0;
     if (GB % (8 * RS) == 0) {

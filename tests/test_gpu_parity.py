@@ -296,9 +296,10 @@ def test_persistent_worker_partition_layout_and_pacing_change_no_bits(monkeypatc
     _free(g)
     # the other layout; then the default layout with the stores paced by the chain's steps (the default only for
     # nets too large for the cache): k bursts per layer, and three
-    # ... and the forward kernel's other dealing of row blocks to XCDs (the default only for nets read from memory)
+    # ... the forward kernel's other dealing of row blocks to XCDs (the default only for nets read from memory), and
+    # other dealings of the chain's strips (wide layers only)
     for env in ({"LF_PERSISTENT_SPREAD": "0"}, {"LF_PERSISTENT_PACE": str(k)}, {"LF_PERSISTENT_PACE": "3"},
-                {"LF_PERSISTENT_FWD_BAND": "1"}):
+                {"LF_PERSISTENT_FWD_BAND": "1"}, {"LF_PERSISTENT_STRIP_RUN": "8"}, {"LF_PERSISTENT_STRIP_RUN": "1"}):
         for name, value in env.items():
             monkeypatch.setenv(name, value)
         g = run_gpu(net, k, sched=P.LF_SCHED_PERSISTENT)
